@@ -1,0 +1,98 @@
+/*
+ * deltanet.h - C ABI of the MI355X (gfx950) chunkwise-parallel DeltaNet layer.
+ *
+ * The operation is the DeltaNet token mixer of "Parallelizing Linear Transformers with the Delta
+ * Rule over Sequence Length": per (sequence, head) chain, with a state S in R^{d_k x d_v},
+ *
+ *     S_t = S_{t-1} + beta_t k_t (v_t - S_{t-1}^T k_t)^T ,   o_t = S_t^T q_t
+ *
+ * (section 2.2, the delta update rule and read-out; section 3.1 writes the same update as a
+ * generalized Householder transition S_{t-1}(I - beta k k^T) + beta v k^T; the state is kept in the
+ * orientation of the paper's pseudocode listing, d_k rows by d_v columns).  It is evaluated in the
+ * chunkwise-parallel form of section 3.2 (Eq. 8-9: inter-chunk state carry plus causal intra-chunk
+ * output) with the per-chunk WY factors W, U built by the UT transform (Eq. 10-11).  No scale
+ * factor is applied to q; normalising q, k and squashing beta are the caller's job.
+ *
+ * Conventions common to every call
+ *  - All data pointers are DEVICE pointers unless a name ends in _host.  The caller owns every
+ *    buffer; the library never allocates, frees or synchronises.  All work is enqueued on
+ *    `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Dense layout: q,k [B,L,H,d_k]; v,o,do [B,L,H,d_v]; beta [B,L,H]; states [B,H,d_k,d_v].
+ *    Packed layout (cu_seqlens != NULL): B must be 1, L is the total token count, sequence n
+ *    covers rows cu_seqlens[n] .. cu_seqlens[n+1]-1, the state is reset at every sequence start and
+ *    states are [num_seqs,H,d_k,d_v].  All tensors are contiguous and row-major.
+ *  - q,k,v,beta,o,do,dq,dk,dv have element type `dtype` (fp32, or bf16 with fp32 accumulation);
+ *    states, state gradients and dbeta are always fp32.
+ *  - Every data pointer must be 16-byte aligned.
+ *  - `workspace` is caller-provided device scratch of at least deltanet_workspace_bytes();
+ *    its contents are undefined afterwards.
+ *  - Return value: DN_OK (0) or a negative dn_status.  All validation happens before the first
+ *    launch; on a validation error nothing has been enqueued.  No exceptions, no abort.
+ *  - Sequences of length 0 are allowed in the packed layout; lengths need not be multiples of
+ *    the chunk size (a ragged last chunk is handled exactly, as beta = 0 leaves the state
+ *    unchanged, section 2.2).
+ */
+#ifndef DELTANET_H_
+#define DELTANET_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DN_F32 = 0, DN_BF16 = 1 } dn_dtype;
+
+typedef enum {
+    DN_OK = 0,
+    DN_ERR_NULL = -1,        /* a required pointer is NULL */
+    DN_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent */
+    DN_ERR_UNSUPPORTED = -3, /* (dtype, d_k, d_v, chunk) has no compiled kernel */
+    DN_ERR_ALIGN = -4,       /* a data pointer is not 16-byte aligned */
+    DN_ERR_WORKSPACE = -5,   /* workspace is NULL or too small */
+    DN_ERR_CUSEQLENS = -6,   /* cu_seqlens_host is not 0 = c[0] <= c[1] <= ... <= c[N] = L */
+    DN_ERR_LAUNCH = -7       /* the HIP runtime reported an error at launch */
+} dn_status;
+
+typedef struct {
+    int32_t B, L, H, d_k, d_v;
+    int32_t chunk;                   /* C of section 3.2; 64 is the compiled value */
+    int32_t dtype;                   /* dn_dtype */
+    int32_t num_seqs;                /* packed layout only: N */
+    const int32_t *cu_seqlens;       /* DEVICE int32 [N+1], or NULL for the dense layout */
+    const int32_t *cu_seqlens_host;  /* optional HOST copy of the same array; if given it is
+                                        validated (DN_ERR_CUSEQLENS) and never dereferenced later */
+} dn_shape;
+
+/* Bytes of device scratch that deltanet_fwd (want_bwd = 0) or deltanet_bwd (want_bwd != 0) needs
+ * for this shape.  Host-only; touches no device. */
+int deltanet_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes);
+
+/*
+ * Forward pass (Eq. 8-11).  initial_state may be NULL (zeros).  final_state may be NULL (not
+ * written).  Outputs: o (element type dtype), final_state (fp32).
+ */
+int deltanet_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                 const float *initial_state, void *o, float *final_state, void *workspace,
+                 size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward pass: exact gradient of  sum(o * d_o) + sum(final_state * dfinal_state)  with respect to
+ * q, k, v, beta and initial_state.  Self-contained: chunk states are recomputed from the inputs
+ * (section 3.2, "hidden states recomputed during the backward pass"), so nothing from the forward
+ * call has to be kept.  dfinal_state may be NULL (zeros); dinitial_state may be NULL (not written).
+ * Outputs: dq, dk, dv (element type dtype), dbeta (fp32, shape of beta), dinitial_state (fp32).
+ */
+int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                 const float *initial_state, const void *d_o, const float *dfinal_state, void *dq,
+                 void *dk, void *dv, float *dbeta, float *dinitial_state, void *workspace,
+                 size_t workspace_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a dn_status value. */
+const char *deltanet_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DELTANET_H_ */

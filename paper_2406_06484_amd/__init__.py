@@ -1,0 +1,15 @@
+"""MI355X-native chunkwise-parallel DeltaNet forward/backward (hand-written HIP behind a C ABI).
+
+``deltanet_fwd`` / ``deltanet_bwd`` are thin argument-marshalling bindings over
+``libdeltanet_hip.so`` (see ``include/deltanet.h``).  There is no CPU or PyTorch fallback: if the
+library has not been built, calling them raises.
+"""
+from .binding import (  # noqa: F401
+    DeltaNetError,
+    deltanet_bwd,
+    deltanet_fwd,
+    deltanet_status_string,
+    deltanet_workspace_bytes,
+    library_path,
+    load_library,
+)

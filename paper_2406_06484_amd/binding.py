@@ -1,0 +1,191 @@
+"""ctypes binding of ``libdeltanet_hip.so`` (declared in ``include/deltanet.h``).
+
+Argument marshalling only: every step of the DeltaNet forward/backward runs in the HIP kernels.
+PyTorch supplies device memory and the stream.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdeltanet_hip.so")
+_lib = None
+
+DN_F32, DN_BF16 = 0, 1
+
+
+class DeltaNetError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("deltanet: %s (status %d)" % (msg, status))
+        self.status = status
+
+
+class dn_shape(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("L", ctypes.c_int32), ("H", ctypes.c_int32),
+        ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("chunk", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("num_seqs", ctypes.c_int32),
+        ("cu_seqlens", ctypes.c_void_p), ("cu_seqlens_host", ctypes.c_void_p),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library; raises if it has not been built (run ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`; "
+                "there is no CPU fallback" % _LIB_PATH)
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        sp = ctypes.POINTER(dn_shape)
+        lib.deltanet_workspace_bytes.restype = ctypes.c_int
+        lib.deltanet_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(sz)]
+        lib.deltanet_fwd.restype = ctypes.c_int
+        lib.deltanet_fwd.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
+        lib.deltanet_bwd.restype = ctypes.c_int
+        lib.deltanet_bwd.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
+        lib.deltanet_status_string.restype = ctypes.c_char_p
+        lib.deltanet_status_string.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def deltanet_status_string(status: int) -> str:
+    return load_library().deltanet_status_string(int(status)).decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise DeltaNetError(status, deltanet_status_string(status))
+
+
+def _dt(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return DN_F32
+    if t.dtype == torch.bfloat16:
+        return DN_BF16
+    raise TypeError("q/k/v/beta must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _shape_of(q, v, cu_seqlens, chunk, cu_host_keepalive):
+    import numpy as np
+    s = dn_shape()
+    if cu_seqlens is None:
+        if q.dim() != 4:
+            raise ValueError("dense q must be [B, L, H, d_k]")
+        s.B, s.L, s.H, s.d_k = q.shape
+        s.num_seqs = 0
+        s.cu_seqlens = None
+        s.cu_seqlens_host = None
+    else:
+        if q.dim() != 3:
+            raise ValueError("packed q must be [T, H, d_k]")
+        s.B = 1
+        s.L, s.H, s.d_k = q.shape
+        s.num_seqs = cu_seqlens.numel() - 1
+        s.cu_seqlens = cu_seqlens.data_ptr()
+        host = np.ascontiguousarray(cu_seqlens.cpu().numpy().astype(np.int32))
+        cu_host_keepalive.append(host)
+        s.cu_seqlens_host = host.ctypes.data
+    s.d_v = v.shape[-1]
+    s.chunk = chunk
+    s.dtype = _dt(q)
+    return s
+
+
+def _p(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _req(t, name, dtype=None, shape=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s" % (name, dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+
+
+def deltanet_workspace_bytes(shape: dn_shape, want_bwd: bool) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().deltanet_workspace_bytes(ctypes.byref(shape), int(bool(want_bwd)), ctypes.byref(out)))
+    return int(out.value)
+
+
+def _workspace(shape, want_bwd, workspace, device):
+    import torch
+    need = deltanet_workspace_bytes(shape, want_bwd)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: int = 64,
+                 output_final_state: bool = True, o=None, final_state=None, workspace=None,
+                 stream=None) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
+    """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None)."""
+    import torch
+    lib = load_library()
+    keep = []
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta")):
+        _req(t, n, q.dtype)
+    s = _shape_of(q, v, cu_seqlens, chunk, keep)
+    _req(k, "k", shape=q.shape); _req(v, "v", shape=tuple(q.shape[:-1]) + (s.d_v,))
+    _req(beta, "beta", shape=q.shape[:-1])
+    N = s.num_seqs if cu_seqlens is not None else s.B
+    st_shape = (N, s.H, s.d_k, s.d_v)
+    if initial_state is not None:
+        _req(initial_state, "initial_state", torch.float32, st_shape)
+    if o is None:
+        o = torch.empty_like(v)
+    _req(o, "o", q.dtype, v.shape)
+    if final_state is None and output_final_state:
+        final_state = torch.empty(st_shape, dtype=torch.float32, device=q.device)
+    if final_state is not None:
+        _req(final_state, "final_state", torch.float32, st_shape)
+    workspace, wbytes = _workspace(s, False, workspace, q.device)
+    _check(lib.deltanet_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
+                            _p(final_state), _p(workspace), wbytes, _stream(stream)))
+    return o, final_state
+
+
+def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None,
+                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None):
+    """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None)."""
+    import torch
+    lib = load_library()
+    keep = []
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta"), (d_o, "d_o")):
+        _req(t, n, q.dtype)
+    s = _shape_of(q, v, cu_seqlens, chunk, keep)
+    _req(k, "k", shape=q.shape); _req(v, "v", shape=tuple(q.shape[:-1]) + (s.d_v,))
+    _req(beta, "beta", shape=q.shape[:-1]); _req(d_o, "d_o", shape=v.shape)
+    N = s.num_seqs if cu_seqlens is not None else s.B
+    st_shape = (N, s.H, s.d_k, s.d_v)
+    for t, n in ((initial_state, "initial_state"), (dfinal_state, "dfinal_state")):
+        if t is not None:
+            _req(t, n, torch.float32, st_shape)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dbeta = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
+    dS0 = torch.empty(st_shape, dtype=torch.float32, device=q.device) if want_dinitial_state else None
+    workspace, wbytes = _workspace(s, True, workspace, q.device)
+    _check(lib.deltanet_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(d_o),
+                            _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace),
+                            wbytes, _stream(stream)))
+    return dq, dk, dv, dbeta, dS0

@@ -1,0 +1,183 @@
+// C ABI of the DeltaNet library (declared in include/deltanet.h): validation, workspace layout,
+// dispatch to the compiled (dtype, d_k, d_v) instantiation.  Host code only.
+#include "../../include/deltanet.h"
+#include "dn_host.hpp"
+
+#include <string.h>
+
+namespace {
+
+using namespace dn;
+typedef __bf16 bf16_t;
+
+constexpr int kChunk = 64;
+
+struct Plan {
+    Problem pb;
+    size_t off_coff, off_W, off_U, off_Ut, off_dUt, off_Sc, off_dSc, off_dW, off_dK1, total;
+    size_t esz;
+};
+
+size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+typedef int (*run_fn)(const Problem &, const Ptrs &);
+struct Impl { int dtype, dk, dv; run_fn fwd, bwd; size_t (*lds)(); };
+
+#define DN_IMPL(ENUM, T, DK, DV) { ENUM, DK, DV, &run_fwd<T, DK, DV>, &run_bwd<T, DK, DV>, &max_lds_bytes<T, DK, DV> }
+const Impl kImpls[] = {
+    DN_IMPL(DN_F32, float, 64, 64),     DN_IMPL(DN_F32, float, 32, 64),    DN_IMPL(DN_F32, float, 64, 32),
+    DN_IMPL(DN_BF16, bf16_t, 128, 128), DN_IMPL(DN_BF16, bf16_t, 64, 64),
+    DN_IMPL(DN_BF16, bf16_t, 64, 128),  DN_IMPL(DN_BF16, bf16_t, 128, 64),
+};
+
+const Impl *find_impl(const dn_shape *s) {
+    for (const Impl &im : kImpls)
+        if (im.dtype == s->dtype && im.dk == s->d_k && im.dv == s->d_v) return &im;
+    return nullptr;
+}
+
+int validate_shape(const dn_shape *s, const Impl **impl) {
+    if (!s) return DN_ERR_NULL;
+    if (s->B <= 0 || s->L < 0 || s->H <= 0 || s->d_k <= 0 || s->d_v <= 0) return DN_ERR_SHAPE;
+    if (s->dtype != DN_F32 && s->dtype != DN_BF16) return DN_ERR_UNSUPPORTED;
+    if (s->chunk != kChunk) return DN_ERR_UNSUPPORTED;
+    if (s->cu_seqlens) {
+        if (s->B != 1 || s->num_seqs < 0) return DN_ERR_SHAPE;
+        if (s->cu_seqlens_host) {
+            const int32_t *c = s->cu_seqlens_host;
+            if (c[0] != 0 || c[s->num_seqs] != s->L) return DN_ERR_CUSEQLENS;
+            for (int n = 0; n < s->num_seqs; ++n)
+                if (c[n + 1] < c[n]) return DN_ERR_CUSEQLENS;
+        }
+    }
+    // 32-bit row indices and grid limits
+    const long long rows = (long long)s->B * s->L;
+    if (rows * s->H >= (1ll << 31) || s->H > 65535) return DN_ERR_SHAPE;
+    const long long nseq = s->cu_seqlens ? s->num_seqs : s->B;
+    if (nseq > 65535) return DN_ERR_SHAPE;
+    *impl = find_impl(s);
+    return *impl ? DN_OK : DN_ERR_UNSUPPORTED;
+}
+
+void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
+    memset(pl, 0, sizeof(*pl));
+    Problem &pb = pl->pb;
+    const bool packed = s->cu_seqlens != nullptr;
+    pb.N = packed ? s->num_seqs : s->B;
+    pb.L = s->L;
+    pb.H = s->H;
+    pb.cu = s->cu_seqlens;
+    const long long per = (s->L + kChunk - 1) / kChunk;
+    pb.chunks_ub = packed ? (int)(s->L / kChunk + s->num_seqs) : (int)(per * s->B);
+    if (packed && s->L == 0) pb.chunks_ub = 0;
+    pl->esz = s->dtype == DN_BF16 ? 2 : 4;
+    const size_t tiles = (size_t)pb.chunks_ub * s->H;
+    const size_t tK = up256(tiles * kChunk * s->d_k * pl->esz), tV = up256(tiles * kChunk * s->d_v * pl->esz);
+    const size_t tS = up256(tiles * (size_t)s->d_k * s->d_v * pl->esz);
+    size_t o = 0;
+    pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * ((size_t)pb.N + 1)) : 0;
+    pl->off_W = o; o += tK;
+    pl->off_U = o; o += tV;
+    if (want_bwd) {
+        pl->off_Ut = o; o += tV;
+        pl->off_dUt = o; o += tV;
+        pl->off_Sc = o; o += tS;
+        pl->off_dSc = o; o += tS;
+        pl->off_dW = o; o += tK;
+        pl->off_dK1 = o; o += tK;
+    }
+    pl->total = o;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd) {
+    unsigned char *b = static_cast<unsigned char *>(ws);
+    pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
+    p->W = b + pl.off_W;
+    p->U = b + pl.off_U;
+    if (want_bwd) {
+        p->Ut = b + pl.off_Ut; p->dUt = b + pl.off_dUt; p->Sc = b + pl.off_Sc;
+        p->dSc = b + pl.off_dSc; p->dW = b + pl.off_dW; p->dK1 = b + pl.off_dK1;
+    }
+}
+
+int check_device_lds(const Impl *impl) {
+    int dev = 0, lds = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return DN_ERR_LAUNCH;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return DN_ERR_LAUNCH;
+    return (size_t)lds >= impl->lds() ? DN_OK : DN_ERR_UNSUPPORTED;
+}
+
+} // namespace
+
+extern "C" {
+
+int deltanet_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes) {
+    if (!out_bytes) return DN_ERR_NULL;
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    Plan pl;
+    make_plan(shape, want_bwd, &pl);
+    *out_bytes = pl.total;
+    return DN_OK;
+}
+
+int deltanet_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                 const float *initial_state, void *o, float *final_state, void *workspace,
+                 size_t workspace_bytes, void *hip_stream) {
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    if (!q || !k || !v || !beta || !o) return DN_ERR_NULL;
+    const void *al[] = {q, k, v, beta, initial_state, o, final_state, workspace, shape->cu_seqlens};
+    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
+    Plan pl;
+    make_plan(shape, 0, &pl);
+    if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
+    if (int rc = check_device_lds(impl)) return rc;
+    Ptrs p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.k = k; p.v = v; p.beta = beta; p.S0 = initial_state; p.o = o; p.ST = final_state;
+    pl.pb.stream = static_cast<hipStream_t>(hip_stream);
+    bind_workspace(pl, workspace, &p, &pl.pb, false);
+    return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+}
+
+int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                 const float *initial_state, const void *d_o, const float *dfinal_state, void *dq,
+                 void *dk, void *dv, float *dbeta, float *dinitial_state, void *workspace,
+                 size_t workspace_bytes, void *hip_stream) {
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    if (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta) return DN_ERR_NULL;
+    const void *al[] = {q, k, v, beta, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dinitial_state,
+                        workspace, shape->cu_seqlens};
+    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
+    Plan pl;
+    make_plan(shape, 1, &pl);
+    if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
+    if (int rc = check_device_lds(impl)) return rc;
+    Ptrs p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.k = k; p.v = v; p.beta = beta; p.S0 = initial_state; p.d_o = d_o; p.dST = dfinal_state;
+    p.dq = dq; p.dk = dk; p.dv = dv; p.dbeta = dbeta; p.dS0 = dinitial_state;
+    pl.pb.stream = static_cast<hipStream_t>(hip_stream);
+    bind_workspace(pl, workspace, &p, &pl.pb, true);
+    return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+}
+
+const char *deltanet_status_string(int status) {
+    switch (status) {
+    case DN_OK: return "ok";
+    case DN_ERR_NULL: return "a required pointer is NULL";
+    case DN_ERR_SHAPE: return "a size is non-positive, inconsistent or too large";
+    case DN_ERR_UNSUPPORTED: return "no compiled kernel for this (dtype, d_k, d_v, chunk), or the device lacks the LDS it needs";
+    case DN_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+    case DN_ERR_WORKSPACE: return "workspace is NULL or too small";
+    case DN_ERR_CUSEQLENS: return "cu_seqlens_host is not a non-decreasing sequence from 0 to L";
+    case DN_ERR_LAUNCH: return "the HIP runtime reported an error";
+    default: return "unknown status";
+    }
+}
+
+} // extern "C"

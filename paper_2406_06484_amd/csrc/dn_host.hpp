@@ -1,0 +1,33 @@
+// Host-side launch plan shared by the C ABI (dn_api.hip) and the per-dtype instantiation files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dn {
+
+struct Problem {
+    int N, L, H;            // N sequences (dense: B sequences of L rows; packed: L = total rows)
+    int chunks_ub;          // upper bound on the total number of chunks (grid size of per-chunk kernels)
+    const int32_t *cu;      // device cu_seqlens or nullptr
+    int32_t *coff;          // device chunk-offset prefix [N+1] inside the workspace (packed only)
+    hipStream_t stream;
+};
+
+struct Ptrs {
+    // user tensors (device)
+    const void *q, *k, *v, *beta, *d_o;
+    const float *S0, *dST;
+    void *o, *dq, *dk, *dv;
+    float *ST, *dbeta, *dS0;
+    // workspace tiles, indexed by (global chunk * H + head)
+    void *W, *U, *Ut, *dUt, *Sc, *dSc, *dW, *dK1;
+};
+
+// 0 on success, else the hipError_t of the failing launch.  Defined once per (T, DK, DV).
+template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p);
+template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p);
+// largest dynamic LDS any kernel of this instantiation needs
+template <typename T, int DK, int DV> size_t max_lds_bytes();
+
+} // namespace dn

@@ -1,0 +1,76 @@
+// Launch sequences of the forward and backward pass for one (T, DK, DV); included only by the
+// instantiation files.
+#pragma once
+#include "dn_host.hpp"
+#include "dn_kernels.hpp"
+
+namespace dn {
+
+template <typename K> static inline int set_lds(K kernel, size_t bytes) {
+    return (int)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+#define DN_LAUNCH(kernel, grid, lds, ...)                                              \
+    do {                                                                               \
+        if (int e_ = set_lds(kernel, lds)) return e_;                                  \
+        hipLaunchKernelGGL(kernel, grid, dim3(NTHR), lds, pb.stream, __VA_ARGS__);     \
+        if (int e_ = (int)hipGetLastError()) return e_;                                \
+    } while (0)
+
+static inline SeqMap make_map(const Problem &pb) {
+    SeqMap sm;
+    sm.cu = pb.cu; sm.coff = pb.coff; sm.N = pb.N; sm.L = pb.L; sm.ncd = (pb.L + C - 1) / C;
+    return sm;
+}
+
+static inline int launch_offsets(const Problem &pb) {
+    if (!pb.cu) return 0;
+    hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(NTHR), 0, pb.stream, pb.cu, pb.N, pb.coff);
+    return (int)hipGetLastError();
+}
+
+constexpr size_t kLdsPerWorkgroup = 160 * 1024; // gfx950
+
+template <typename T, int DK, int DV> size_t max_lds_bytes() {
+    static_assert(PrepSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_wy_prep LDS");
+    static_assert(ScanFwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_fwd LDS");
+    static_assert(ScanBwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_bwd LDS");
+    static_assert(DqkwSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_dqkw LDS");
+    static_assert(WySmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_wy LDS");
+    size_t m = PrepSmem<T, DK, DV>::bytes;
+    if (ScanFwdSmem<T, DK, DV>::bytes > m) m = ScanFwdSmem<T, DK, DV>::bytes;
+    if (ScanBwdSmem<T, DK, DV>::bytes > m) m = ScanBwdSmem<T, DK, DV>::bytes;
+    if (DqkwSmem<T, DK, DV>::bytes > m) m = DqkwSmem<T, DK, DV>::bytes;
+    if (WySmem<T, DK, DV>::bytes > m) m = WySmem<T, DK, DV>::bytes;
+    return m;
+}
+
+template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p) {
+    if (pb.N == 0 || pb.chunks_ub == 0) return 0;
+    const SeqMap sm = make_map(pb);
+    if (int e = launch_offsets(pb)) return e;
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(VBlock<DV>::NV, pb.H, pb.N);
+    DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH((k_scan_fwd<T, DK, DV, false>), gchain, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    return 0;
+}
+
+template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p) {
+    if (pb.N == 0) return 0;
+    const SeqMap sm = make_map(pb);
+    if (int e = launch_offsets(pb)) return e;
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(VBlock<DV>::NV, pb.H, pb.N);
+    if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if (pb.chunks_ub) DN_LAUNCH((k_scan_fwd<T, DK, DV, true>), gchain, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH((k_scan_bwd<T, DK, DV>), gchain, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if (pb.chunks_ub) DN_LAUNCH((k_bwd_dqkw<T, DK, DV>), gchunk, (DqkwSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if (pb.chunks_ub) DN_LAUNCH((k_bwd_wy<T, DK, DV>), gchunk, (WySmem<T, DK, DV>::bytes), sm, pb.H, p);
+    return 0;
+}
+
+#define DN_INSTANTIATE(T, DK, DV)                                        \
+    template int run_fwd<T, DK, DV>(const Problem &, const Ptrs &);      \
+    template int run_bwd<T, DK, DV>(const Problem &, const Ptrs &);      \
+    template size_t max_lds_bytes<T, DK, DV>();
+
+} // namespace dn

@@ -1,0 +1,106 @@
+"""GPU parity (through the C ABI) against the fp64 oracle on small shapes that still span several
+chunks, a ragged tail, both dtypes, d_k != d_v, packed sequences and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_06484_amd as dn
+from paper_2406_06484_amd.synth import make_config, make_inputs
+from tests.gpu_util import TOL, check_fwd_bwd, dev_inputs, gpu_bwd, gpu_fwd, nerr
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config0_fp32_fwd_bwd():
+    check_fwd_bwd(make_config(0), label="cfg0")
+
+
+@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("f32", 64, 32),
+                                         ("bf16", 64, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 128, 64)])
+def test_ragged_multi_chunk_with_states(dtype, dk, dv):
+    inp = make_inputs(100 + dk + dv, B=2, L=200, H=3, dk=dk, dv=dv, dtype=dtype,
+                      with_initial_state=True, with_dfinal_state=True)
+    inp.initial_state *= 10.0  # make the carried-in state matter
+    check_fwd_bwd(inp, label="%s %dx%d" % (dtype, dk, dv))
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_packed_sequences(dtype, d):
+    cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)  # empty, tiny, exact-chunk, ragged
+    inp = make_inputs(7, H=2, dk=d, dv=d, dtype=dtype, cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)
+    check_fwd_bwd(inp, label="packed %s" % dtype)
+    # the packed call equals separate dense calls, sequence by sequence
+    o, ST = gpu_fwd(inp)
+    for n in (2, 4):
+        a, b = cu[n], cu[n + 1]
+        sub = make_inputs(7, H=2, dk=d, dv=d, dtype=dtype, B=1, L=int(b - a))
+        sub.q, sub.k, sub.v, sub.beta = (x[None, a:b] for x in (inp.q, inp.k, inp.v, inp.beta))
+        sub.initial_state = inp.initial_state[n:n + 1]
+        o1, ST1 = gpu_fwd(sub)
+        assert nerr(o1[0], o[a:b]) < 1e-6 and nerr(ST1[0], ST[n]) < 1e-6
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_short_sequence_and_length_one(dtype):
+    for L in (1, 17, 64, 65):
+        inp = make_inputs(40 + L, B=1, L=L, H=1, dk=64, dv=64, dtype=dtype, with_dfinal_state=True)
+        check_fwd_bwd(inp, label="L=%d %s" % (L, dtype))
+
+
+def test_beta_zero_leaves_state_bitwise_unchanged():
+    inp = make_inputs(3, B=1, L=130, H=2, dk=64, dv=64, dtype="f32", with_initial_state=True)
+    inp.beta[:] = 0.0
+    o, ST = gpu_fwd(inp)
+    assert np.array_equal(ST, inp.initial_state.astype(np.float32))
+    o_ref, _ = oracle.fwd(inp.q, inp.k, inp.v, inp.beta, inp.initial_state)
+    assert nerr(o, o_ref) < 1e-5
+
+
+def test_beta_one_onehot_keys_exact_in_bf16():
+    """One-hot keys and small-integer values are exact in bf16, so store-and-retrieve must be exact."""
+    d, L = 128, 128
+    rng = np.random.default_rng(9)
+    perm = rng.permutation(d)
+    k = np.eye(d)[perm][None, :, None, :]
+    inp = make_inputs(9, B=1, L=L, H=1, dk=d, dv=d, dtype="bf16")
+    inp.q = k.copy(); inp.k = k.copy(); inp.beta[:] = 1.0
+    inp.v = rng.integers(-8, 9, size=inp.v.shape).astype(np.float64)
+    o, ST = gpu_fwd(inp)
+    assert np.array_equal(o[0, :, 0], inp.v[0, :, 0])                       # q_t = k_t reads back v_t
+    assert np.array_equal(ST[0, 0], k[0, :, 0].T @ inp.v[0, :, 0])          # S = sum k v^T
+
+
+def test_state_chaining_on_gpu_matches_one_shot():
+    inp = make_inputs(21, B=1, L=300, H=2, dk=64, dv=64, dtype="f32", with_dfinal_state=True)
+    d = dev_inputs(inp)
+    o, ST = dn.deltanet_fwd(d["q"], d["k"], d["v"], d["beta"])
+    t0 = 150  # not a multiple of the chunk size
+    cut = lambda x, a, b: x[:, a:b].contiguous()
+    o1, S1 = dn.deltanet_fwd(cut(d["q"], 0, t0), cut(d["k"], 0, t0), cut(d["v"], 0, t0), cut(d["beta"], 0, t0))
+    o2, S2 = dn.deltanet_fwd(cut(d["q"], t0, 300), cut(d["k"], t0, 300), cut(d["v"], t0, 300), cut(d["beta"], t0, 300), S1)
+    assert nerr(torch.cat([o1, o2], 1).cpu().numpy(), o.cpu().numpy()) < 1e-5
+    assert nerr(S2.cpu().numpy(), ST.cpu().numpy()) < 1e-5
+    # gradients chain the same way: dS0 of part 2 is dfinal_state of part 1
+    full = dn.deltanet_bwd(d["q"], d["k"], d["v"], d["beta"], d["d_o"], None, d["dST"])
+    g2 = dn.deltanet_bwd(cut(d["q"], t0, 300), cut(d["k"], t0, 300), cut(d["v"], t0, 300), cut(d["beta"], t0, 300),
+                         cut(d["d_o"], t0, 300), S1, d["dST"])
+    g1 = dn.deltanet_bwd(cut(d["q"], 0, t0), cut(d["k"], 0, t0), cut(d["v"], 0, t0), cut(d["beta"], 0, t0),
+                         cut(d["d_o"], 0, t0), None, g2[4])
+    for i in range(4):
+        assert nerr(torch.cat([g1[i], g2[i]], 1).cpu().numpy(), full[i].cpu().numpy()) < 2e-5
+    assert nerr(g1[4].cpu().numpy(), full[4].cpu().numpy()) < 2e-5
+
+
+def test_results_are_deterministic_and_ignore_workspace_contents():
+    inp = make_inputs(5, B=2, L=192, H=2, dk=128, dv=128, dtype="bf16")
+    d = dev_inputs(inp)
+    outs = []
+    for fill in (0, 255):
+        from paper_2406_06484_amd.binding import _shape_of, deltanet_workspace_bytes
+        s = _shape_of(d["q"], d["v"], None, 64, [])
+        ws = torch.full((deltanet_workspace_bytes(s, True),), fill, dtype=torch.uint8, device="cuda")
+        g = dn.deltanet_bwd(d["q"], d["k"], d["v"], d["beta"], d["d_o"], workspace=ws)
+        outs.append([t.clone() for t in g])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)

@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the DeltaNet layer hot path on one MI355X.
+
+A "step" is one forward plus one backward pass of the layer (deltanet_fwd + deltanet_bwd through
+the C ABI) over one batch of synthetic input shaped like the paper's 1.3B-model layers:
+bf16, B=8, L=2048, H=16, d_k=d_v=128, chunk 64.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line: tokens/s of the layer (B*L tokens per step), the dominant kernel's
+roofline position (per-kernel time from HIP events recorded by the library on the launch stream),
+and the fp64 CPU oracle timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+C = 64
+
+
+def model_flops_per_token_head(d: int, c: int = C):
+    """Dense-tile FLOP count of the chunkwise algorithm per token per head (no recompute)."""
+    fwd = 6 * d * d + 10 * c * d + (2.0 / 3.0) * c * c
+    bwd = 12 * d * d + 20 * c * d + 4 * c * c
+    return fwd, bwd
+
+
+def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
+    """Dense-tile FLOPs one (chunk, head) costs in each kernel (what that kernel contracts)."""
+    if "k_wy_prep" in name:      # K K^T, forward substitution, T K, T V
+        return 6 * c * c * d + (2.0 / 3.0) * c ** 3
+    if "k_scan_fwd" in name and "true" in name:   # state recompute: W S, K^T Ut
+        return 4 * c * d * d
+    if "k_scan_fwd" in name:     # W S, Q S, K^T Ut, Q K^T, P Ut
+        return 6 * c * d * d + 4 * c * c * d
+    if "k_scan_bwd" in name:     # K dS, Q^T dO, W^T dUt, Q K^T, P^T dO
+        return 6 * c * d * d + 4 * c * c * d
+    if "k_bwd_dqkw" in name:     # dO S^T, dUt S^T, Ut dS^T, dO Ut^T, dP K, dP^T Q
+        return 6 * c * d * d + 6 * c * c * d
+    if "k_bwd_wy" in name:       # K K^T, dW K^T, dU V^T, X^T dW, X^T dU, (Ah+Ah^T) K, dX X^T, X^T M1, inverse
+        return 12 * c * c * d + 4 * c ** 3 + (2.0 / 3.0) * c ** 3
+    return 0.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2406_06484_amd as dn
+    from paper_2406_06484_amd.synth import CONFIGS, make_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    dn.load_library()
+    cfg = CONFIGS[2]
+    B, L, H, d = cfg["B"], cfg["L"], cfg["H"], cfg["dk"]
+    inp = make_config(2)
+    dev = torch.device("cuda:0")
+    bf = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.float32).to(torch.bfloat16).to(dev)
+    q, k, v, beta, d_o = (bf(getattr(inp, n)) for n in ("q", "k", "v", "beta", "d_o"))
+    from paper_2406_06484_amd.binding import _shape_of, deltanet_workspace_bytes
+    shp = _shape_of(q, v, None, C, [])
+    ws = torch.empty(deltanet_workspace_bytes(shp, True), dtype=torch.uint8, device=dev)
+    o = torch.empty_like(v)
+    ST = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
+
+    def step():
+        dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
+        return dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    tokens = B * L
+    value = tokens * args.steps / dt
+
+    # fwd / bwd split (untimed for `value`)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    fw = bw = 0.0
+    for _ in range(args.steps):
+        ev[0].record(); dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
+        ev[1].record(); dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
+        ev[2].record(); torch.cuda.synchronize()
+        fw += ev[0].elapsed_time(ev[1]); bw += ev[1].elapsed_time(ev[2])
+    fw /= args.steps; bw /= args.steps
+
+    # per-kernel device time from the library's own HIP events on the launch stream
+    dn.deltanet_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = dn.deltanet_profile_collect()
+    dn.deltanet_profile_enable(False)
+    chunk_heads = B * H * (L // C)
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        nm = name.strip("()")
+        avg = ms / n
+        fl = kernel_flops_per_chunk_head(nm, d) * chunk_heads
+        kernels[nm] = {"avg_ms": round(avg, 4), "launches_per_step": n // args.steps,
+                       "tflops": round(fl / (avg * 1e-3) / 1e12, 2)}
+    # k_wy_prep runs twice per step (forward and backward); weight by launches per step
+    dom = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
+    fwd_f, bwd_f = model_flops_per_token_head(d)
+    model_tflops = (fwd_f + bwd_f) * H * value / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None}
+
+    out = {
+        "metric": "DeltaNet layer fwd+bwd tokens/s at H=16,d=128,L=2048; % bf16 MFMA peak",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[2]: bf16 fwd+bwd, B=8, L=2048, H=16, d_k=d_v=128, chunk=64",
+                   "tokens_per_step": tokens},
+        "fwd_ms": round(fw, 4), "bwd_ms": round(bw, 4),
+        "model_tflops": round(model_tflops, 2),
+        "pct_bf16_mfma_peak": round(100 * model_tflops / PEAK_BF16_TFLOPS, 3),
+        "algorithmic_hbm_gbs": round((1026 + 1798) * H * value / 1e9, 1),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        nthr = oracle.max_threads()
+        t0 = time.perf_counter()
+        reps = 0
+        while True:  # the whole workload through the fp64 oracle, repeated until >= 10 s of wall time
+            oracle.fwd(inp.q, inp.k, inp.v, inp.beta)
+            oracle.bwd(inp.q, inp.k, inp.v, inp.beta, inp.d_o)
+            reps += 1
+            if time.perf_counter() - t0 >= 10.0 or reps >= 3:
+                break
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(tokens * reps / cdt, 1), "unit": "tokens/s", "cores": nthr, "kind": "oracle",
+                               "sample": "the full workload (all %d chains x %d tokens), fwd+bwd, %d repetition(s), fp64, "
+                                         "OpenMP over chains" % (B * H, L, reps)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

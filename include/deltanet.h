@@ -89,6 +89,22 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
                  void *dk, void *dv, float *dbeta, float *dinitial_state, void *workspace,
                  size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Measurement aid (not part of the method): per-kernel device time.  After
+ * deltanet_profile_enable(1), every kernel launch of deltanet_fwd / deltanet_bwd is bracketed by a
+ * pair of HIP events recorded on the launch stream.  deltanet_profile_collect waits for those
+ * events, sums the elapsed milliseconds per kernel name into `out` (at most max_entries distinct
+ * kernels; HOST memory), stores the number of entries and forgets the records.  Events cost a few
+ * microseconds per launch, so whole-pass timings should be taken with profiling disabled.
+ */
+typedef struct {
+    char name[96];    /* kernel name with its template arguments, as written in the source */
+    double total_ms;  /* summed device time between the two events */
+    int32_t launches;
+} dn_kernel_time;
+int deltanet_profile_enable(int on);
+int deltanet_profile_collect(dn_kernel_time *out, int max_entries, int *num_entries);
+
 /* Static, NUL-terminated description of a dn_status value. */
 const char *deltanet_status_string(int status);
 

@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     DeltaNetError,
     deltanet_bwd,
     deltanet_fwd,
+    deltanet_profile_collect,
+    deltanet_profile_enable,
     deltanet_status_string,
     deltanet_workspace_bytes,
     library_path,

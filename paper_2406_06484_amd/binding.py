@@ -31,6 +31,10 @@ class dn_shape(ctypes.Structure):
     ]
 
 
+class dn_kernel_time(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 96), ("total_ms", ctypes.c_double), ("launches", ctypes.c_int32)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -52,6 +56,10 @@ def load_library():
         lib.deltanet_fwd.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
         lib.deltanet_bwd.restype = ctypes.c_int
         lib.deltanet_bwd.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
+        lib.deltanet_profile_enable.restype = ctypes.c_int
+        lib.deltanet_profile_enable.argtypes = [ctypes.c_int]
+        lib.deltanet_profile_collect.restype = ctypes.c_int
+        lib.deltanet_profile_collect.argtypes = [ctypes.POINTER(dn_kernel_time), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         lib.deltanet_status_string.restype = ctypes.c_char_p
         lib.deltanet_status_string.argtypes = [ctypes.c_int]
         _lib = lib
@@ -60,6 +68,18 @@ def load_library():
 
 def deltanet_status_string(status: int) -> str:
     return load_library().deltanet_status_string(int(status)).decode()
+
+
+def deltanet_profile_enable(on: bool) -> None:
+    _check(load_library().deltanet_profile_enable(int(bool(on))))
+
+
+def deltanet_profile_collect(max_entries: int = 32) -> dict:
+    """{kernel name: (total_ms, launches)} since profiling was enabled or last collected."""
+    buf = (dn_kernel_time * max_entries)()
+    n = ctypes.c_int(0)
+    _check(load_library().deltanet_profile_collect(buf, max_entries, ctypes.byref(n)))
+    return {buf[i].name.decode(): (buf[i].total_ms, buf[i].launches) for i in range(n.value)}
 
 
 def _check(status: int):

@@ -5,6 +5,35 @@
 
 #include <string.h>
 
+#include <mutex>
+#include <string>
+#include <vector>
+
+namespace dn {
+namespace {
+struct ProfRec { std::string name; hipEvent_t a, b; };
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+} // namespace
+
+void prof_begin(const char *kernel_name, hipStream_t stream) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    ProfRec r;
+    r.name = kernel_name;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+    (void)hipEventRecord(r.a, stream);
+    g_prof.push_back(r);
+}
+void prof_end(hipStream_t stream) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof.empty()) (void)hipEventRecord(g_prof.back().b, stream);
+}
+} // namespace dn
+
 namespace {
 
 using namespace dn;
@@ -164,6 +193,38 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     bind_workspace(pl, workspace, &p, &pl.pb, true);
     return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+}
+
+int deltanet_profile_enable(int on) {
+    std::lock_guard<std::mutex> lk(dn::g_prof_mu);
+    dn::g_prof_on = on != 0;
+    return DN_OK;
+}
+
+int deltanet_profile_collect(dn_kernel_time *out, int max_entries, int *num_entries) {
+    if (!num_entries || (max_entries > 0 && !out)) return DN_ERR_NULL;
+    std::lock_guard<std::mutex> lk(dn::g_prof_mu);
+    int n = 0;
+    int rc = DN_OK;
+    for (dn::ProfRec &r : dn::g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) rc = DN_ERR_LAUNCH;
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+        int i = 0;
+        for (; i < n; ++i) if (r.name == out[i].name) break;
+        if (i == n) {
+            if (n == max_entries) continue;
+            memset(&out[n], 0, sizeof(out[n]));
+            strncpy(out[n].name, r.name.c_str(), sizeof(out[n].name) - 1);
+            ++n;
+        }
+        out[i].total_ms += ms;
+        out[i].launches += 1;
+    }
+    dn::g_prof.clear();
+    *num_entries = n;
+    return rc;
 }
 
 const char *deltanet_status_string(int status) {

@@ -24,6 +24,11 @@ struct Ptrs {
     void *W, *U, *Ut, *dUt, *Sc, *dSc, *dW, *dK1;
 };
 
+// Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is
+// bracketed by a pair of HIP events on the launch stream.  No-ops when disabled.
+void prof_begin(const char *kernel_name, hipStream_t stream);
+void prof_end(hipStream_t stream);
+
 // 0 on success, else the hipError_t of the failing launch.  Defined once per (T, DK, DV).
 template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p);
 template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p);

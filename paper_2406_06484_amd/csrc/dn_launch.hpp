@@ -13,7 +13,9 @@ template <typename K> static inline int set_lds(K kernel, size_t bytes) {
 #define DN_LAUNCH(kernel, grid, lds, ...)                                              \
     do {                                                                               \
         if (int e_ = set_lds(kernel, lds)) return e_;                                  \
+        prof_begin(#kernel, pb.stream);                                                \
         hipLaunchKernelGGL(kernel, grid, dim3(NTHR), lds, pb.stream, __VA_ARGS__);     \
+        prof_end(pb.stream);                                                           \
         if (int e_ = (int)hipGetLastError()) return e_;                                \
     } while (0)
 

@@ -1,0 +1,88 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2406_06484_amd", "libdeltanet_hip.so")
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="library not built (run __graft_entry__.build())")
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "deltanet.h")).read()
+    return sorted(set(re.findall(r"\b(deltanet_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(LIB)
+    syms = header_symbols()
+    assert {"deltanet_fwd", "deltanet_bwd", "deltanet_workspace_bytes", "deltanet_status_string"} <= set(syms)
+    for s in syms:
+        assert hasattr(lib, s), s
+
+
+def _shape(**kw):
+    from paper_2406_06484_amd.binding import dn_shape
+    s = dn_shape()
+    base = dict(B=2, L=256, H=4, d_k=128, d_v=128, chunk=64, dtype=1, num_seqs=0, cu_seqlens=None, cu_seqlens_host=None)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(s, k, v)
+    return s
+
+
+def test_workspace_query_and_validation_errors():
+    from paper_2406_06484_amd.binding import load_library
+    lib = load_library()
+    out = ctypes.c_size_t(0)
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape()), 0, ctypes.byref(out)) == 0
+    fwd_bytes = out.value
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape()), 1, ctypes.byref(out)) == 0
+    assert out.value > fwd_bytes > 0
+    # W and U tiles for every (chunk, head): 2 * B*L*H*d * 2 bytes
+    assert fwd_bytes == 2 * 2 * 256 * 4 * 128 * 2
+    assert lib.deltanet_workspace_bytes(None, 0, ctypes.byref(out)) == -1
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(H=0)), 0, ctypes.byref(out)) == -2
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(d_k=96)), 0, ctypes.byref(out)) == -3
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(chunk=32)), 0, ctypes.byref(out)) == -3
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(dtype=7)), 0, ctypes.byref(out)) == -3
+    # fp32 is compiled for head dim 64 only
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(dtype=0)), 0, ctypes.byref(out)) == -3
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(dtype=0, d_k=64, d_v=64)), 0, ctypes.byref(out)) == 0
+    for code in range(0, -9, -1):
+        assert lib.deltanet_status_string(code)
+
+
+def test_fwd_bwd_reject_bad_arguments_before_any_launch():
+    from paper_2406_06484_amd.binding import load_library
+    lib = load_library()
+    s = _shape()
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    args = [fake] * 4 + [None, fake, None]
+    assert lib.deltanet_fwd(ctypes.byref(s), None, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -1
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.deltanet_fwd(ctypes.byref(s), odd, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -4
+    assert lib.deltanet_fwd(ctypes.byref(s), *args, fake, 16, None) == -5
+    assert lib.deltanet_fwd(ctypes.byref(s), *args, None, 0, None) == -5
+    bargs = [fake] * 4 + [None, fake, None, fake, fake, fake, fake, None]
+    assert lib.deltanet_bwd(ctypes.byref(s), *bargs, fake, 16, None) == -5
+    bargs[10] = None  # dbeta is required
+    assert lib.deltanet_bwd(ctypes.byref(s), *bargs, fake, 1 << 40, None) == -1
+
+
+def test_cu_seqlens_host_is_validated():
+    from paper_2406_06484_amd.binding import load_library
+    lib = load_library()
+    out = ctypes.c_size_t(0)
+    fake = 0x1000
+    good = np.array([0, 10, 10, 300, 512], dtype=np.int32)
+    for arr, rc in ((good, 0), (np.array([0, 10, 5, 300, 512], np.int32), -6), (np.array([1, 10, 20, 300, 512], np.int32), -6),
+                    (np.array([0, 10, 20, 300, 500], np.int32), -6)):
+        s = _shape(B=1, L=512, num_seqs=4, cu_seqlens=fake, cu_seqlens_host=arr.ctypes.data)
+        assert lib.deltanet_workspace_bytes(ctypes.byref(s), 1, ctypes.byref(out)) == rc
+    s = _shape(B=2, L=512, num_seqs=4, cu_seqlens=fake, cu_seqlens_host=good.ctypes.data)
+    assert lib.deltanet_workspace_bytes(ctypes.byref(s), 1, ctypes.byref(out)) == -2  # packed needs B = 1

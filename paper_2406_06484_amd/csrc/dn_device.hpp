@@ -20,7 +20,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // Per-element-type constants: LDS row padding (elements) and elements per 16 bytes.
 template <typename T> struct El;
 template <> struct El<float> { static constexpr int PAD = 4; static constexpr int VEC = 4; };
-template <> struct El<bf16>  { static constexpr int PAD = 8; static constexpr int VEC = 8; };
+template <> struct El<bf16>  { static constexpr int PAD = 16; static constexpr int VEC = 8; };
 
 template <typename T> __host__ __device__ constexpr int ldn(int cols) { return cols + El<T>::PAD; }
 
@@ -76,6 +76,56 @@ __device__ inline void mma_nt(f32x16 &acc, const float *A, int lda, const float 
 #pragma unroll 8
     for (int k0 = 0; k0 < KDIM; k0 += 2)
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k0], pb[k0], acc, 0, 0, 0);
+}
+
+// Operand fragments for the 32x32 MFMAs, from LDS, in two storage orders:
+//   KC  storage [n][k], contraction index contiguous  (one 16-byte read per lane in bf16)
+//   KS  storage [k][n], contraction index strided     (bf16: two ds_read_b64_tr_b16, the CDNA4
+//       transposing LDS read; fp32: a plain read, since an fp32 fragment is one element per lane)
+// `base` points at (n0, k = 0) for KC and at (k = 0, n0) for KS.  Both orders give lane l the
+// operand row/column n0 + (l & 31) and, in bf16, k = k0 + 8*(l >> 5) + 0..7.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ inline bf16x8 frag_kc(const bf16 *base, int ld, int k0) {
+    const int lane = threadIdx.x & 63;
+    return *reinterpret_cast<const bf16x8 *>(base + (lane & 31) * ld + k0 + 8 * (lane >> 5));
+}
+__device__ inline bf16x8 frag_ks(const bf16 *base, int ld, int k0) {
+    // Within each group of 16 lanes the transposing read hands lane i the 16-bit element (i & 3) of
+    // the four 8-byte rows addressed by lanes (i >> 2), (i >> 2) + 4, + 8, + 12.  With lane i
+    // pointing at row k0' + (i >> 2), columns 4*(i & 3).., lane i ends up with column i, rows k0'..k0'+3.
+    const int lane = threadIdx.x & 63, i = lane & 15;
+    const bf16 *p = base + (k0 + 8 * (lane >> 5) + (i >> 2)) * ld + (lane & 16) + 4 * (i & 3);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * ld));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+__device__ inline float frag_kc(const float *base, int ld, int k0) {
+    const int lane = threadIdx.x & 63;
+    return base[(lane & 31) * ld + k0 + (lane >> 5)];
+}
+__device__ inline float frag_ks(const float *base, int ld, int k0) {
+    const int lane = threadIdx.x & 63;
+    return base[(k0 + (lane >> 5)) * ld + (lane & 31)];
+}
+__device__ inline void mfma32(f32x16 &acc, bf16x8 a, bf16x8 b) { acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0); }
+__device__ inline void mfma32(f32x16 &acc, float a, float b) { acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0); }
+template <typename T> struct KStep;
+template <> struct KStep<bf16> { static constexpr int value = 16; };
+template <> struct KStep<float> { static constexpr int value = 2; };
+
+// acc(32x32) += A * B over KDIM contraction steps; AKS / BKS select the storage order of each operand
+template <int KDIM, bool AKS, bool BKS, typename T>
+__device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb) {
+#pragma unroll 8
+    for (int k0 = 0; k0 < KDIM; k0 += KStep<T>::value) {
+        const auto a = AKS ? frag_ks(A, lda, k0) : frag_kc(A, lda, k0);
+        const auto b = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
+        mfma32(acc, a, b);
+    }
 }
 
 __device__ inline f32x16 zero16() {
@@ -144,6 +194,26 @@ __device__ inline void load_tile(T *dst, int ld, const T *src, long row_stride, 
         *reinterpret_cast<uint4 *>(dst + r * ld + tc) = val;
     }
 }
+// The same tile fetched into registers first (to be parked while LDS is busy) and stored later.
+template <typename T, int ROWS, int COLS> struct TileRegs {
+    static constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NTHR / TPR, NIT = ROWS / RPI;
+    static_assert(COLS % VEC == 0 && NTHR % TPR == 0 && ROWS % RPI == 0, "tile shape");
+    uint4 v[NIT];
+    __device__ inline void load(const T *src, long row_stride, int nvalid) {
+        const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int r = it * RPI + tr;
+            v[it] = make_uint4(0, 0, 0, 0);
+            if (r < nvalid) v[it] = *reinterpret_cast<const uint4 *>(src + (long)r * row_stride + tc);
+        }
+    }
+    __device__ inline void store(T *dst, int ld) const {
+        const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) *reinterpret_cast<uint4 *>(dst + (it * RPI + tr) * ld + tc) = v[it];
+    }
+};
 // LDS -> global, ROWS x COLS, rows >= nvalid dropped
 template <typename T, int ROWS, int COLS>
 __device__ inline void store_tile(T *dst, long row_stride, const T *src, int ld, int nvalid) {
@@ -213,6 +283,89 @@ __device__ inline void tri_inverse_64(const float *sA, float *sX, float *sM, int
         }
         __syncthreads();
     }
+}
+
+
+// In-place variant used by the fast kernels.  On entry sX (fp32, leading dimension ld) holds the
+// strictly lower triangular A with zeros elsewhere; on exit it holds X = (I + A)^{-1}.
+// Blocked forward substitution: the eight 8x8 diagonal blocks are solved column by column (16
+// lanes of every wavefront), then 2x2 block merges X21 = -X22 (A21 X11) double the block size
+// 8 -> 16 -> 32 on the vector ALU in fp32 and 32 -> 64 on the matrix cores with operands of type T.
+// sM: 512 floats of scratch.  sOp: 4 x 32 x LO elements of type T, LO >= 32 + 8.  Ends with a barrier.
+template <typename T>
+__device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *sOp, int LO) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (lane < 16) {
+        const int b = (2 * wave + (lane >> 3)) * 8, j = lane & 7;
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float s = (i == j) ? 1.f : 0.f;
+#pragma unroll
+            for (int m = 0; m < i; ++m) s -= sX[(b + i) * ld + b + m] * x[m];
+            x[i] = (i < j) ? 0.f : s;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sX[(b + i) * ld + b + j] = x[i];
+    }
+    __syncthreads();
+    { // 8 -> 16: four merges, one output element per thread
+        const int m = tid >> 6, i = (tid >> 3) & 7, j = tid & 7, r0 = 16 * m + 8, c0 = 16 * m;
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + c0 + k] * sX[(c0 + k) * ld + c0 + j];
+        sM[tid] = s;
+        __syncthreads();
+        s = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + r0 + k] * sM[(m << 6) + k * 8 + j];
+        sX[(r0 + i) * ld + c0 + j] = -s;
+        __syncthreads();
+    }
+    { // 16 -> 32: two merges, two output elements per thread
+        const int m = tid >> 7, i = (tid >> 3) & 15, j = 2 * (tid & 7), r0 = 32 * m + 16, c0 = 32 * m;
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const float a = sX[(r0 + i) * ld + c0 + k];
+            s0 += a * sX[(c0 + k) * ld + c0 + j];
+            s1 += a * sX[(c0 + k) * ld + c0 + j + 1];
+        }
+        sM[(m << 8) + i * 16 + j] = s0;
+        sM[(m << 8) + i * 16 + j + 1] = s1;
+        __syncthreads();
+        s0 = s1 = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const float a = sX[(r0 + i) * ld + r0 + k];
+            s0 += a * sM[(m << 8) + k * 16 + j];
+            s1 += a * sM[(m << 8) + k * 16 + j + 1];
+        }
+        sX[(r0 + i) * ld + c0 + j] = -s0;
+        sX[(r0 + i) * ld + c0 + j + 1] = -s1;
+        __syncthreads();
+    }
+    // 32 -> 64 on the matrix cores: operands A21, X11^T, X22 and (later) M^T, each 32 x LO
+    T *oA = sOp, *oX11T = sOp + 32 * LO, *oX22 = sOp + 64 * LO, *oMT = sOp + 96 * LO;
+    for (int e = tid; e < 32 * 32; e += NTHR) {
+        const int i = e >> 5, k = e & 31;
+        oA[i * LO + k] = from_f32<T>(sX[(32 + i) * ld + k]);
+        oX11T[k * LO + i] = from_f32<T>(sX[i * ld + k]);
+        oX22[i * LO + k] = from_f32<T>(sX[(32 + i) * ld + 32 + k]);
+    }
+    __syncthreads();
+    f32x16 acc = zero16();
+    if (wave == 0) {
+        mma<32, false, false, T>(acc, oA, LO, oX11T, LO); // M = A21 X11
+        acc_to_lds_t<T>(oMT, LO, 0, 0, acc);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        acc = zero16();
+        mma<32, false, false, T>(acc, oX22, LO, oMT, LO); // X22 M
+        acc_each(acc, [&](int r, int c, float &v) { sX[(32 + r) * ld + c] = -v; });
+    }
+    __syncthreads();
 }
 
 } // namespace dn

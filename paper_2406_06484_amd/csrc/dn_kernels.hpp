@@ -39,17 +39,17 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
 }
 
 // =============================================================================================
-// k_wy_prep
+// k_wy_prep.  LDS holds one row-major operand tile (K, later V), the fp32 C x C matrix that is
+// inverted in place, and T; V waits in registers until K is no longer needed.
 template <typename T, int DK, int DV> struct PrepSmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LM = 52;
-    static constexpr size_t oK = 0;
-    static constexpr size_t oKT = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oVT = oKT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oR1 = oVT + align16(sizeof(T) * DV * LT); // V staging, then A and X, then U staging
-    static constexpr size_t szR1 = cmax(sizeof(T) * C * LV, 2 * sizeof(float) * C * LF);
-    static constexpr size_t oT = oR1 + align16(szR1);
-    static constexpr size_t oM = oT + align16(sizeof(T) * C * LT);
-    static constexpr size_t oBeta = oM + sizeof(float) * 16 * LM;
+    static constexpr int DM = cmax(DK, DV);
+    static constexpr int LD = ldn<T>(DM), LT = ldn<T>(C), LF = C + 4, LO = 40;
+    static constexpr size_t oKV = 0;
+    static constexpr size_t oX = oKV + align16(sizeof(T) * C * LD);
+    static constexpr size_t oT = oX + align16(sizeof(float) * C * LF);     // inverse operands, then T
+    static constexpr size_t szT = cmax(sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO);
+    static constexpr size_t oM = oT + align16(szT);
+    static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t bytes = oBeta + sizeof(float) * C;
 };
 
@@ -57,12 +57,8 @@ template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     using SM = PrepSmem<T, DK, DV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    T *sK = reinterpret_cast<T *>(smem + SM::oK);
-    T *sKT = reinterpret_cast<T *>(smem + SM::oKT);
-    T *sVT = reinterpret_cast<T *>(smem + SM::oVT);
-    T *sV = reinterpret_cast<T *>(smem + SM::oR1);
-    float *sA = reinterpret_cast<float *>(smem + SM::oR1);
-    float *sX = sA + C * SM::LF;
+    T *sKV = reinterpret_cast<T *>(smem + SM::oKV);
+    float *sX = reinterpret_cast<float *>(smem + SM::oX);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
@@ -76,48 +72,44 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     const long row0 = (long)t0 + (long)ic * C;
     const long tile = ((long)(cb + ic) * H + h);
 
-    load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-    load_tile<T, C, DV>(sV, SM::LV, (const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
+    TileRegs<T, C, DV> vregs; // V is fetched now and parked in registers
+    vregs.load((const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
+    load_tile<T, C, DK>(sKV, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
     __syncthreads();
-    transpose_tile<T, DK>(sKT, SM::LT, sK, SM::LK);
-    transpose_tile<T, DV>(sVT, SM::LT, sV, SM::LV);
-    // Gram tile of this wave: rows 32*mi.., cols 32*ni..
-    const int mi = wave >> 1, ni = wave & 1;
-    f32x16 g = zero16();
-    if (!(mi == 0 && ni == 1)) mma_nt<DK>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-    __syncthreads(); // sV (aliasing sA/sX) is dead now
-    acc_each(g, [&](int r, int c, float &val) {
-        const int i = 32 * mi + r, j = 32 * ni + c;
-        sA[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
-    });
+    { // A = tril(diag(beta) K K^T, -1), Eq. 10
+        const int mi = wave >> 1, ni = wave & 1;
+        f32x16 g = zero16();
+        if (!(mi == 0 && ni == 1)) mma<DK, false, false, T>(g, sKV + 32 * mi * SM::LD, SM::LD, sKV + 32 * ni * SM::LD, SM::LD);
+        acc_each(g, [&](int r, int c, float &val) {
+            const int i = 32 * mi + r, j = 32 * ni + c;
+            sX[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
+        });
+    }
     __syncthreads();
-    tri_inverse_64(sA, sX, sM, SM::LF, SM::LM);
-    // T = X diag(beta), Eq. 10
-    for (int e = tid; e < C * C; e += NTHR) {
+    tri_inverse_64_inplace<T>(sX, SM::LF, sM, sT, SM::LO);
+    for (int e = tid; e < C * C; e += NTHR) { // T = X diag(beta)
         const int i = e >> 6, j = e & 63;
         sT[i * SM::LT + j] = from_f32<T>(sX[i * SM::LF + j] * sBeta[j]);
     }
     __syncthreads();
-    // W = T K -> staged in sK; U = T V -> staged in R1 (Eq. 11)
-    T *sWout = sK, *sUout = sV;
-    for (int t = wave; t < 2 * (DK / 32); t += NWAVE) {
+    for (int t = wave; t < 2 * (DK / 32); t += NWAVE) { // W = T K, Eq. 11 (K read through the transposing path)
         const int a = t / (DK / 32), b = t % (DK / 32);
         f32x16 acc = zero16();
-        if (a == 0) mma_nt<32>(acc, sT, SM::LT, sKT + 32 * b * SM::LT, SM::LT);
-        else mma_nt<C>(acc, sT + 32 * SM::LT, SM::LT, sKT + 32 * b * SM::LT, SM::LT);
-        acc_to_lds<T>(sWout, SM::LK, 32 * a, 32 * b, acc);
-    }
-    for (int t = wave; t < 2 * (DV / 32); t += NWAVE) {
-        const int a = t / (DV / 32), b = t % (DV / 32);
-        f32x16 acc = zero16();
-        if (a == 0) mma_nt<32>(acc, sT, SM::LT, sVT + 32 * b * SM::LT, SM::LT);
-        else mma_nt<C>(acc, sT + 32 * SM::LT, SM::LT, sVT + 32 * b * SM::LT, SM::LT);
-        acc_to_lds<T>(sUout, SM::LV, 32 * a, 32 * b, acc);
+        if (a == 0) mma<32, false, true, T>(acc, sT, SM::LT, sKV + 32 * b, SM::LD);
+        else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sKV + 32 * b, SM::LD);
+        acc_to_global<T>((T *)p.W + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
     }
     __syncthreads();
-    store_tile<T, C, DK>((T *)p.W + tile * C * DK, DK, sWout, SM::LK, C);
-    store_tile<T, C, DV>((T *)p.U + tile * C * DV, DV, sUout, SM::LV, C);
+    vregs.store(sKV, SM::LD);
+    __syncthreads();
+    for (int t = wave; t < 2 * (DV / 32); t += NWAVE) { // U = T V
+        const int a = t / (DV / 32), b = t % (DV / 32);
+        f32x16 acc = zero16();
+        if (a == 0) mma<32, false, true, T>(acc, sT, SM::LT, sKV + 32 * b, SM::LD);
+        else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sKV + 32 * b, SM::LD);
+        acc_to_global<T>((T *)p.U + tile * C * DV, DV, 32 * a, 32 * b, C, acc);
+    }
 }
 
 // =============================================================================================
@@ -131,8 +123,7 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LK);
     static constexpr size_t oW = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oKT = oW + align16(sizeof(T) * C * LK);
-    static constexpr size_t oU = oKT + align16(sizeof(T) * DK * LT);
+    static constexpr size_t oU = oW + align16(sizeof(T) * C * LK);
     static constexpr size_t oST = oU + align16(sizeof(T) * C * LB);
     static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LK);
     static constexpr size_t oP = oUT + align16(sizeof(T) * BV * LT);
@@ -149,7 +140,6 @@ __global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
-    T *sKT = reinterpret_cast<T *>(smem + SM::oKT);
     T *sU = reinterpret_cast<T *>(smem + SM::oU);
     T *sST = reinterpret_cast<T *>(smem + SM::oST);
     T *sUT = reinterpret_cast<T *>(smem + SM::oUT);
@@ -186,7 +176,7 @@ __global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        load_tile<T, C, DK>(sQ, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        if (!STORE) load_tile<T, C, DK>(sQ, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
         load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
         load_tile<T, C, DK>(sW, SM::LK, (const T *)p.W + tile * C * DK, DK, C);
         load_tile<T, C, BV>(sU, SM::LB, (const T *)p.U + tile * C * DV + vb, DV, C);
@@ -199,11 +189,10 @@ __global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
             }
         }
         __syncthreads();
-        transpose_tile<T, DK>(sKT, SM::LT, sK, SM::LK);
         if (!STORE) { // P = tril(Q K^T), diagonal included (Eq. 9)
             const int a = wave >> 1, b = wave & 1;
             f32x16 acc = zero16();
-            if (!(a == 0 && b == 1)) mma_nt<DK>(acc, sQ + 32 * a * SM::LK, SM::LK, sK + 32 * b * SM::LK, SM::LK);
+            if (!(a == 0 && b == 1)) mma<DK, false, false, T>(acc, sQ + 32 * a * SM::LK, SM::LK, sK + 32 * b * SM::LK, SM::LK);
             acc_each(acc, [&](int r, int c, float &val) {
                 sP[(32 * a + r) * SM::LT + 32 * b + c] = from_f32<T>((32 * b + c <= 32 * a + r) ? val : 0.f);
             });
@@ -212,7 +201,7 @@ __global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         for (int t = wave; t < U_TILES; t += NWAVE) {
             const int a = t / NVT, b = t % NVT;
             f32x16 acc = zero16();
-            mma_nt<DK>(acc, sW + 32 * a * SM::LK, SM::LK, sST + 32 * b * SM::LK, SM::LK);
+            mma<DK, false, false, T>(acc, sW + 32 * a * SM::LK, SM::LK, sST + 32 * b * SM::LK, SM::LK);
             acc_each(acc, [&](int r, int c, float &val) { val = to_f32(sU[(32 * a + r) * SM::LB + 32 * b + c]) - val; });
             acc_to_lds_t<T>(sUT, SM::LT, 32 * a, 32 * b, acc);
             if (STORE) acc_to_global<T>((T *)p.Ut + tile * C * DV + vb, DV, 32 * a, 32 * b, C, acc);
@@ -222,17 +211,17 @@ __global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
             for (int t = wave; t < U_TILES; t += NWAVE) {
                 const int a = t / NVT, b = t % NVT;
                 f32x16 acc = zero16();
-                mma_nt<DK>(acc, sQ + 32 * a * SM::LK, SM::LK, sST + 32 * b * SM::LK, SM::LK);
-                if (a == 0) mma_nt<32>(acc, sP, SM::LT, sUT + 32 * b * SM::LT, SM::LT);
-                else mma_nt<C>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * b * SM::LT, SM::LT);
+                mma<DK, false, false, T>(acc, sQ + 32 * a * SM::LK, SM::LK, sST + 32 * b * SM::LK, SM::LK);
+                if (a == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * b * SM::LT, SM::LT);
+                else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * b * SM::LT, SM::LT);
                 acc_to_global<T>((T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * a, 32 * b, nvalid, acc);
             }
         }
-        // S += K^T Ut (Eq. 8)
+        // S += K^T Ut (Eq. 8); K^T comes straight from the row-major K tile
 #pragma unroll
         for (int s = 0; s < S_TPW; ++s) {
             const int t = wave + s * NWAVE;
-            if (t < S_TILES) mma_nt<C>(S[s], sKT + 32 * (t / NVT) * SM::LT, SM::LT, sUT + 32 * (t % NVT) * SM::LT, SM::LT);
+            if (t < S_TILES) mma<C, true, false, T>(S[s], sK + 32 * (t / NVT), SM::LK, sUT + 32 * (t % NVT) * SM::LT, SM::LT);
         }
         __syncthreads();
         publish_state();
@@ -254,17 +243,12 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr int LK = ldn<T>(DK), LB = ldn<T>(BV), LT = ldn<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LK);
-    static constexpr size_t oQT = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oWT = oQT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oDO = oWT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oDOT = oDO + align16(sizeof(T) * C * LB);
-    static constexpr size_t oPT = oDOT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t oW = oK + align16(sizeof(T) * C * LK);
+    static constexpr size_t oDO = oW + align16(sizeof(T) * C * LK);
+    static constexpr size_t oPT = oDO + align16(sizeof(T) * C * LB);
     static constexpr size_t oDST = oPT + align16(sizeof(T) * C * LT);
-    // W is staged row-major here only until it has been transposed; afterwards the same bytes
-    // hold -dUt^T (written two barriers later, read before the barrier that ends the iteration)
-    static constexpr size_t oW = oDST + align16(sizeof(T) * BV * LK);
-    static constexpr size_t oDUT = oW;
-    static constexpr size_t bytes = oW + align16(cmax(sizeof(T) * C * LK, sizeof(T) * BV * LT));
+    static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LK);
+    static constexpr size_t bytes = oDUT + align16(sizeof(T) * BV * LT);
 };
 
 template <typename T, int DK, int DV>
@@ -277,10 +261,7 @@ __global__ __launch_bounds__(NTHR) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
-    T *sQT = reinterpret_cast<T *>(smem + SM::oQT);
-    T *sWT = reinterpret_cast<T *>(smem + SM::oWT);
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
-    T *sDOT = reinterpret_cast<T *>(smem + SM::oDOT);
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
     T *sDST = reinterpret_cast<T *>(smem + SM::oDST);
     T *sDUT = reinterpret_cast<T *>(smem + SM::oDUT);
@@ -324,13 +305,10 @@ __global__ __launch_bounds__(NTHR) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
             }
         }
         __syncthreads();
-        transpose_tile<T, DK>(sQT, SM::LT, sQ, SM::LK);
-        transpose_tile<T, DK>(sWT, SM::LT, sW, SM::LK);
-        transpose_tile<T, BV>(sDOT, SM::LT, sDO, SM::LB);
         { // P^T, P = tril(Q K^T)
             const int a = wave >> 1, b = wave & 1;
             f32x16 acc = zero16();
-            if (!(a == 0 && b == 1)) mma_nt<DK>(acc, sQ + 32 * a * SM::LK, SM::LK, sK + 32 * b * SM::LK, SM::LK);
+            if (!(a == 0 && b == 1)) mma<DK, false, false, T>(acc, sQ + 32 * a * SM::LK, SM::LK, sK + 32 * b * SM::LK, SM::LK);
             acc_each(acc, [&](int r, int c, float &val) { if (32 * b + c > 32 * a + r) val = 0.f; });
             acc_to_lds_t<T>(sPT, SM::LT, 32 * a, 32 * b, acc);
         }
@@ -339,9 +317,9 @@ __global__ __launch_bounds__(NTHR) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         for (int t = wave; t < U_TILES; t += NWAVE) {
             const int a = t / NVT, b = t % NVT;
             f32x16 acc = zero16();
-            if (a == 1) mma_nt<32>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDOT + 32 * b * SM::LT + 32, SM::LT);
-            else mma_nt<C>(acc, sPT, SM::LT, sDOT + 32 * b * SM::LT, SM::LT);
-            mma_nt<DK>(acc, sK + 32 * a * SM::LK, SM::LK, sDST + 32 * b * SM::LK, SM::LK);
+            if (a == 1) mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LB + 32 * b, SM::LB);
+            else mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * b, SM::LB);
+            mma<DK, false, false, T>(acc, sK + 32 * a * SM::LK, SM::LK, sDST + 32 * b * SM::LK, SM::LK);
             acc_to_global<T>((T *)p.dUt + tile * C * DV + vb, DV, 32 * a, 32 * b, C, acc);
             acc_each(acc, [&](int, int, float &val) { val = -val; });
             acc_to_lds_t<T>(sDUT, SM::LT, 32 * a, 32 * b, acc);
@@ -353,8 +331,8 @@ __global__ __launch_bounds__(NTHR) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
             const int t = wave + s * NWAVE;
             if (t < S_TILES) {
                 const int a = t / NVT, b = t % NVT;
-                mma_nt<C>(dS[s], sQT + 32 * a * SM::LT, SM::LT, sDOT + 32 * b * SM::LT, SM::LT);
-                mma_nt<C>(dS[s], sWT + 32 * a * SM::LT, SM::LT, sDUT + 32 * b * SM::LT, SM::LT);
+                mma<C, true, true, T>(dS[s], sQ + 32 * a, SM::LK, sDO + 32 * b, SM::LB);
+                mma<C, true, false, T>(dS[s], sW + 32 * a, SM::LK, sDUT + 32 * b * SM::LT, SM::LT);
             }
         }
         __syncthreads();
@@ -377,13 +355,11 @@ template <typename T, int DK, int DV> struct DqkwSmem {
     static constexpr size_t oDO = 0;
     static constexpr size_t oUt = oDO + align16(sizeof(T) * C * LV);
     static constexpr size_t oDUt = oUt + align16(sizeof(T) * C * LV);
-    static constexpr size_t oKT = oDUt + align16(sizeof(T) * C * LV);
-    static constexpr size_t oQT = oKT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oDP = oQT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oDPT = oDP + align16(sizeof(T) * C * LT);
-    static constexpr size_t oS = oDPT + align16(sizeof(T) * C * LT); // K,Q staging, then S, then dS'
-    static constexpr size_t szS = cmax(sizeof(T) * DK * LV, 2 * align16(sizeof(T) * C * LK));
-    static constexpr size_t bytes = oS + align16(szS);
+    static constexpr size_t oK = oDUt + align16(sizeof(T) * C * LV);
+    static constexpr size_t oQ = oK + align16(sizeof(T) * C * LK);
+    static constexpr size_t oDP = oQ + align16(sizeof(T) * C * LK);
+    static constexpr size_t oS = oDP + align16(sizeof(T) * C * LT); // S, then dS'
+    static constexpr size_t bytes = oS + align16(sizeof(T) * DK * LV);
 };
 
 template <typename T, int DK, int DV>
@@ -393,13 +369,10 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
     T *sUt = reinterpret_cast<T *>(smem + SM::oUt);
     T *sDUt = reinterpret_cast<T *>(smem + SM::oDUt);
-    T *sKT = reinterpret_cast<T *>(smem + SM::oKT);
-    T *sQT = reinterpret_cast<T *>(smem + SM::oQT);
+    T *sK = reinterpret_cast<T *>(smem + SM::oK);
+    T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sDP = reinterpret_cast<T *>(smem + SM::oDP);
-    T *sDPT = reinterpret_cast<T *>(smem + SM::oDPT);
     T *sS = reinterpret_cast<T *>(smem + SM::oS);
-    T *sKn = sS;
-    T *sQn = reinterpret_cast<T *>(smem + SM::oS + align16(sizeof(T) * C * SM::LK));
 
     int n, ic;
     if (!sm.chunk(blockIdx.x, n, ic)) return;
@@ -412,44 +385,52 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
 
     load_tile<T, C, DV>(sDO, SM::LV, (const T *)p.d_o + (row0 * H + h) * DV, (long)H * DV, nvalid);
     load_tile<T, C, DV>(sUt, SM::LV, (const T *)p.Ut + tile * C * DV, DV, C);
+    load_tile<T, DK, DV>(sS, SM::LV, (const T *)p.Sc + tile * DK * DV, DV, DK);
     load_tile<T, C, DV>(sDUt, SM::LV, (const T *)p.dUt + tile * C * DV, DV, C);
-    load_tile<T, C, DK>(sKn, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-    load_tile<T, C, DK>(sQn, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+    load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+    load_tile<T, C, DK>(sQ, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
     __syncthreads();
-    transpose_tile<T, DK>(sKT, SM::LT, sKn, SM::LK);
-    transpose_tile<T, DK>(sQT, SM::LT, sQn, SM::LK);
-    { // dP = tril(dO Ut^T), both orientations
+    { // dP = tril(dO Ut^T)
         const int a = wave >> 1, b = wave & 1;
         f32x16 acc = zero16();
-        if (!(a == 0 && b == 1)) mma_nt<DV>(acc, sDO + 32 * a * SM::LV, SM::LV, sUt + 32 * b * SM::LV, SM::LV);
+        if (!(a == 0 && b == 1)) mma<DV, false, false, T>(acc, sDO + 32 * a * SM::LV, SM::LV, sUt + 32 * b * SM::LV, SM::LV);
         acc_each(acc, [&](int r, int c, float &val) { if (32 * b + c > 32 * a + r) val = 0.f; });
         acc_to_lds<T>(sDP, SM::LT, 32 * a, 32 * b, acc);
-        acc_to_lds_t<T>(sDPT, SM::LT, 32 * a, 32 * b, acc);
     }
-    __syncthreads();
-    load_tile<T, DK, DV>(sS, SM::LV, (const T *)p.Sc + tile * DK * DV, DV, DK);
-    __syncthreads();
-    for (int t = wave; t < 2 * (DK / 32); t += NWAVE) {
-        const int a = t / (DK / 32), b = t % (DK / 32);
-        f32x16 acc = zero16(); // dQ = dO S^T + dP K
-        mma_nt<DV>(acc, sDO + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
-        if (a == 0) mma_nt<32>(acc, sDP, SM::LT, sKT + 32 * b * SM::LT, SM::LT);
-        else mma_nt<C>(acc, sDP + 32 * SM::LT, SM::LT, sKT + 32 * b * SM::LT, SM::LT);
-        acc_to_global<T>((T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, acc);
-        f32x16 w = zero16(); // dW = -dUt S^T
-        mma_nt<DV>(w, sDUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
-        acc_each(w, [&](int, int, float &val) { val = -val; });
-        acc_to_global<T>((T *)p.dW + tile * C * DK, DK, 32 * a, 32 * b, C, w);
+    constexpr int KT = 2 * (DK / 32), TPW = (KT + NWAVE - 1) / NWAVE;
+    f32x16 part[TPW]; // dO S^T now, dP K after the barrier
+#pragma unroll
+    for (int s = 0; s < TPW; ++s) {
+        part[s] = zero16();
+        const int t = wave + s * NWAVE;
+        if (t < KT) {
+            const int a = t / (DK / 32), b = t % (DK / 32);
+            mma<DV, false, false, T>(part[s], sDO + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
+            f32x16 w = zero16(); // dW = -dUt S^T
+            mma<DV, false, false, T>(w, sDUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
+            acc_each(w, [&](int, int, float &val) { val = -val; });
+            acc_to_global<T>((T *)p.dW + tile * C * DK, DK, 32 * a, 32 * b, C, w);
+        }
     }
-    __syncthreads();
+    __syncthreads(); // dP visible; S no longer needed
     load_tile<T, DK, DV>(sS, SM::LV, (const T *)p.dSc + tile * DK * DV, DV, DK);
+#pragma unroll
+    for (int s = 0; s < TPW; ++s) {
+        const int t = wave + s * NWAVE;
+        if (t < KT) {
+            const int a = t / (DK / 32), b = t % (DK / 32);
+            if (a == 0) mma<32, false, true, T>(part[s], sDP, SM::LT, sK + 32 * b, SM::LK);
+            else mma<C, false, true, T>(part[s], sDP + 32 * SM::LT, SM::LT, sK + 32 * b, SM::LK);
+            acc_to_global<T>((T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, part[s]);
+        }
+    }
     __syncthreads();
-    for (int t = wave; t < 2 * (DK / 32); t += NWAVE) {
+    for (int t = wave; t < KT; t += NWAVE) {
         const int a = t / (DK / 32), b = t % (DK / 32);
         f32x16 acc = zero16(); // dK1 = dP^T Q + Ut dS'^T
-        if (a == 1) mma_nt<32>(acc, sDPT + 32 * SM::LT + 32, SM::LT, sQT + 32 * b * SM::LT + 32, SM::LT);
-        else mma_nt<C>(acc, sDPT, SM::LT, sQT + 32 * b * SM::LT, SM::LT);
-        mma_nt<DV>(acc, sUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
+        if (a == 1) mma<32, true, true, T>(acc, sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * b, SM::LK);
+        else mma<C, true, true, T>(acc, sDP, SM::LT, sQ + 32 * b, SM::LK);
+        mma<DV, false, false, T>(acc, sUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
         acc_to_global<T>((T *)p.dK1 + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
     }
 }
@@ -462,52 +443,37 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
 //   dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K;  dV = diag(beta) dVb;
 //   dbeta_i = sum_m X[m][i] dX'[m][i] + sum_j dA[i][j] G[i][j].
 template <typename T, int DK, int DV> struct WySmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LM = 52;
-    // region N: phase 1 = K, V, dW, dU row-major; phase 2 = A, X, G (fp32), inverse scratch, M1^T
-    static constexpr size_t p1K = 0;
-    static constexpr size_t p1V = p1K + align16(sizeof(T) * C * LK);
-    static constexpr size_t p1dW = p1V + align16(sizeof(T) * C * LV);
-    static constexpr size_t p1dU = p1dW + align16(sizeof(T) * C * LK);
-    static constexpr size_t p1end = p1dU + align16(sizeof(T) * C * LV);
-    static constexpr size_t p2A = 0;
-    static constexpr size_t p2X = p2A + sizeof(float) * C * LF;
-    static constexpr size_t p2G = p2X + sizeof(float) * C * LF;
-    static constexpr size_t p2M = p2G + sizeof(float) * C * LF;
-    static constexpr size_t p2M1T = p2A; // M1^T overwrites A once the inverse is done
-    static constexpr size_t p2end = p2M + align16(sizeof(float) * 16 * LM);
-    static constexpr size_t oKT = align16(cmax(p1end, p2end));
-    static constexpr size_t oDWT = oKT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oDUT = oDWT + align16(sizeof(T) * DK * LT);
-    static constexpr size_t oXn = oDUT + align16(sizeof(T) * DV * LT);
-    // in fp32 the inverse itself (same leading dimension) serves as the row-major operand copy
-    static constexpr bool kXnIsX = sizeof(T) == sizeof(float);
-    static constexpr size_t oXT = oXn + (kXnIsX ? 0 : align16(sizeof(T) * C * LT));
-    static constexpr size_t oDX = oXT + align16(sizeof(T) * C * LT); // dX, later Ah + Ah^T
-    static constexpr size_t oBeta = oDX + align16(sizeof(T) * C * LT);
+    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40;
+    static constexpr bool kXnIsX = sizeof(T) == sizeof(float); // fp32: the inverse itself is the operand
+    static constexpr size_t oK = 0;
+    static constexpr size_t oV = oK + align16(sizeof(T) * C * LK);            // V, then the fp32 A / X
+    static constexpr size_t oDW = oV + align16(cmax(sizeof(T) * C * LV, sizeof(float) * C * LF)); // dW, then dA o G (fp32)
+    static constexpr size_t oDU = oDW + align16(cmax(sizeof(T) * C * LK, sizeof(float) * C * LF)); // dU, then M1^T
+    static constexpr size_t oXn = oDU + align16(cmax(sizeof(T) * C * LV, sizeof(T) * C * LT));   // inverse operands, then X as T
+    static constexpr size_t szXn = cmax(kXnIsX ? 0 : sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO);
+    static constexpr size_t oDX = oXn + align16(szXn);                        // dX, later Ah + Ah^T
+    static constexpr size_t oM = oDX + align16(sizeof(T) * C * LT);
+    static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t oDb = oBeta + sizeof(float) * C;
-    static constexpr size_t bytes = oDb + sizeof(float) * 4 * C; // one slot per (row tile, lane half)
+    static constexpr size_t bytes = oDb + sizeof(float) * 4 * C;
 };
 
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
     using SM = WySmem<T, DK, DV>;
-    extern __shared__ __align__(16) unsigned char smem[];
-    T *sK = reinterpret_cast<T *>(smem + SM::p1K);
-    T *sV = reinterpret_cast<T *>(smem + SM::p1V);
-    T *sDW = reinterpret_cast<T *>(smem + SM::p1dW);
-    T *sDU = reinterpret_cast<T *>(smem + SM::p1dU);
-    float *sA = reinterpret_cast<float *>(smem + SM::p2A);
-    float *sX = reinterpret_cast<float *>(smem + SM::p2X);
-    float *sG = reinterpret_cast<float *>(smem + SM::p2G);
-    float *sM = reinterpret_cast<float *>(smem + SM::p2M);
-    T *sM1T = reinterpret_cast<T *>(smem + SM::p2M1T);
-    T *sKT = reinterpret_cast<T *>(smem + SM::oKT);
-    T *sDWT = reinterpret_cast<T *>(smem + SM::oDWT);
-    T *sDUT = reinterpret_cast<T *>(smem + SM::oDUT);
-    T *sXn = SM::kXnIsX ? reinterpret_cast<T *>(smem + SM::p2X) : reinterpret_cast<T *>(smem + SM::oXn);
     static_assert(!SM::kXnIsX || SM::LT == SM::LF, "fp32 operand copy aliases the inverse");
-    T *sXT = reinterpret_cast<T *>(smem + SM::oXT);
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *sK = reinterpret_cast<T *>(smem + SM::oK);
+    T *sV = reinterpret_cast<T *>(smem + SM::oV);
+    float *sX = reinterpret_cast<float *>(smem + SM::oV);
+    T *sDW = reinterpret_cast<T *>(smem + SM::oDW);
+    float *sProd = reinterpret_cast<float *>(smem + SM::oDW);
+    T *sDU = reinterpret_cast<T *>(smem + SM::oDU);
+    T *sM1T = reinterpret_cast<T *>(smem + SM::oDU);
+    T *sOp = reinterpret_cast<T *>(smem + SM::oXn);
+    T *sXn = SM::kXnIsX ? reinterpret_cast<T *>(smem + SM::oV) : reinterpret_cast<T *>(smem + SM::oXn);
     T *sDX = reinterpret_cast<T *>(smem + SM::oDX);
+    float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
 
@@ -515,7 +481,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
     if (!sm.chunk(blockIdx.x, n, ic)) return;
     int t0, len, cb;
     sm.seq(n, t0, len, cb);
-    const int h = blockIdx.y, tid = threadIdx.x, wave = tid >> 6;
+    const int h = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nvalid = min(C, len - ic * C);
     const long row0 = (long)t0 + (long)ic * C;
     const long tile = ((long)(cb + ic) * H + h);
@@ -526,51 +492,34 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
     load_tile<T, C, DV>(sV, SM::LV, (const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
     load_tile<T, C, DK>(sDW, SM::LK, (const T *)p.dW + tile * C * DK, DK, C);
     load_tile<T, C, DV>(sDU, SM::LV, (const T *)p.dUt + tile * C * DV, DV, C);
-    if (tid < C) {
-        sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
-    }
+    if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
     __syncthreads();
     f32x16 g = zero16(), dxp = zero16();
     if (!upper) {
-        mma_nt<DK>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-        mma_nt<DK>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-        mma_nt<DV>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
+        mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
+        mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
+        mma<DV, false, false, T>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
     }
-    transpose_tile<T, DK>(sKT, SM::LT, sK, SM::LK);
-    transpose_tile<T, DK>(sDWT, SM::LT, sDW, SM::LK);
-    transpose_tile<T, DV>(sDUT, SM::LT, sDU, SM::LV);
-    __syncthreads(); // phase 1 buffers are dead
-    acc_each(g, [&](int r, int c, float &val) {
-        const int i = 32 * mi + r, j = 32 * ni + c;
-        const float gij = j < i ? val : 0.f;
-        sG[i * SM::LF + j] = gij;
-        sA[i * SM::LF + j] = sBeta[i] * gij;
-    });
+    acc_each(g, [&](int r, int c, float &val) { if (32 * ni + c >= 32 * mi + r) val = 0.f; }); // strictly lower G
+    __syncthreads(); // V is dead: its bytes become the fp32 matrix
+    acc_each(g, [&](int r, int c, float &val) { sX[(32 * mi + r) * SM::LF + 32 * ni + c] = sBeta[32 * mi + r] * val; });
     __syncthreads();
-    tri_inverse_64(sA, sX, sM, SM::LF, SM::LM);
-    for (int e = tid; e < C * C; e += NTHR) {
-        const int i = e >> 6, j = e & 63;
-        const T x = from_f32<T>(sX[i * SM::LF + j]);
-        if (!SM::kXnIsX) sXn[i * SM::LT + j] = x;
-        sXT[j * SM::LT + i] = x;
-    }
-    { // dbeta part 1 (column sums of X o dX') and dX = dX' diag(beta)
-        const int lane = tid & 63, c = lane & 31;
+    tri_inverse_64_inplace<T>(sX, SM::LF, sM, sOp, SM::LO);
+    { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta), X as an operand
         float part = 0.f;
-        acc_each(dxp, [&](int r, int cc, float &val) {
-            const int i = 32 * mi + r, j = 32 * ni + cc;
+        acc_each(dxp, [&](int r, int c, float &val) {
+            const int i = 32 * mi + r, j = 32 * ni + c;
             part += sX[i * SM::LF + j] * val;
             val *= sBeta[j];
         });
-        sDb[(2 * mi + (lane >> 5)) * C + 32 * ni + c] = part; // summed in a fixed order at the end
+        sDb[(2 * mi + (lane >> 5)) * C + 32 * ni + (lane & 31)] = part; // summed in a fixed order at the end
         acc_to_lds<T>(sDX, SM::LT, 32 * mi, 32 * ni, dxp);
+        if (!SM::kXnIsX)
+            for (int e = tid; e < C * C; e += NTHR) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
     }
     __syncthreads();
-    { // M1 = dX X^T, stored transposed
-        f32x16 acc = zero16();
-        mma_nt<C>(acc, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
-        acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, acc);
-    }
+    f32x16 m1 = zero16(); // M1 = dX X^T
+    mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
     constexpr int KB_TILES = 2 * (DK / 32), KB_TPW = (KB_TILES + NWAVE - 1) / NWAVE;
     f32x16 dKb[KB_TPW];
 #pragma unroll
@@ -579,29 +528,33 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
         const int t = wave + s * NWAVE;
         if (t < KB_TILES) {
             const int a = t / (DK / 32), b = t % (DK / 32);
-            if (a == 1) mma_nt<32>(dKb[s], sXT + 32 * SM::LT + 32, SM::LT, sDWT + 32 * b * SM::LT + 32, SM::LT);
-            else mma_nt<C>(dKb[s], sXT, SM::LT, sDWT + 32 * b * SM::LT, SM::LT);
+            if (a == 1) mma<32, true, true, T>(dKb[s], sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * b, SM::LK);
+            else mma<C, true, true, T>(dKb[s], sXn, SM::LT, sDW + 32 * b, SM::LK);
         }
     }
     for (int t = wave; t < 2 * (DV / 32); t += NWAVE) { // dV = diag(beta) X^T dU
         const int a = t / (DV / 32), b = t % (DV / 32);
         f32x16 acc = zero16();
-        if (a == 1) mma_nt<32>(acc, sXT + 32 * SM::LT + 32, SM::LT, sDUT + 32 * b * SM::LT + 32, SM::LT);
-        else mma_nt<C>(acc, sXT, SM::LT, sDUT + 32 * b * SM::LT, SM::LT);
+        if (a == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * b, SM::LV);
+        else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * b, SM::LV);
         acc_each(acc, [&](int r, int, float &val) { val *= sBeta[32 * a + r]; });
         acc_to_global<T>((T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * a, 32 * b, nvalid, acc);
     }
+    __syncthreads(); // dW, dU, dX are dead
+    acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1);
     __syncthreads();
-    { // dA = -tril(X^T M1, -1); dbeta part 2 products into sG; Ah + Ah^T into sDX
+    { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah + Ah^T into sDX
         f32x16 acc = zero16();
         if (!upper) {
-            if (mi == 1) mma_nt<32>(acc, sXT + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
-            else mma_nt<C>(acc, sXT, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
+            if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
+            else mma<C, true, false, T>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
         }
-        acc_each(acc, [&](int r, int c, float &val) {
-            const int i = 32 * mi + r, j = 32 * ni + c;
-            const float da = j < i ? -val : 0.f;
-            sG[i * SM::LF + j] *= da; // dA o G, summed by rows below
+        const int l31 = lane & 31, hh = lane >> 5;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int i = 32 * mi + 8 * (e >> 2) + 4 * hh + (e & 3), j = 32 * ni + l31;
+            const float da = j < i ? -acc[e] : 0.f;
+            sProd[i * SM::LF + j] = da * g[e];
             if (!upper) {
                 if (j < i) {
                     const T ah = from_f32<T>(sBeta[i] * da);
@@ -611,7 +564,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
                     sDX[i * SM::LT + i] = from_f32<T>(0.f);
                 }
             }
-        });
+        }
     }
     __syncthreads();
 #pragma unroll
@@ -623,7 +576,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
             acc_each(dKb[s], [&](int r, int c, float &val) {
                 val = val * sBeta[32 * a + r] + to_f32(k1[(32 * a + r) * DK + 32 * b + c]);
             });
-            mma_nt<C>(dKb[s], sDX + 32 * a * SM::LT, SM::LT, sKT + 32 * b * SM::LT, SM::LT);
+            mma<C, false, true, T>(dKb[s], sDX + 32 * a * SM::LT, SM::LT, sK + 32 * b, SM::LK);
             acc_to_global<T>((T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, dKb[s]);
         }
     }
@@ -631,7 +584,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
         const int i = tid >> 2, seg = tid & 3;
         float s = 0.f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s += sG[i * SM::LF + seg * 16 + j];
+        for (int j = 0; j < 16; ++j) s += sProd[i * SM::LF + seg * 16 + j];
         s += __shfl_xor(s, 1);
         s += __shfl_xor(s, 2);
         if (seg == 0 && i < nvalid)

@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_W, off_U, off_Ut, off_dUt, off_Sc, off_dSc, off_dW, off_dK1, total;
+    size_t off_coff, off_W, off_U, off_P, off_Ut, off_dUt, off_Sc, off_dSc, off_dW, off_dK1, total;
     size_t esz;
 };
 
@@ -107,6 +107,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
     pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * ((size_t)pb.N + 1)) : 0;
     pl->off_W = o; o += tK;
     pl->off_U = o; o += tV;
+    pl->off_P = o; o += up256(tiles * kChunk * kChunk * pl->esz); // tril(Q K^T) (forward) or its transpose (backward)
     if (want_bwd) {
         pl->off_Ut = o; o += tV;
         pl->off_dUt = o; o += tV;
@@ -125,6 +126,9 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
     p->W = b + pl.off_W;
     p->U = b + pl.off_U;
+    p->P = p->PT = b + pl.off_P;
+    p->want_p = !want_bwd;
+    p->want_pt = want_bwd;
     if (want_bwd) {
         p->Ut = b + pl.off_Ut; p->dUt = b + pl.off_dUt; p->Sc = b + pl.off_Sc;
         p->dSc = b + pl.off_dSc; p->dW = b + pl.off_dW; p->dK1 = b + pl.off_dK1;

@@ -23,6 +23,8 @@ template <> struct El<float> { static constexpr int PAD = 4; static constexpr in
 template <> struct El<bf16>  { static constexpr int PAD = 16; static constexpr int VEC = 8; };
 
 template <typename T> __host__ __device__ constexpr int ldn(int cols) { return cols + El<T>::PAD; }
+// leading dimension for tiles that are only ever read with the contraction index contiguous
+template <typename T> __host__ __device__ constexpr int ldc(int cols) { return cols + 16 / (int)sizeof(T); }
 
 __device__ inline float to_f32(float x) { return x; }
 __device__ inline float to_f32(bf16 x) { return (float)x; }
@@ -128,6 +130,35 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
     }
 }
 
+// A-operand fragments of a 32-row block fetched straight from global memory (row-major, contraction
+// index contiguous) into registers: for operands that exactly one wavefront consumes, this skips LDS.
+template <typename T> struct FragOf;
+template <> struct FragOf<bf16> { typedef bf16x8 type; static constexpr int KPL = 8; };
+template <> struct FragOf<float> { typedef float type; static constexpr int KPL = 1; };
+template <typename T, int KDIM> struct AFrags {
+    static constexpr int N = KDIM / KStep<T>::value;
+    typename FragOf<T>::type f[N];
+    // base: row 0 of the block, k = 0; rows >= nvalid read as zero
+    __device__ inline void load(const T *base, long ld, int nvalid) {
+        const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
+        const T *p = base + (long)r * ld + h * FragOf<T>::KPL;
+#pragma unroll
+        for (int s = 0; s < N; ++s) {
+            typename FragOf<T>::type z = {};
+            f[s] = r < nvalid ? *reinterpret_cast<const typename FragOf<T>::type *>(p + s * KStep<T>::value) : z;
+        }
+    }
+};
+// acc += A(registers) * B(LDS) over the contraction range [KBEG, KEND)
+template <int KBEG, int KEND, bool BKS, typename T, int KDIM>
+__device__ inline void mma_ra(f32x16 &acc, const AFrags<T, KDIM> &a, const T *B, int ldb) {
+#pragma unroll
+    for (int k0 = KBEG; k0 < KEND; k0 += KStep<T>::value) {
+        const auto b = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
+        mfma32(acc, a.f[k0 / KStep<T>::value], b);
+    }
+}
+
 __device__ inline f32x16 zero16() {
     f32x16 z;
 #pragma unroll
@@ -179,6 +210,14 @@ __device__ inline void acc_to_global(T *dst, long row_stride, int row0, int col0
     });
 }
 
+// tile -> global, transposed: dst[col][row], 4 consecutive rows per store (no row masking)
+template <typename T>
+__device__ inline void acc_to_global_t(T *dst, long ld, int row0, int col0, const f32x16 &acc) {
+    acc_each4(acc, [&](int r, int c, float a, float b, float cc, float d) {
+        st4(dst + (long)(col0 + c) * ld + row0 + r, a, b, cc, d);
+    });
+}
+
 // ---------------------------------------------------------------------------------------------
 // Global -> LDS: ROWS x COLS tile, 16-byte loads, rows >= nvalid become zero.
 template <typename T, int ROWS, int COLS>
@@ -195,9 +234,9 @@ __device__ inline void load_tile(T *dst, int ld, const T *src, long row_stride, 
     }
 }
 // The same tile fetched into registers first (to be parked while LDS is busy) and stored later.
-template <typename T, int ROWS, int COLS> struct TileRegs {
-    static constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NTHR / TPR, NIT = ROWS / RPI;
-    static_assert(COLS % VEC == 0 && NTHR % TPR == 0 && ROWS % RPI == 0, "tile shape");
+template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
+    static constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NT / TPR, NIT = ROWS / RPI;
+    static_assert(COLS % VEC == 0 && NT % TPR == 0 && ROWS % RPI == 0, "tile shape");
     uint4 v[NIT];
     __device__ inline void load(const T *src, long row_stride, int nvalid) {
         const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;

@@ -86,6 +86,18 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
             sX[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
         });
     }
+    if (p.want_p || p.want_pt) { // P = tril(Q K^T) (Eq. 9), Q rows straight from global memory
+        const int mi = wave >> 1, ni = wave & 1;
+        if (!(mi == 0 && ni == 1)) {
+            AFrags<T, DK> qf;
+            qf.load((const T *)p.q + ((row0 + 32 * mi) * H + h) * DK, (long)H * DK, nvalid - 32 * mi);
+            f32x16 acc = zero16();
+            mma_ra<0, DK, false>(acc, qf, sKV + 32 * ni * SM::LD, SM::LD);
+            acc_each(acc, [&](int r, int c, float &val) { if (32 * ni + c > 32 * mi + r) val = 0.f; });
+            if (p.want_p) acc_to_global<T>((T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
+            if (p.want_pt) acc_to_global_t<T>((T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
+        }
+    }
     __syncthreads();
     tri_inverse_64_inplace<T>(sX, SM::LF, sM, sT, SM::LO);
     for (int e = tid; e < C * C; e += NTHR) { // T = X diag(beta)
@@ -113,29 +125,42 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
 }
 
 // =============================================================================================
-// k_scan_fwd: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
-// writes every chunk-initial state and Ut to the workspace instead of O.
+// The two chain-serial kernels.  One workgroup of 8 wavefronts owns one chain and BV = 64 columns
+// of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.  The operand
+// tiles of the next chunk are fetched into registers while the current chunk is computed, so global
+// latency overlaps the MFMAs.  Workgroup ids are laid out so that the v-blocks of one chain land
+// on the same XCD (ids are dealt round-robin over the 8 XCDs) and share its L2 for Q, K, W.
+constexpr int NTS = 512, NWS = 8; // threads / waves of a scan workgroup
 template <int DV> struct VBlock { static constexpr int BV = DV < 64 ? DV : 64; static constexpr int NV = DV / BV; };
 
+__device__ inline bool chain_of_block(int nchains, int nv, int &chain, int &vbi) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    vbi = slot % nv;
+    chain = (slot / nv) * 8 + xcd;
+    return chain < nchains;
+}
+__host__ inline int chain_grid(int nchains, int nv) { return ((nchains + 7) / 8) * 8 * nv; }
+
+// k_scan_fwd: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
+// writes every chunk-initial state and Ut to the workspace instead of O.
 template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr int BV = VBlock<DV>::BV;
-    static constexpr int LK = ldn<T>(DK), LB = ldn<T>(BV), LT = ldn<T>(C);
+    static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LU = ldc<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
-    static constexpr size_t oK = oQ + align16(sizeof(T) * C * LK);
+    static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
     static constexpr size_t oW = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oU = oW + align16(sizeof(T) * C * LK);
-    static constexpr size_t oST = oU + align16(sizeof(T) * C * LB);
-    static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LK);
-    static constexpr size_t oP = oUT + align16(sizeof(T) * BV * LT);
-    static constexpr size_t bytes = oP + align16(sizeof(T) * C * LT);
+    static constexpr size_t oU = oW + align16(sizeof(T) * C * LQ);
+    static constexpr size_t oST = oU + align16(sizeof(T) * C * LU);
+    static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LS);
+    static constexpr size_t bytes = oUT + align16(sizeof(T) * BV * LT);
 };
 
 template <typename T, int DK, int DV, bool STORE>
-__global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
+__global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     using SM = ScanFwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NVT = BV / 32, NKT = DK / 32;
-    constexpr int S_TILES = NKT * NVT, S_TPW = (S_TILES + NWAVE - 1) / NWAVE;
-    constexpr int U_TILES = 2 * NVT;
+    constexpr int BV = SM::BV, NV = VBlock<DV>::NV, NVT = BV / 32;
+    constexpr int S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT;
+    static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
     extern __shared__ __align__(16) unsigned char smem[];
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
@@ -143,208 +168,168 @@ __global__ __launch_bounds__(NTHR) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     T *sU = reinterpret_cast<T *>(smem + SM::oU);
     T *sST = reinterpret_cast<T *>(smem + SM::oST);
     T *sUT = reinterpret_cast<T *>(smem + SM::oUT);
-    T *sP = reinterpret_cast<T *>(smem + SM::oP);
 
-    const int vb = blockIdx.x * BV, h = blockIdx.y, n = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6;
+    int chain, vbi;
+    if (!chain_of_block(sm.N * H, NV, chain, vbi)) return;
+    const int n = chain / H, h = chain - n * H, vb = vbi * BV;
+    const int wave = threadIdx.x >> 6;
     int t0, len, cb;
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
-    const long chain = (long)n * H + h;
+    // wave -> tiles: state tile (sa, sb) = rows 32*sa of d_k, cols 32*sb of the v-block;
+    // waves 0..U_TILES-1 build Ut tile (ua, ub); waves 4..4+U_TILES-1 build the same tile of O
+    const int sa = wave / NVT, sb = wave % NVT;
+    const bool has_s = wave < S_TILES;
+    const bool does_u = wave < U_TILES, does_o = !STORE && wave >= 4 && wave < 4 + U_TILES;
+    const int ut = does_o ? wave - 4 : wave, ua = ut / NVT, ub = ut % NVT;
 
-    f32x16 S[S_TPW];
-#pragma unroll
-    for (int s = 0; s < S_TPW; ++s) {
-        S[s] = zero16();
-        const int t = wave + s * NWAVE;
-        if (t < S_TILES && p.S0) {
-            const int a = t / NVT, b = t % NVT;
-            const float *src = p.S0 + chain * DK * DV + vb;
-            acc_each(S[s], [&](int r, int c, float &val) { val = src[(long)(32 * a + r) * DV + 32 * b + c]; });
-        }
+    f32x16 S = zero16();
+    if (has_s && p.S0) {
+        const float *src = p.S0 + (long)chain * DK * DV + vb;
+        acc_each(S, [&](int r, int c, float &val) { val = src[(long)(32 * sa + r) * DV + 32 * sb + c]; });
     }
-    auto publish_state = [&]() { // S -> sST (transposed, operand precision)
-#pragma unroll
-        for (int s = 0; s < S_TPW; ++s) {
-            const int t = wave + s * NWAVE;
-            if (t < S_TILES) acc_to_lds_t<T>(sST, SM::LK, 32 * (t / NVT), 32 * (t % NVT), S[s]);
-        }
+
+    TileRegs<T, C, DK, NTS> rq, rk, rw;
+    TileRegs<T, C, BV, NTS> ru;
+    AFrags<T, C> rp; // rows of P = tril(Q K^T) for the waves that finish an output tile
+    auto prefetch = [&](int ic) {
+        const int nvalid = min(C, len - ic * C);
+        const long row0 = (long)t0 + (long)ic * C;
+        const long tile = ((long)(cb + ic) * H + h);
+        if (!STORE) rq.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        rk.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        rw.load((const T *)p.W + tile * C * DK, DK, C);
+        ru.load((const T *)p.U + tile * C * DV + vb, DV, C);
+        if (does_o) rp.load((const T *)p.P + tile * C * C + 32 * ua * C, C, C);
     };
-    publish_state();
+    if (nchunks > 0) prefetch(0);
 
     for (int ic = 0; ic < nchunks; ++ic) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        if (!STORE) load_tile<T, C, DK>(sQ, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        load_tile<T, C, DK>(sW, SM::LK, (const T *)p.W + tile * C * DK, DK, C);
-        load_tile<T, C, BV>(sU, SM::LB, (const T *)p.U + tile * C * DV + vb, DV, C);
-        if (STORE) { // chunk-initial state for the chunk-parallel backward kernel
-            T *dst = (T *)p.Sc + tile * DK * DV + vb;
-#pragma unroll
-            for (int s = 0; s < S_TPW; ++s) {
-                const int t = wave + s * NWAVE;
-                if (t < S_TILES) acc_to_global<T>(dst, DV, 32 * (t / NVT), 32 * (t % NVT), DK, S[s]);
-            }
+        if (!STORE) rq.store(sQ, SM::LQ);
+        rk.store(sK, SM::LK);
+        rw.store(sW, SM::LQ);
+        ru.store(sU, SM::LU);
+        const AFrags<T, C> pc = rp;
+        if (has_s) {
+            if (STORE) acc_to_global<T>((T *)p.Sc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
+            acc_to_lds_t<T>(sST, SM::LS, 32 * sa, 32 * sb, S);
         }
         __syncthreads();
-        if (!STORE) { // P = tril(Q K^T), diagonal included (Eq. 9)
-            const int a = wave >> 1, b = wave & 1;
-            f32x16 acc = zero16();
-            if (!(a == 0 && b == 1)) mma<DK, false, false, T>(acc, sQ + 32 * a * SM::LK, SM::LK, sK + 32 * b * SM::LK, SM::LK);
-            acc_each(acc, [&](int r, int c, float &val) {
-                sP[(32 * a + r) * SM::LT + 32 * b + c] = from_f32<T>((32 * b + c <= 32 * a + r) ? val : 0.f);
-            });
-        }
-        // Ut = U - W S  (inner term of Eq. 8-9)
-        for (int t = wave; t < U_TILES; t += NWAVE) {
-            const int a = t / NVT, b = t % NVT;
-            f32x16 acc = zero16();
-            mma<DK, false, false, T>(acc, sW + 32 * a * SM::LK, SM::LK, sST + 32 * b * SM::LK, SM::LK);
-            acc_each(acc, [&](int r, int c, float &val) { val = to_f32(sU[(32 * a + r) * SM::LB + 32 * b + c]) - val; });
-            acc_to_lds_t<T>(sUT, SM::LT, 32 * a, 32 * b, acc);
-            if (STORE) acc_to_global<T>((T *)p.Ut + tile * C * DV + vb, DV, 32 * a, 32 * b, C, acc);
+        if (ic + 1 < nchunks) prefetch(ic + 1);
+        f32x16 acc = zero16();
+        if (does_u) { // Ut = U - W S (inner term of Eq. 8-9)
+            mma<DK, false, false, T>(acc, sW + 32 * ua * SM::LQ, SM::LQ, sST + 32 * ub * SM::LS, SM::LS);
+            acc_each(acc, [&](int r, int c, float &val) { val = to_f32(sU[(32 * ua + r) * SM::LU + 32 * ub + c]) - val; });
+            acc_to_lds_t<T>(sUT, SM::LT, 32 * ua, 32 * ub, acc);
+            if (STORE) acc_to_global<T>((T *)p.Ut + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
+        } else if (does_o) { // Q S
+            mma<DK, false, false, T>(acc, sQ + 32 * ua * SM::LQ, SM::LQ, sST + 32 * ub * SM::LS, SM::LS);
         }
         __syncthreads();
-        if (!STORE) { // O = Q S + P Ut (Eq. 9)
-            for (int t = wave; t < U_TILES; t += NWAVE) {
-                const int a = t / NVT, b = t % NVT;
-                f32x16 acc = zero16();
-                mma<DK, false, false, T>(acc, sQ + 32 * a * SM::LK, SM::LK, sST + 32 * b * SM::LK, SM::LK);
-                if (a == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * b * SM::LT, SM::LT);
-                else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * b * SM::LT, SM::LT);
-                acc_to_global<T>((T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * a, 32 * b, nvalid, acc);
-            }
+        if (does_o) { // O = Q S + P Ut (Eq. 9)
+            if (ua == 0) mma_ra<0, 32, false>(acc, pc, sUT + 32 * ub * SM::LT, SM::LT);
+            else mma_ra<0, C, false>(acc, pc, sUT + 32 * ub * SM::LT, SM::LT);
+            acc_to_global<T>((T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * ua, 32 * ub, nvalid, acc);
         }
-        // S += K^T Ut (Eq. 8); K^T comes straight from the row-major K tile
-#pragma unroll
-        for (int s = 0; s < S_TPW; ++s) {
-            const int t = wave + s * NWAVE;
-            if (t < S_TILES) mma<C, true, false, T>(S[s], sK + 32 * (t / NVT), SM::LK, sUT + 32 * (t % NVT) * SM::LT, SM::LT);
-        }
+        if (has_s) mma<C, true, false, T>(S, sK + 32 * sa, SM::LK, sUT + 32 * sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         __syncthreads();
-        publish_state();
     }
-    if (!STORE && p.ST) {
-        float *dst = p.ST + chain * DK * DV + vb;
-#pragma unroll
-        for (int s = 0; s < S_TPW; ++s) {
-            const int t = wave + s * NWAVE;
-            if (t < S_TILES) acc_to_global<float>(dst, DV, 32 * (t / NVT), 32 * (t % NVT), DK, S[s]);
-        }
-    }
+    if (!STORE && p.ST && has_s)
+        acc_to_global<float>(p.ST + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
 }
 
-// =============================================================================================
-// k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state).
+// k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
+//   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
 template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr int BV = VBlock<DV>::BV;
-    static constexpr int LK = ldn<T>(DK), LB = ldn<T>(BV), LT = ldn<T>(C);
+    static constexpr int LQ = ldn<T>(DK), LK = ldc<T>(DK), LD = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
-    static constexpr size_t oK = oQ + align16(sizeof(T) * C * LK);
+    static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
     static constexpr size_t oW = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oDO = oW + align16(sizeof(T) * C * LK);
-    static constexpr size_t oPT = oDO + align16(sizeof(T) * C * LB);
-    static constexpr size_t oDST = oPT + align16(sizeof(T) * C * LT);
-    static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LK);
+    static constexpr size_t oDO = oW + align16(sizeof(T) * C * LQ);
+    static constexpr size_t oDST = oDO + align16(sizeof(T) * C * LD);
+    static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LS);
     static constexpr size_t bytes = oDUT + align16(sizeof(T) * BV * LT);
 };
 
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTHR) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
+__global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     using SM = ScanBwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NVT = BV / 32, NKT = DK / 32;
-    constexpr int S_TILES = NKT * NVT, S_TPW = (S_TILES + NWAVE - 1) / NWAVE;
-    constexpr int U_TILES = 2 * NVT;
+    constexpr int BV = SM::BV, NV = VBlock<DV>::NV, NVT = BV / 32;
+    constexpr int S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT;
+    static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
     extern __shared__ __align__(16) unsigned char smem[];
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
-    T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
     T *sDST = reinterpret_cast<T *>(smem + SM::oDST);
     T *sDUT = reinterpret_cast<T *>(smem + SM::oDUT);
 
-    const int vb = blockIdx.x * BV, h = blockIdx.y, n = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6;
+    int chain, vbi;
+    if (!chain_of_block(sm.N * H, NV, chain, vbi)) return;
+    const int n = chain / H, h = chain - n * H, vb = vbi * BV;
+    const int wave = threadIdx.x >> 6;
     int t0, len, cb;
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
-    const long chain = (long)n * H + h;
+    const int sa = wave / NVT, sb = wave % NVT;
+    const bool has_s = wave < S_TILES, does_u = wave < U_TILES;
+    const int ua = wave / NVT, ub = wave % NVT;
 
-    f32x16 dS[S_TPW];
-#pragma unroll
-    for (int s = 0; s < S_TPW; ++s) {
-        dS[s] = zero16();
-        const int t = wave + s * NWAVE;
-        if (t < S_TILES && p.dST) {
-            const int a = t / NVT, b = t % NVT;
-            const float *src = p.dST + chain * DK * DV + vb;
-            acc_each(dS[s], [&](int r, int c, float &val) { val = src[(long)(32 * a + r) * DV + 32 * b + c]; });
-        }
+    f32x16 dS = zero16();
+    if (has_s && p.dST) {
+        const float *src = p.dST + (long)chain * DK * DV + vb;
+        acc_each(dS, [&](int r, int c, float &val) { val = src[(long)(32 * sa + r) * DV + 32 * sb + c]; });
     }
 
-    for (int ic = nchunks - 1; ic >= 0; --ic) {
+    TileRegs<T, C, DK, NTS> rq, rk, rw;
+    TileRegs<T, C, BV, NTS> rdo;
+    AFrags<T, C> rpt; // rows of P^T for the waves that build dUt
+    auto prefetch = [&](int ic) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        load_tile<T, C, DK>(sQ, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        load_tile<T, C, DK>(sW, SM::LK, (const T *)p.W + tile * C * DK, DK, C);
-        load_tile<T, C, BV>(sDO, SM::LB, (const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
-        { // dS' (gradient w.r.t. the state after this chunk): to the workspace and, transposed, to LDS
-            T *dst = (T *)p.dSc + tile * DK * DV + vb;
-#pragma unroll
-            for (int s = 0; s < S_TPW; ++s) {
-                const int t = wave + s * NWAVE;
-                if (t < S_TILES) {
-                    acc_to_global<T>(dst, DV, 32 * (t / NVT), 32 * (t % NVT), DK, dS[s]);
-                    acc_to_lds_t<T>(sDST, SM::LK, 32 * (t / NVT), 32 * (t % NVT), dS[s]);
-                }
-            }
+        rq.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        rk.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        rw.load((const T *)p.W + tile * C * DK, DK, C);
+        rdo.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
+        if (does_u) rpt.load((const T *)p.PT + tile * C * C + 32 * ua * C, C, C);
+    };
+    if (nchunks > 0) prefetch(nchunks - 1);
+
+    for (int ic = nchunks - 1; ic >= 0; --ic) {
+        const long tile = ((long)(cb + ic) * H + h);
+        rq.store(sQ, SM::LQ);
+        rk.store(sK, SM::LK);
+        rw.store(sW, SM::LQ);
+        rdo.store(sDO, SM::LD);
+        const AFrags<T, C> ptc = rpt;
+        if (has_s) { // dS' (gradient w.r.t. the state after this chunk)
+            acc_to_global<T>((T *)p.dSc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
+            acc_to_lds_t<T>(sDST, SM::LS, 32 * sa, 32 * sb, dS);
         }
         __syncthreads();
-        { // P^T, P = tril(Q K^T)
-            const int a = wave >> 1, b = wave & 1;
+        if (ic > 0) prefetch(ic - 1);
+        if (does_u) { // dUt tile (ua, ub); P^T is upper triangular
             f32x16 acc = zero16();
-            if (!(a == 0 && b == 1)) mma<DK, false, false, T>(acc, sQ + 32 * a * SM::LK, SM::LK, sK + 32 * b * SM::LK, SM::LK);
-            acc_each(acc, [&](int r, int c, float &val) { if (32 * b + c > 32 * a + r) val = 0.f; });
-            acc_to_lds_t<T>(sPT, SM::LT, 32 * a, 32 * b, acc);
-        }
-        __syncthreads();
-        // dUt = P^T dO + K dS'; kept negated in LDS for the state update below
-        for (int t = wave; t < U_TILES; t += NWAVE) {
-            const int a = t / NVT, b = t % NVT;
-            f32x16 acc = zero16();
-            if (a == 1) mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LB + 32 * b, SM::LB);
-            else mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * b, SM::LB);
-            mma<DK, false, false, T>(acc, sK + 32 * a * SM::LK, SM::LK, sDST + 32 * b * SM::LK, SM::LK);
-            acc_to_global<T>((T *)p.dUt + tile * C * DV + vb, DV, 32 * a, 32 * b, C, acc);
+            if (ua == 0) mma_ra<0, C, true>(acc, ptc, sDO + 32 * ub, SM::LD);
+            else mma_ra<32, C, true>(acc, ptc, sDO + 32 * ub, SM::LD);
+            mma<DK, false, false, T>(acc, sK + 32 * ua * SM::LK, SM::LK, sDST + 32 * ub * SM::LS, SM::LS);
+            acc_to_global<T>((T *)p.dUt + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
             acc_each(acc, [&](int, int, float &val) { val = -val; });
-            acc_to_lds_t<T>(sDUT, SM::LT, 32 * a, 32 * b, acc);
+            acc_to_lds_t<T>(sDUT, SM::LT, 32 * ua, 32 * ub, acc);
         }
+        if (has_s) mma<C, true, true, T>(dS, sQ + 32 * sa, SM::LQ, sDO + 32 * sb, SM::LD); // + Q^T dO
         __syncthreads();
-        // dS = dS' + Q^T dO - W^T dUt
-#pragma unroll
-        for (int s = 0; s < S_TPW; ++s) {
-            const int t = wave + s * NWAVE;
-            if (t < S_TILES) {
-                const int a = t / NVT, b = t % NVT;
-                mma<C, true, true, T>(dS[s], sQ + 32 * a, SM::LK, sDO + 32 * b, SM::LB);
-                mma<C, true, false, T>(dS[s], sW + 32 * a, SM::LK, sDUT + 32 * b * SM::LT, SM::LT);
-            }
-        }
+        if (has_s) mma<C, true, false, T>(dS, sW + 32 * sa, SM::LQ, sDUT + 32 * sb * SM::LT, SM::LT); // - W^T dUt
         __syncthreads();
     }
-    if (p.dS0) {
-        float *dst = p.dS0 + chain * DK * DV + vb;
-#pragma unroll
-        for (int s = 0; s < S_TPW; ++s) {
-            const int t = wave + s * NWAVE;
-            if (t < S_TILES) acc_to_global<float>(dst, DV, 32 * (t / NVT), 32 * (t % NVT), DK, dS[s]);
-        }
-    }
+    if (p.dS0 && has_s)
+        acc_to_global<float>(p.dS0 + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
 }
 
 // =============================================================================================

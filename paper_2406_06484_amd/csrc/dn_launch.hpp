@@ -10,11 +10,12 @@ template <typename K> static inline int set_lds(K kernel, size_t bytes) {
     return (int)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-#define DN_LAUNCH(kernel, grid, lds, ...)                                              \
+#define DN_LAUNCH(kernel, grid, lds, ...) DN_LAUNCH_NT(kernel, grid, NTHR, lds, __VA_ARGS__)
+#define DN_LAUNCH_NT(kernel, grid, nthreads, lds, ...)                                 \
     do {                                                                               \
         if (int e_ = set_lds(kernel, lds)) return e_;                                  \
         prof_begin(#kernel, pb.stream);                                                \
-        hipLaunchKernelGGL(kernel, grid, dim3(NTHR), lds, pb.stream, __VA_ARGS__);     \
+        hipLaunchKernelGGL(kernel, grid, dim3(nthreads), lds, pb.stream, __VA_ARGS__); \
         prof_end(pb.stream);                                                           \
         if (int e_ = (int)hipGetLastError()) return e_;                                \
     } while (0)
@@ -51,9 +52,9 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     if (pb.N == 0 || pb.chunks_ub == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(VBlock<DV>::NV, pb.H, pb.N);
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<DV>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    DN_LAUNCH((k_scan_fwd<T, DK, DV, false>), gchain, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;
 }
 
@@ -61,10 +62,10 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (pb.N == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(VBlock<DV>::NV, pb.H, pb.N);
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<DV>::NV));
     if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    if (pb.chunks_ub) DN_LAUNCH((k_scan_fwd<T, DK, DV, true>), gchain, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    DN_LAUNCH((k_scan_bwd<T, DK, DV>), gchain, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if (pb.chunks_ub) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH_NT((k_scan_bwd<T, DK, DV>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     if (pb.chunks_ub) DN_LAUNCH((k_bwd_dqkw<T, DK, DV>), gchunk, (DqkwSmem<T, DK, DV>::bytes), sm, pb.H, p);
     if (pb.chunks_ub) DN_LAUNCH((k_bwd_wy<T, DK, DV>), gchunk, (WySmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;

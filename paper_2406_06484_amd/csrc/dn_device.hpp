@@ -17,6 +17,13 @@ typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding
+// global load and store of the wave (it is a full workgroup fence), which would serialise the
+// register prefetch of the next chunk and the output stores with the barrier.  Every barrier in
+// these kernels guards LDS contents only; nothing written to global memory is read back by the
+// same launch.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Per-element-type constants: LDS row padding (elements) and elements per 16 bytes.
 template <typename T> struct El;
 template <> struct El<float> { static constexpr int PAD = 4; static constexpr int VEC = 4; };
@@ -210,6 +217,43 @@ __device__ inline void acc_to_global(T *dst, long row_stride, int row0, int col0
     });
 }
 
+// Wave-private LDS staging for coalesced tile stores.  A 32 x 32 accumulator tile is first laid
+// out row-major in LDS (cheap narrow LDS writes), then each lane moves 16 bytes at a time to global
+// memory, so a store instruction covers whole 64-byte (bf16) or 128-byte (fp32) row segments.
+// Scattered 2-byte global stores straight from the accumulator layout cost ~100 cycles apiece.
+template <typename T> struct Stage {
+    static constexpr int LD = 32 + 16 / (int)sizeof(T);       // row stride in elements, 16-byte aligned
+    static constexpr int ELEMS = 32 * LD;                      // per wave
+    static constexpr int SEGS = 32 * (int)sizeof(T) / 16;      // 16-byte segments per row
+};
+__device__ inline void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+template <typename T>
+__device__ inline void stage_flush(const T *stage, T *dst, long row_stride, int row0, int col0, int nvalid) {
+    const int lane = threadIdx.x & 63;
+    wave_lds_fence();
+#pragma unroll
+    for (int it = 0; it < 32 * Stage<T>::SEGS / 64; ++it) {
+        const int idx = it * 64 + lane, r = idx / Stage<T>::SEGS, sg = idx % Stage<T>::SEGS;
+        if (row0 + r < nvalid)
+            *reinterpret_cast<uint4 *>(dst + (long)(row0 + r) * row_stride + col0 + sg * El<T>::VEC) =
+                *reinterpret_cast<const uint4 *>(stage + r * Stage<T>::LD + sg * El<T>::VEC);
+    }
+    wave_lds_fence(); // the staging tile may be rewritten right away
+}
+// dst[row0 + r][col0 + c] = acc(r, c), rows >= nvalid dropped; `stage` is this wave's staging tile
+template <typename T>
+__device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc) {
+    acc_to_lds<T>(stage, Stage<T>::LD, 0, 0, acc);
+    stage_flush<T>(stage, dst, row_stride, row0, col0, nvalid);
+}
+// dst[col0 + c][row0 + r] = acc(r, c)  (transposed tile), no masking
+template <typename T>
+__device__ inline void acc_store_t(T *stage, T *dst, long row_stride, int row0, int col0, const f32x16 &acc) {
+    acc_to_lds_t<T>(stage, Stage<T>::LD, 0, 0, acc);
+    stage_flush<T>(stage, dst, row_stride, col0, row0, 1 << 30);
+}
+
 // tile -> global, transposed: dst[col][row], 4 consecutive rows per store (no row masking)
 template <typename T>
 __device__ inline void acc_to_global_t(T *dst, long ld, int row0, int col0, const f32x16 &acc) {
@@ -289,7 +333,7 @@ __device__ inline void transpose_tile(T *dstT, int ldT, const T *src, int ld) {
 __device__ inline void tri_inverse_64(const float *sA, float *sX, float *sM, int ld, int ldm) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     for (int e = tid; e < C * C; e += NTHR) sX[(e >> 6) * ld + (e & 63)] = 0.f;
-    __syncthreads();
+    lds_barrier();
     if (lane < 16) {
         const int b = wave * 16, j = lane;
         float x[16];
@@ -303,7 +347,7 @@ __device__ inline void tri_inverse_64(const float *sA, float *sX, float *sM, int
 #pragma unroll
         for (int i = 0; i < 16; ++i) sX[(b + i) * ld + b + j] = x[i];
     }
-    __syncthreads();
+    lds_barrier();
     const int i = tid >> 4, j = tid & 15;
     for (int a = 1; a < 4; ++a) {
         for (int b = 0; b < a; ++b) {
@@ -313,14 +357,14 @@ __device__ inline void tri_inverse_64(const float *sA, float *sX, float *sM, int
                 for (int m = 0; m < 16; ++m) s += sA[(16 * a + i) * ld + 16 * c + m] * sX[(16 * c + m) * ld + 16 * b + j];
             sM[i * ldm + 16 * b + j] = s;
         }
-        __syncthreads();
+        lds_barrier();
         for (int b = 0; b < a; ++b) {
             float s = 0.f;
 #pragma unroll
             for (int m = 0; m < 16; ++m) s += sX[(16 * a + i) * ld + 16 * a + m] * sM[m * ldm + 16 * b + j];
             sX[(16 * a + i) * ld + 16 * b + j] = -s;
         }
-        __syncthreads();
+        lds_barrier();
     }
 }
 
@@ -347,19 +391,19 @@ __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *s
 #pragma unroll
         for (int i = 0; i < 8; ++i) sX[(b + i) * ld + b + j] = x[i];
     }
-    __syncthreads();
+    lds_barrier();
     { // 8 -> 16: four merges, one output element per thread
         const int m = tid >> 6, i = (tid >> 3) & 7, j = tid & 7, r0 = 16 * m + 8, c0 = 16 * m;
         float s = 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + c0 + k] * sX[(c0 + k) * ld + c0 + j];
         sM[tid] = s;
-        __syncthreads();
+        lds_barrier();
         s = 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + r0 + k] * sM[(m << 6) + k * 8 + j];
         sX[(r0 + i) * ld + c0 + j] = -s;
-        __syncthreads();
+        lds_barrier();
     }
     { // 16 -> 32: two merges, two output elements per thread
         const int m = tid >> 7, i = (tid >> 3) & 15, j = 2 * (tid & 7), r0 = 32 * m + 16, c0 = 32 * m;
@@ -372,7 +416,7 @@ __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *s
         }
         sM[(m << 8) + i * 16 + j] = s0;
         sM[(m << 8) + i * 16 + j + 1] = s1;
-        __syncthreads();
+        lds_barrier();
         s0 = s1 = 0.f;
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
@@ -382,7 +426,7 @@ __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *s
         }
         sX[(r0 + i) * ld + c0 + j] = -s0;
         sX[(r0 + i) * ld + c0 + j + 1] = -s1;
-        __syncthreads();
+        lds_barrier();
     }
     // 32 -> 64 on the matrix cores: operands A21, X11^T, X22 and (later) M^T, each 32 x LO
     T *oA = sOp, *oX11T = sOp + 32 * LO, *oX22 = sOp + 64 * LO, *oMT = sOp + 96 * LO;
@@ -392,19 +436,19 @@ __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *s
         oX11T[k * LO + i] = from_f32<T>(sX[i * ld + k]);
         oX22[i * LO + k] = from_f32<T>(sX[(32 + i) * ld + 32 + k]);
     }
-    __syncthreads();
+    lds_barrier();
     f32x16 acc = zero16();
     if (wave == 0) {
         mma<32, false, false, T>(acc, oA, LO, oX11T, LO); // M = A21 X11
         acc_to_lds_t<T>(oMT, LO, 0, 0, acc);
     }
-    __syncthreads();
+    lds_barrier();
     if (wave == 0) {
         acc = zero16();
         mma<32, false, false, T>(acc, oX22, LO, oMT, LO); // X22 M
         acc_each(acc, [&](int r, int c, float &v) { sX[(32 + r) * ld + c] = -v; });
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 } // namespace dn

@@ -50,13 +50,16 @@ template <typename T, int DK, int DV> struct PrepSmem {
     static constexpr size_t szT = cmax(sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO);
     static constexpr size_t oM = oT + align16(szT);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
-    static constexpr size_t bytes = oBeta + sizeof(float) * C;
+    static constexpr size_t oStage = align16(oBeta + sizeof(float) * C); // per-wave output staging tiles
+    static constexpr size_t bytes = oStage + 4 * cmax(sizeof(T) * Stage<T>::ELEMS, 0);
 };
 
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     using SM = PrepSmem<T, DK, DV>;
     extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (sizeof(T) * Stage<T>::ELEMS);
+    T *stg = reinterpret_cast<T *>(stg_raw);
     T *sKV = reinterpret_cast<T *>(smem + SM::oKV);
     float *sX = reinterpret_cast<float *>(smem + SM::oX);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     vregs.load((const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
     load_tile<T, C, DK>(sKV, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
-    __syncthreads();
+    lds_barrier();
     { // A = tril(diag(beta) K K^T, -1), Eq. 10
         const int mi = wave >> 1, ni = wave & 1;
         f32x16 g = zero16();
@@ -94,33 +97,33 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
             f32x16 acc = zero16();
             mma_ra<0, DK, false>(acc, qf, sKV + 32 * ni * SM::LD, SM::LD);
             acc_each(acc, [&](int r, int c, float &val) { if (32 * ni + c > 32 * mi + r) val = 0.f; });
-            if (p.want_p) acc_to_global<T>((T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
-            if (p.want_pt) acc_to_global_t<T>((T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
+            if (p.want_p) acc_store<T>(stg, (T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
+            if (p.want_pt) acc_store_t<T>(stg, (T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
         }
     }
-    __syncthreads();
+    lds_barrier();
     tri_inverse_64_inplace<T>(sX, SM::LF, sM, sT, SM::LO);
     for (int e = tid; e < C * C; e += NTHR) { // T = X diag(beta)
         const int i = e >> 6, j = e & 63;
         sT[i * SM::LT + j] = from_f32<T>(sX[i * SM::LF + j] * sBeta[j]);
     }
-    __syncthreads();
+    lds_barrier();
     for (int t = wave; t < 2 * (DK / 32); t += NWAVE) { // W = T K, Eq. 11 (K read through the transposing path)
         const int a = t / (DK / 32), b = t % (DK / 32);
         f32x16 acc = zero16();
         if (a == 0) mma<32, false, true, T>(acc, sT, SM::LT, sKV + 32 * b, SM::LD);
         else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sKV + 32 * b, SM::LD);
-        acc_to_global<T>((T *)p.W + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
+        acc_store<T>(stg, (T *)p.W + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
     }
-    __syncthreads();
+    lds_barrier();
     vregs.store(sKV, SM::LD);
-    __syncthreads();
+    lds_barrier();
     for (int t = wave; t < 2 * (DV / 32); t += NWAVE) { // U = T V
         const int a = t / (DV / 32), b = t % (DV / 32);
         f32x16 acc = zero16();
         if (a == 0) mma<32, false, true, T>(acc, sT, SM::LT, sKV + 32 * b, SM::LD);
         else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sKV + 32 * b, SM::LD);
-        acc_to_global<T>((T *)p.U + tile * C * DV, DV, 32 * a, 32 * b, C, acc);
+        acc_store<T>(stg, (T *)p.U + tile * C * DV, DV, 32 * a, 32 * b, C, acc);
     }
 }
 
@@ -152,7 +155,8 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oU = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oST = oU + align16(sizeof(T) * C * LU);
     static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t bytes = oUT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t oStage = align16(oUT + align16(sizeof(T) * BV * LT)); // per-wave output staging tiles
+    static constexpr size_t bytes = oStage + 8 * cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
 };
 
 template <typename T, int DK, int DV, bool STORE>
@@ -162,6 +166,9 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     constexpr int S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT;
     static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
     extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS));
+    T *stg = reinterpret_cast<T *>(stg_raw);
+    float *stgf = reinterpret_cast<float *>(stg_raw);
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
@@ -214,31 +221,31 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         ru.store(sU, SM::LU);
         const AFrags<T, C> pc = rp;
         if (has_s) {
-            if (STORE) acc_to_global<T>((T *)p.Sc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
+            if (STORE) acc_store<T>(stg, (T *)p.Sc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
             acc_to_lds_t<T>(sST, SM::LS, 32 * sa, 32 * sb, S);
         }
-        __syncthreads();
+        lds_barrier();
         if (ic + 1 < nchunks) prefetch(ic + 1);
         f32x16 acc = zero16();
         if (does_u) { // Ut = U - W S (inner term of Eq. 8-9)
             mma<DK, false, false, T>(acc, sW + 32 * ua * SM::LQ, SM::LQ, sST + 32 * ub * SM::LS, SM::LS);
             acc_each(acc, [&](int r, int c, float &val) { val = to_f32(sU[(32 * ua + r) * SM::LU + 32 * ub + c]) - val; });
             acc_to_lds_t<T>(sUT, SM::LT, 32 * ua, 32 * ub, acc);
-            if (STORE) acc_to_global<T>((T *)p.Ut + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
+            if (STORE) acc_store<T>(stg, (T *)p.Ut + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
         } else if (does_o) { // Q S
             mma<DK, false, false, T>(acc, sQ + 32 * ua * SM::LQ, SM::LQ, sST + 32 * ub * SM::LS, SM::LS);
         }
-        __syncthreads();
+        lds_barrier();
         if (does_o) { // O = Q S + P Ut (Eq. 9)
             if (ua == 0) mma_ra<0, 32, false>(acc, pc, sUT + 32 * ub * SM::LT, SM::LT);
             else mma_ra<0, C, false>(acc, pc, sUT + 32 * ub * SM::LT, SM::LT);
-            acc_to_global<T>((T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * ua, 32 * ub, nvalid, acc);
+            acc_store<T>(stg, (T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * ua, 32 * ub, nvalid, acc);
         }
         if (has_s) mma<C, true, false, T>(S, sK + 32 * sa, SM::LK, sUT + 32 * sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
-        __syncthreads();
+        lds_barrier();
     }
     if (!STORE && p.ST && has_s)
-        acc_to_global<float>(p.ST + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
+        acc_store<float>(stgf, p.ST + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
 }
 
 // k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
@@ -252,7 +259,8 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t oDO = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oDST = oDO + align16(sizeof(T) * C * LD);
     static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t bytes = oDUT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t oStage = align16(oDUT + align16(sizeof(T) * BV * LT)); // per-wave output staging tiles
+    static constexpr size_t bytes = oStage + 8 * cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
 };
 
 template <typename T, int DK, int DV>
@@ -262,6 +270,9 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     constexpr int S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT;
     static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
     extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS));
+    T *stg = reinterpret_cast<T *>(stg_raw);
+    float *stgf = reinterpret_cast<float *>(stg_raw);
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
@@ -309,27 +320,27 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         rdo.store(sDO, SM::LD);
         const AFrags<T, C> ptc = rpt;
         if (has_s) { // dS' (gradient w.r.t. the state after this chunk)
-            acc_to_global<T>((T *)p.dSc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
+            acc_store<T>(stg, (T *)p.dSc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
             acc_to_lds_t<T>(sDST, SM::LS, 32 * sa, 32 * sb, dS);
         }
-        __syncthreads();
+        lds_barrier();
         if (ic > 0) prefetch(ic - 1);
         if (does_u) { // dUt tile (ua, ub); P^T is upper triangular
             f32x16 acc = zero16();
             if (ua == 0) mma_ra<0, C, true>(acc, ptc, sDO + 32 * ub, SM::LD);
             else mma_ra<32, C, true>(acc, ptc, sDO + 32 * ub, SM::LD);
             mma<DK, false, false, T>(acc, sK + 32 * ua * SM::LK, SM::LK, sDST + 32 * ub * SM::LS, SM::LS);
-            acc_to_global<T>((T *)p.dUt + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
+            acc_store<T>(stg, (T *)p.dUt + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
             acc_each(acc, [&](int, int, float &val) { val = -val; });
             acc_to_lds_t<T>(sDUT, SM::LT, 32 * ua, 32 * ub, acc);
         }
         if (has_s) mma<C, true, true, T>(dS, sQ + 32 * sa, SM::LQ, sDO + 32 * sb, SM::LD); // + Q^T dO
-        __syncthreads();
+        lds_barrier();
         if (has_s) mma<C, true, false, T>(dS, sW + 32 * sa, SM::LQ, sDUT + 32 * sb * SM::LT, SM::LT); // - W^T dUt
-        __syncthreads();
+        lds_barrier();
     }
     if (p.dS0 && has_s)
-        acc_to_global<float>(p.dS0 + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
+        acc_store<float>(stgf, p.dS0 + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
 }
 
 // =============================================================================================
@@ -344,13 +355,16 @@ template <typename T, int DK, int DV> struct DqkwSmem {
     static constexpr size_t oQ = oK + align16(sizeof(T) * C * LK);
     static constexpr size_t oDP = oQ + align16(sizeof(T) * C * LK);
     static constexpr size_t oS = oDP + align16(sizeof(T) * C * LT); // S, then dS'
-    static constexpr size_t bytes = oS + align16(sizeof(T) * DK * LV);
+    static constexpr size_t oStage = align16(oS + align16(sizeof(T) * DK * LV)); // per-wave output staging tiles
+    static constexpr size_t bytes = oStage + 4 * cmax(sizeof(T) * Stage<T>::ELEMS, 0);
 };
 
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
     using SM = DqkwSmem<T, DK, DV>;
     extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (sizeof(T) * Stage<T>::ELEMS);
+    T *stg = reinterpret_cast<T *>(stg_raw);
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
     T *sUt = reinterpret_cast<T *>(smem + SM::oUt);
     T *sDUt = reinterpret_cast<T *>(smem + SM::oDUt);
@@ -368,13 +382,22 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
     const long row0 = (long)t0 + (long)ic * C;
     const long tile = ((long)(cb + ic) * H + h);
 
-    load_tile<T, C, DV>(sDO, SM::LV, (const T *)p.d_o + (row0 * H + h) * DV, (long)H * DV, nvalid);
-    load_tile<T, C, DV>(sUt, SM::LV, (const T *)p.Ut + tile * C * DV, DV, C);
-    load_tile<T, DK, DV>(sS, SM::LV, (const T *)p.Sc + tile * DK * DV, DV, DK);
-    load_tile<T, C, DV>(sDUt, SM::LV, (const T *)p.dUt + tile * C * DV, DV, C);
-    load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-    load_tile<T, C, DK>(sQ, SM::LK, (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-    __syncthreads();
+    { // all global loads are issued before the first LDS store, so their latencies overlap
+        TileRegs<T, C, DV> r_do, r_ut, r_dut;
+        TileRegs<T, DK, DV> r_s;
+        TileRegs<T, C, DK> r_k, r_q;
+        r_do.load((const T *)p.d_o + (row0 * H + h) * DV, (long)H * DV, nvalid);
+        r_ut.load((const T *)p.Ut + tile * C * DV, DV, C);
+        r_s.load((const T *)p.Sc + tile * DK * DV, DV, DK);
+        r_dut.load((const T *)p.dUt + tile * C * DV, DV, C);
+        r_k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r_q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r_do.store(sDO, SM::LV); r_ut.store(sUt, SM::LV); r_s.store(sS, SM::LV);
+        r_dut.store(sDUt, SM::LV); r_k.store(sK, SM::LK); r_q.store(sQ, SM::LK);
+    }
+    TileRegs<T, DK, DV> r_ds; // dS' is fetched now and moved into S's place once S is dead
+    r_ds.load((const T *)p.dSc + tile * DK * DV, DV, DK);
+    lds_barrier();
     { // dP = tril(dO Ut^T)
         const int a = wave >> 1, b = wave & 1;
         f32x16 acc = zero16();
@@ -394,11 +417,11 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
             f32x16 w = zero16(); // dW = -dUt S^T
             mma<DV, false, false, T>(w, sDUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
             acc_each(w, [&](int, int, float &val) { val = -val; });
-            acc_to_global<T>((T *)p.dW + tile * C * DK, DK, 32 * a, 32 * b, C, w);
+            acc_store<T>(stg, (T *)p.dW + tile * C * DK, DK, 32 * a, 32 * b, C, w);
         }
     }
-    __syncthreads(); // dP visible; S no longer needed
-    load_tile<T, DK, DV>(sS, SM::LV, (const T *)p.dSc + tile * DK * DV, DV, DK);
+    lds_barrier(); // dP visible; S no longer needed
+    r_ds.store(sS, SM::LV);
 #pragma unroll
     for (int s = 0; s < TPW; ++s) {
         const int t = wave + s * NWAVE;
@@ -406,17 +429,17 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
             const int a = t / (DK / 32), b = t % (DK / 32);
             if (a == 0) mma<32, false, true, T>(part[s], sDP, SM::LT, sK + 32 * b, SM::LK);
             else mma<C, false, true, T>(part[s], sDP + 32 * SM::LT, SM::LT, sK + 32 * b, SM::LK);
-            acc_to_global<T>((T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, part[s]);
+            acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, part[s]);
         }
     }
-    __syncthreads();
+    lds_barrier();
     for (int t = wave; t < KT; t += NWAVE) {
         const int a = t / (DK / 32), b = t % (DK / 32);
         f32x16 acc = zero16(); // dK1 = dP^T Q + Ut dS'^T
         if (a == 1) mma<32, true, true, T>(acc, sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * b, SM::LK);
         else mma<C, true, true, T>(acc, sDP, SM::LT, sQ + 32 * b, SM::LK);
         mma<DV, false, false, T>(acc, sUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
-        acc_to_global<T>((T *)p.dK1 + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
+        acc_store<T>(stg, (T *)p.dK1 + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
     }
 }
 
@@ -440,7 +463,8 @@ template <typename T, int DK, int DV> struct WySmem {
     static constexpr size_t oM = oDX + align16(sizeof(T) * C * LT);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t oDb = oBeta + sizeof(float) * C;
-    static constexpr size_t bytes = oDb + sizeof(float) * 4 * C;
+    static constexpr size_t oStage = align16(oDb + sizeof(float) * 4 * C); // per-wave output staging tiles
+    static constexpr size_t bytes = oStage + 4 * cmax(sizeof(T) * Stage<T>::ELEMS, 0);
 };
 
 template <typename T, int DK, int DV>
@@ -448,6 +472,8 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
     using SM = WySmem<T, DK, DV>;
     static_assert(!SM::kXnIsX || SM::LT == SM::LF, "fp32 operand copy aliases the inverse");
     extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (sizeof(T) * Stage<T>::ELEMS);
+    T *stg = reinterpret_cast<T *>(stg_raw);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sV = reinterpret_cast<T *>(smem + SM::oV);
     float *sX = reinterpret_cast<float *>(smem + SM::oV);
@@ -473,12 +499,17 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
     const int mi = wave >> 1, ni = wave & 1; // this wave's 32x32 tile of every C x C matrix
     const bool upper = (mi == 0 && ni == 1);
 
-    load_tile<T, C, DK>(sK, SM::LK, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-    load_tile<T, C, DV>(sV, SM::LV, (const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
-    load_tile<T, C, DK>(sDW, SM::LK, (const T *)p.dW + tile * C * DK, DK, C);
-    load_tile<T, C, DV>(sDU, SM::LV, (const T *)p.dUt + tile * C * DV, DV, C);
+    { // all global loads are issued before the first LDS store, so their latencies overlap
+        TileRegs<T, C, DK> r_k, r_dw;
+        TileRegs<T, C, DV> r_v, r_du;
+        r_k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r_v.load((const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
+        r_dw.load((const T *)p.dW + tile * C * DK, DK, C);
+        r_du.load((const T *)p.dUt + tile * C * DV, DV, C);
+        r_k.store(sK, SM::LK); r_v.store(sV, SM::LV); r_dw.store(sDW, SM::LK); r_du.store(sDU, SM::LV);
+    }
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
-    __syncthreads();
+    lds_barrier();
     f32x16 g = zero16(), dxp = zero16();
     if (!upper) {
         mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
@@ -486,9 +517,9 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
         mma<DV, false, false, T>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
     }
     acc_each(g, [&](int r, int c, float &val) { if (32 * ni + c >= 32 * mi + r) val = 0.f; }); // strictly lower G
-    __syncthreads(); // V is dead: its bytes become the fp32 matrix
+    lds_barrier(); // V is dead: its bytes become the fp32 matrix
     acc_each(g, [&](int r, int c, float &val) { sX[(32 * mi + r) * SM::LF + 32 * ni + c] = sBeta[32 * mi + r] * val; });
-    __syncthreads();
+    lds_barrier();
     tri_inverse_64_inplace<T>(sX, SM::LF, sM, sOp, SM::LO);
     { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta), X as an operand
         float part = 0.f;
@@ -502,7 +533,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
         if (!SM::kXnIsX)
             for (int e = tid; e < C * C; e += NTHR) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
     }
-    __syncthreads();
+    lds_barrier();
     f32x16 m1 = zero16(); // M1 = dX X^T
     mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
     constexpr int KB_TILES = 2 * (DK / 32), KB_TPW = (KB_TILES + NWAVE - 1) / NWAVE;
@@ -523,11 +554,11 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
         if (a == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * b, SM::LV);
         else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * b, SM::LV);
         acc_each(acc, [&](int r, int, float &val) { val *= sBeta[32 * a + r]; });
-        acc_to_global<T>((T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * a, 32 * b, nvalid, acc);
+        acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * a, 32 * b, nvalid, acc);
     }
-    __syncthreads(); // dW, dU, dX are dead
+    lds_barrier(); // dW, dU, dX are dead
     acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1);
-    __syncthreads();
+    lds_barrier();
     { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah + Ah^T into sDX
         f32x16 acc = zero16();
         if (!upper) {
@@ -551,7 +582,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
 #pragma unroll
     for (int s = 0; s < KB_TPW; ++s) { // dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K
         const int t = wave + s * NWAVE;
@@ -562,7 +593,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
                 val = val * sBeta[32 * a + r] + to_f32(k1[(32 * a + r) * DK + 32 * b + c]);
             });
             mma<C, false, true, T>(dKb[s], sDX + 32 * a * SM::LT, SM::LT, sK + 32 * b, SM::LK);
-            acc_to_global<T>((T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, dKb[s]);
+            acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, dKb[s]);
         }
     }
     { // dbeta = column sums from part 1 + row sums of dA o G

@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_W, off_U, off_P, off_Ut, off_dUt, off_Sc, off_dSc, off_dW, off_dK1, total;
+    size_t off_coff, off_T, off_P, off_Ut, off_dUt, off_Sc, off_dSc, off_dW, off_dK1, total;
     size_t esz;
 };
 
@@ -105,9 +105,9 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
     const size_t tS = up256(tiles * (size_t)s->d_k * s->d_v * pl->esz);
     size_t o = 0;
     pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * ((size_t)pb.N + 1)) : 0;
-    pl->off_W = o; o += tK;
-    pl->off_U = o; o += tV;
-    pl->off_P = o; o += up256(tiles * kChunk * kChunk * pl->esz); // tril(Q K^T) (forward) or its transpose (backward)
+    const size_t tC = up256(tiles * kChunk * kChunk * pl->esz);
+    pl->off_T = o; o += tC; // T of Eq. 10
+    pl->off_P = o; o += tC; // tril(Q K^T) (forward) or its transpose (backward)
     if (want_bwd) {
         pl->off_Ut = o; o += tV;
         pl->off_dUt = o; o += tV;
@@ -124,8 +124,7 @@ bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) !=
 void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd) {
     unsigned char *b = static_cast<unsigned char *>(ws);
     pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
-    p->W = b + pl.off_W;
-    p->U = b + pl.off_U;
+    p->Tm = b + pl.off_T;
     p->P = p->PT = b + pl.off_P;
     p->want_p = !want_bwd;
     p->want_pt = want_bwd;

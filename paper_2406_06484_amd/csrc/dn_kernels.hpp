@@ -39,32 +39,31 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
 }
 
 // =============================================================================================
-// k_wy_prep.  LDS holds one row-major operand tile (K, later V), the fp32 C x C matrix that is
-// inverted in place, and T; V waits in registers until K is no longer needed.
+// k_wy_prep: per chunk, T = (I + tril(diag(beta) K K^T, -1))^-1 diag(beta) (Eq. 10) and
+// P = tril(Q K^T) (the causal intra-chunk scores of Eq. 9), stored row-major and/or transposed.
+// W = T K and U = T V (Eq. 11) are rebuilt from T inside the scan kernels: T is 8 KB per chunk
+// where W and U are 32 KB.
 template <typename T, int DK, int DV> struct PrepSmem {
-    static constexpr int DM = cmax(DK, DV);
-    static constexpr int LD = ldn<T>(DM), LT = ldn<T>(C), LF = C + 4, LO = 40;
-    static constexpr size_t oKV = 0;
-    static constexpr size_t oX = oKV + align16(sizeof(T) * C * LD);
-    static constexpr size_t oT = oX + align16(sizeof(float) * C * LF);     // inverse operands, then T
-    static constexpr size_t szT = cmax(sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO);
+    static constexpr int LD = ldc<T>(DK), LT = ldc<T>(C), LF = C + 4, LO = 40;
+    static constexpr size_t oK = 0;
+    static constexpr size_t oX = oK + align16(sizeof(T) * C * LD);
+    static constexpr size_t oT = oX + align16(sizeof(float) * C * LF); // P staging, inverse operands, then T
+    static constexpr size_t szT = cmax(cmax(sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO), NWAVE * sizeof(T) * Stage<T>::ELEMS);
     static constexpr size_t oM = oT + align16(szT);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
-    static constexpr size_t oStage = align16(oBeta + sizeof(float) * C); // per-wave output staging tiles
-    static constexpr size_t bytes = oStage + 4 * cmax(sizeof(T) * Stage<T>::ELEMS, 0);
+    static constexpr size_t bytes = oBeta + sizeof(float) * C;
 };
 
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     using SM = PrepSmem<T, DK, DV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (sizeof(T) * Stage<T>::ELEMS);
-    T *stg = reinterpret_cast<T *>(stg_raw);
-    T *sKV = reinterpret_cast<T *>(smem + SM::oKV);
+    T *sK = reinterpret_cast<T *>(smem + SM::oK);
     float *sX = reinterpret_cast<float *>(smem + SM::oX);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
+    T *stg = sT + (threadIdx.x >> 6) * Stage<T>::ELEMS;
 
     int n, ic;
     if (!sm.chunk(blockIdx.x, n, ic)) return;
@@ -74,32 +73,28 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     const int nvalid = min(C, len - ic * C);
     const long row0 = (long)t0 + (long)ic * C;
     const long tile = ((long)(cb + ic) * H + h);
+    const int mi = wave >> 1, ni = wave & 1; // this wave's 32 x 32 tile of the C x C matrices
+    const bool upper = mi == 0 && ni == 1;
 
-    TileRegs<T, C, DV> vregs; // V is fetched now and parked in registers
-    vregs.load((const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
-    load_tile<T, C, DK>(sKV, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+    AFrags<T, DK> qf; // Q rows straight from global memory
+    if (!upper) qf.load((const T *)p.q + ((row0 + 32 * mi) * H + h) * DK, (long)H * DK, nvalid - 32 * mi);
+    load_tile<T, C, DK>(sK, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
     lds_barrier();
-    { // A = tril(diag(beta) K K^T, -1), Eq. 10
-        const int mi = wave >> 1, ni = wave & 1;
+    { // A = tril(diag(beta) K K^T, -1)
         f32x16 g = zero16();
-        if (!(mi == 0 && ni == 1)) mma<DK, false, false, T>(g, sKV + 32 * mi * SM::LD, SM::LD, sKV + 32 * ni * SM::LD, SM::LD);
+        if (!upper) mma<DK, false, false, T>(g, sK + 32 * mi * SM::LD, SM::LD, sK + 32 * ni * SM::LD, SM::LD);
         acc_each(g, [&](int r, int c, float &val) {
             const int i = 32 * mi + r, j = 32 * ni + c;
             sX[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
         });
     }
-    if (p.want_p || p.want_pt) { // P = tril(Q K^T) (Eq. 9), Q rows straight from global memory
-        const int mi = wave >> 1, ni = wave & 1;
-        if (!(mi == 0 && ni == 1)) {
-            AFrags<T, DK> qf;
-            qf.load((const T *)p.q + ((row0 + 32 * mi) * H + h) * DK, (long)H * DK, nvalid - 32 * mi);
-            f32x16 acc = zero16();
-            mma_ra<0, DK, false>(acc, qf, sKV + 32 * ni * SM::LD, SM::LD);
-            acc_each(acc, [&](int r, int c, float &val) { if (32 * ni + c > 32 * mi + r) val = 0.f; });
-            if (p.want_p) acc_store<T>(stg, (T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
-            if (p.want_pt) acc_store_t<T>(stg, (T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
-        }
+    if (!upper) { // P = tril(Q K^T), diagonal included
+        f32x16 acc = zero16();
+        mma_ra<0, DK, false>(acc, qf, sK + 32 * ni * SM::LD, SM::LD);
+        acc_each(acc, [&](int r, int c, float &val) { if (32 * ni + c > 32 * mi + r) val = 0.f; });
+        if (p.want_p) acc_store<T>(stg, (T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
+        if (p.want_pt) acc_store_t<T>(stg, (T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
     }
     lds_barrier();
     tri_inverse_64_inplace<T>(sX, SM::LF, sM, sT, SM::LO);
@@ -108,31 +103,16 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
         sT[i * SM::LT + j] = from_f32<T>(sX[i * SM::LF + j] * sBeta[j]);
     }
     lds_barrier();
-    for (int t = wave; t < 2 * (DK / 32); t += NWAVE) { // W = T K, Eq. 11 (K read through the transposing path)
-        const int a = t / (DK / 32), b = t % (DK / 32);
-        f32x16 acc = zero16();
-        if (a == 0) mma<32, false, true, T>(acc, sT, SM::LT, sKV + 32 * b, SM::LD);
-        else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sKV + 32 * b, SM::LD);
-        acc_store<T>(stg, (T *)p.W + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
-    }
-    lds_barrier();
-    vregs.store(sKV, SM::LD);
-    lds_barrier();
-    for (int t = wave; t < 2 * (DV / 32); t += NWAVE) { // U = T V
-        const int a = t / (DV / 32), b = t % (DV / 32);
-        f32x16 acc = zero16();
-        if (a == 0) mma<32, false, true, T>(acc, sT, SM::LT, sKV + 32 * b, SM::LD);
-        else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sKV + 32 * b, SM::LD);
-        acc_store<T>(stg, (T *)p.U + tile * C * DV, DV, 32 * a, 32 * b, C, acc);
-    }
+    store_tile<T, C, C>((T *)p.Tm + tile * C * C, C, sT, SM::LT, C);
 }
 
 // =============================================================================================
 // The two chain-serial kernels.  One workgroup of 8 wavefronts owns one chain and BV = 64 columns
-// of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.  The operand
-// tiles of the next chunk are fetched into registers while the current chunk is computed, so global
-// latency overlaps the MFMAs.  Workgroup ids are laid out so that the v-blocks of one chain land
-// on the same XCD (ids are dealt round-robin over the 8 XCDs) and share its L2 for Q, K, W.
+// of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.  Operand tiles
+// are fetched two chunks ahead into two alternating register sets, so global latency overlaps the
+// MFMAs.  W = T K (Eq. 11) is rebuilt per chunk from the 64 x 64 T.  Workgroup ids are laid out so
+// that the v-blocks of one chain land on the same XCD (ids are dealt round-robin over the 8 XCDs)
+// and share its L2 for the Q, K, T tiles they all read.
 constexpr int NTS = 512, NWS = 8; // threads / waves of a scan workgroup
 template <int DV> struct VBlock { static constexpr int BV = DV < 64 ? DV : 64; static constexpr int NV = DV / BV; };
 
@@ -144,35 +124,52 @@ __device__ inline bool chain_of_block(int nchains, int nv, int &chain, int &vbi)
 }
 __host__ inline int chain_grid(int nchains, int nv) { return ((nchains + 7) / 8) * 8 * nv; }
 
+// Which tiles a scan wave owns.  State tile (sa, sb): rows 32*sa of d_k, cols 32*sb of the v-block.
+// T row block ta feeds this wave's W tile (ta, wb) and, for waves < U_TILES, its U / Ut tile (ta, ub).
+template <int DK, int BV> struct ScanMap {
+    static constexpr int NVT = BV / 32, S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT, W_COLS = DK / 32;
+    static_assert(S_TILES <= NWS && U_TILES <= 4 && (NVT == 1 || NVT == 2), "state tiling");
+    int sa, sb, ta, wb, ub;
+    bool has_s, has_w, does_u;
+    __device__ ScanMap(int wave) {
+        sa = wave / NVT; sb = wave % NVT;
+        has_s = wave < S_TILES;
+        if (NVT == 2) { ta = (wave >> 1) & 1; wb = (wave & 1) + 2 * (wave >> 2); ub = wave & 1; }
+        else { ta = wave & 1; wb = wave >> 1; ub = 0; }
+        has_w = wb < W_COLS;
+        does_u = wave < U_TILES;
+    }
+};
+
 // k_scan_fwd: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
 // writes every chunk-initial state and Ut to the workspace instead of O.
 template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr int BV = VBlock<DV>::BV;
-    static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LU = ldc<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
+    static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LV = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
-    static constexpr size_t oW = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oU = oW + align16(sizeof(T) * C * LQ);
-    static constexpr size_t oST = oU + align16(sizeof(T) * C * LU);
+    static constexpr size_t oV = oK + align16(sizeof(T) * C * LK);
+    static constexpr size_t oW = oV + align16(sizeof(T) * C * LV);
+    static constexpr size_t oST = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t oStage = align16(oUT + align16(sizeof(T) * BV * LT)); // per-wave output staging tiles
-    static constexpr size_t bytes = oStage + 8 * cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
+    static constexpr size_t oStage = oUT + align16(sizeof(T) * BV * LT); // per-wave output staging tiles
+    static constexpr size_t szStage = cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
+    static constexpr size_t bytes = oStage + NWS * szStage;
 };
 
 template <typename T, int DK, int DV, bool STORE>
 __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     using SM = ScanFwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NV = VBlock<DV>::NV, NVT = BV / 32;
-    constexpr int S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT;
-    static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
+    constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
+    using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS));
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * SM::szStage;
     T *stg = reinterpret_cast<T *>(stg_raw);
     float *stgf = reinterpret_cast<float *>(stg_raw);
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
+    T *sV = reinterpret_cast<T *>(smem + SM::oV);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
-    T *sU = reinterpret_cast<T *>(smem + SM::oU);
     T *sST = reinterpret_cast<T *>(smem + SM::oST);
     T *sUT = reinterpret_cast<T *>(smem + SM::oUT);
 
@@ -183,94 +180,110 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     int t0, len, cb;
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
-    // wave -> tiles: state tile (sa, sb) = rows 32*sa of d_k, cols 32*sb of the v-block;
-    // waves 0..U_TILES-1 build Ut tile (ua, ub); waves 4..4+U_TILES-1 build the same tile of O
-    const int sa = wave / NVT, sb = wave % NVT;
-    const bool has_s = wave < S_TILES;
-    const bool does_u = wave < U_TILES, does_o = !STORE && wave >= 4 && wave < 4 + U_TILES;
-    const int ut = does_o ? wave - 4 : wave, ua = ut / NVT, ub = ut % NVT;
+    const Map m(wave);
+    // waves 4.. build the output tile (oa, ob) of the same shape as Ut tile (ta, ub) of wave - 4
+    const bool does_o = !STORE && wave >= 4 && wave < 4 + Map::U_TILES;
+    const Map mo(does_o ? wave - 4 : 0);
+    const int oa = mo.ta, ob = mo.ub;
 
     f32x16 S = zero16();
-    if (has_s && p.S0) {
+    if (m.has_s && p.S0) {
         const float *src = p.S0 + (long)chain * DK * DV + vb;
-        acc_each(S, [&](int r, int c, float &val) { val = src[(long)(32 * sa + r) * DV + 32 * sb + c]; });
+        acc_each(S, [&](int r, int c, float &val) { val = src[(long)(32 * m.sa + r) * DV + 32 * m.sb + c]; });
     }
 
-    TileRegs<T, C, DK, NTS> rq, rk, rw;
-    TileRegs<T, C, BV, NTS> ru;
-    AFrags<T, C> rp; // rows of P = tril(Q K^T) for the waves that finish an output tile
-    auto prefetch = [&](int ic) {
+    struct Regs {
+        TileRegs<T, C, DK, NTS> q, k;
+        TileRegs<T, C, BV, NTS> v;
+        AFrags<T, C> t, pf; // rows of T (every wave) and of P = tril(Q K^T) (output waves)
+    } ra, rb;
+    auto fetch = [&](Regs &r, int ic) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        if (!STORE) rq.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        rk.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        rw.load((const T *)p.W + tile * C * DK, DK, C);
-        ru.load((const T *)p.U + tile * C * DV + vb, DV, C);
-        if (does_o) rp.load((const T *)p.P + tile * C * C + 32 * ua * C, C, C);
+        if (!STORE) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
+        r.t.load((const T *)p.Tm + tile * C * C + 32 * m.ta * C, C, C);
+        if (does_o) r.pf.load((const T *)p.P + tile * C * C + 32 * oa * C, C, C);
     };
-    if (nchunks > 0) prefetch(0);
-
-    for (int ic = 0; ic < nchunks; ++ic) {
+    auto step = [&](Regs &r, int ic) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        if (!STORE) rq.store(sQ, SM::LQ);
-        rk.store(sK, SM::LK);
-        rw.store(sW, SM::LQ);
-        ru.store(sU, SM::LU);
-        const AFrags<T, C> pc = rp;
-        if (has_s) {
-            if (STORE) acc_store<T>(stg, (T *)p.Sc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
-            acc_to_lds_t<T>(sST, SM::LS, 32 * sa, 32 * sb, S);
+        if (!STORE) r.q.store(sQ, SM::LQ);
+        r.k.store(sK, SM::LK);
+        r.v.store(sV, SM::LV);
+        const AFrags<T, C> tc = r.t, pc = r.pf;
+        if (m.has_s) {
+            if (STORE) acc_store<T>(stg, (T *)p.Sc + tile * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, S);
+            acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         }
         lds_barrier();
-        if (ic + 1 < nchunks) prefetch(ic + 1);
+        if (ic + 2 < nchunks) fetch(r, ic + 2);
+        if (m.has_w) { // W = T K (Eq. 11), T is lower triangular
+            f32x16 w = zero16();
+            if (m.ta == 0) mma_ra<0, 32, true>(w, tc, sK + 32 * m.wb, SM::LK);
+            else mma_ra<0, C, true>(w, tc, sK + 32 * m.wb, SM::LK);
+            acc_to_lds<T>(sW, SM::LQ, 32 * m.ta, 32 * m.wb, w);
+        }
         f32x16 acc = zero16();
-        if (does_u) { // Ut = U - W S (inner term of Eq. 8-9)
-            mma<DK, false, false, T>(acc, sW + 32 * ua * SM::LQ, SM::LQ, sST + 32 * ub * SM::LS, SM::LS);
-            acc_each(acc, [&](int r, int c, float &val) { val = to_f32(sU[(32 * ua + r) * SM::LU + 32 * ub + c]) - val; });
-            acc_to_lds_t<T>(sUT, SM::LT, 32 * ua, 32 * ub, acc);
-            if (STORE) acc_store<T>(stg, (T *)p.Ut + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
+        if (m.does_u) { // U = T V
+            if (m.ta == 0) mma_ra<0, 32, true>(acc, tc, sV + 32 * m.ub, SM::LV);
+            else mma_ra<0, C, true>(acc, tc, sV + 32 * m.ub, SM::LV);
         } else if (does_o) { // Q S
-            mma<DK, false, false, T>(acc, sQ + 32 * ua * SM::LQ, SM::LQ, sST + 32 * ub * SM::LS, SM::LS);
+            mma<DK, false, false, T>(acc, sQ + 32 * oa * SM::LQ, SM::LQ, sST + 32 * ob * SM::LS, SM::LS);
+        }
+        lds_barrier();
+        if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
+            f32x16 ws = zero16();
+            mma<DK, false, false, T>(ws, sW + 32 * m.ta * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
+            acc -= ws;
+            acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ta, 32 * m.ub, acc);
+            if (STORE) acc_store<T>(stg, (T *)p.Ut + tile * C * DV + vb, DV, 32 * m.ta, 32 * m.ub, C, acc);
         }
         lds_barrier();
         if (does_o) { // O = Q S + P Ut (Eq. 9)
-            if (ua == 0) mma_ra<0, 32, false>(acc, pc, sUT + 32 * ub * SM::LT, SM::LT);
-            else mma_ra<0, C, false>(acc, pc, sUT + 32 * ub * SM::LT, SM::LT);
-            acc_store<T>(stg, (T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * ua, 32 * ub, nvalid, acc);
+            if (oa == 0) mma_ra<0, 32, false>(acc, pc, sUT + 32 * ob * SM::LT, SM::LT);
+            else mma_ra<0, C, false>(acc, pc, sUT + 32 * ob * SM::LT, SM::LT);
+            acc_store<T>(stg, (T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * oa, 32 * ob, nvalid, acc);
         }
-        if (has_s) mma<C, true, false, T>(S, sK + 32 * sa, SM::LK, sUT + 32 * sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
+        if (m.has_s) mma<C, true, false, T>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         lds_barrier();
+    };
+    if (nchunks > 0) fetch(ra, 0);
+    if (nchunks > 1) fetch(rb, 1);
+    for (int ic = 0; ic < nchunks; ic += 2) {
+        step(ra, ic);
+        if (ic + 1 < nchunks) step(rb, ic + 1);
     }
-    if (!STORE && p.ST && has_s)
-        acc_store<float>(stgf, p.ST + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, S);
+    if (!STORE && p.ST && m.has_s)
+        acc_store<float>(stgf, p.ST + (long)chain * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, S);
 }
 
 // k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
 //   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
 template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr int BV = VBlock<DV>::BV;
-    static constexpr int LQ = ldn<T>(DK), LK = ldc<T>(DK), LD = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
+    static constexpr int LQ = ldn<T>(DK), LK = ldn<T>(DK), LD = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
     static constexpr size_t oW = oK + align16(sizeof(T) * C * LK);
     static constexpr size_t oDO = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oDST = oDO + align16(sizeof(T) * C * LD);
     static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t oStage = align16(oDUT + align16(sizeof(T) * BV * LT)); // per-wave output staging tiles
-    static constexpr size_t bytes = oStage + 8 * cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
+    static constexpr size_t oStage = oDUT + align16(sizeof(T) * BV * LT); // per-wave output staging tiles
+    static constexpr size_t szStage = cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
+    static constexpr size_t bytes = oStage + NWS * szStage;
 };
 
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     using SM = ScanBwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NV = VBlock<DV>::NV, NVT = BV / 32;
-    constexpr int S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT;
-    static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
+    constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
+    using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS));
+    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * SM::szStage;
     T *stg = reinterpret_cast<T *>(stg_raw);
     float *stgf = reinterpret_cast<float *>(stg_raw);
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
@@ -287,60 +300,69 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     int t0, len, cb;
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
-    const int sa = wave / NVT, sb = wave % NVT;
-    const bool has_s = wave < S_TILES, does_u = wave < U_TILES;
-    const int ua = wave / NVT, ub = wave % NVT;
+    const Map m(wave);
 
     f32x16 dS = zero16();
-    if (has_s && p.dST) {
+    if (m.has_s && p.dST) {
         const float *src = p.dST + (long)chain * DK * DV + vb;
-        acc_each(dS, [&](int r, int c, float &val) { val = src[(long)(32 * sa + r) * DV + 32 * sb + c]; });
+        acc_each(dS, [&](int r, int c, float &val) { val = src[(long)(32 * m.sa + r) * DV + 32 * m.sb + c]; });
     }
 
-    TileRegs<T, C, DK, NTS> rq, rk, rw;
-    TileRegs<T, C, BV, NTS> rdo;
-    AFrags<T, C> rpt; // rows of P^T for the waves that build dUt
-    auto prefetch = [&](int ic) {
+    struct Regs {
+        TileRegs<T, C, DK, NTS> q, k;
+        TileRegs<T, C, BV, NTS> d_o;
+        AFrags<T, C> t, pt; // rows of T (every wave) and of P^T (the waves that build dUt)
+    } ra, rb;
+    auto fetch = [&](Regs &r, int ic) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        rq.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        rk.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        rw.load((const T *)p.W + tile * C * DK, DK, C);
-        rdo.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
-        if (does_u) rpt.load((const T *)p.PT + tile * C * C + 32 * ua * C, C, C);
+        r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
+        r.t.load((const T *)p.Tm + tile * C * C + 32 * m.ta * C, C, C);
+        if (m.does_u) r.pt.load((const T *)p.PT + tile * C * C + 32 * m.ta * C, C, C);
     };
-    if (nchunks > 0) prefetch(nchunks - 1);
-
-    for (int ic = nchunks - 1; ic >= 0; --ic) {
+    auto step = [&](Regs &r, int ic) {
         const long tile = ((long)(cb + ic) * H + h);
-        rq.store(sQ, SM::LQ);
-        rk.store(sK, SM::LK);
-        rw.store(sW, SM::LQ);
-        rdo.store(sDO, SM::LD);
-        const AFrags<T, C> ptc = rpt;
-        if (has_s) { // dS' (gradient w.r.t. the state after this chunk)
-            acc_store<T>(stg, (T *)p.dSc + tile * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
-            acc_to_lds_t<T>(sDST, SM::LS, 32 * sa, 32 * sb, dS);
+        r.q.store(sQ, SM::LQ);
+        r.k.store(sK, SM::LK);
+        r.d_o.store(sDO, SM::LD);
+        const AFrags<T, C> tc = r.t, ptc = r.pt;
+        if (m.has_s) { // dS' (gradient w.r.t. the state after this chunk)
+            acc_store<T>(stg, (T *)p.dSc + tile * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, dS);
+            acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS);
         }
         lds_barrier();
-        if (ic > 0) prefetch(ic - 1);
-        if (does_u) { // dUt tile (ua, ub); P^T is upper triangular
+        if (ic - 2 >= 0) fetch(r, ic - 2);
+        if (m.has_w) { // W = T K (Eq. 11)
+            f32x16 w = zero16();
+            if (m.ta == 0) mma_ra<0, 32, true>(w, tc, sK + 32 * m.wb, SM::LK);
+            else mma_ra<0, C, true>(w, tc, sK + 32 * m.wb, SM::LK);
+            acc_to_lds<T>(sW, SM::LQ, 32 * m.ta, 32 * m.wb, w);
+        }
+        if (m.does_u) { // dUt tile (ta, ub); P^T is upper triangular
             f32x16 acc = zero16();
-            if (ua == 0) mma_ra<0, C, true>(acc, ptc, sDO + 32 * ub, SM::LD);
-            else mma_ra<32, C, true>(acc, ptc, sDO + 32 * ub, SM::LD);
-            mma<DK, false, false, T>(acc, sK + 32 * ua * SM::LK, SM::LK, sDST + 32 * ub * SM::LS, SM::LS);
-            acc_store<T>(stg, (T *)p.dUt + tile * C * DV + vb, DV, 32 * ua, 32 * ub, C, acc);
+            if (m.ta == 0) mma_ra<0, C, true>(acc, ptc, sDO + 32 * m.ub, SM::LD);
+            else mma_ra<32, C, true>(acc, ptc, sDO + 32 * m.ub, SM::LD);
+            mma<DK, false, false, T>(acc, sK + 32 * m.ta * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+            acc_store<T>(stg, (T *)p.dUt + tile * C * DV + vb, DV, 32 * m.ta, 32 * m.ub, C, acc);
             acc_each(acc, [&](int, int, float &val) { val = -val; });
-            acc_to_lds_t<T>(sDUT, SM::LT, 32 * ua, 32 * ub, acc);
+            acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ta, 32 * m.ub, acc);
         }
-        if (has_s) mma<C, true, true, T>(dS, sQ + 32 * sa, SM::LQ, sDO + 32 * sb, SM::LD); // + Q^T dO
+        if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         lds_barrier();
-        if (has_s) mma<C, true, false, T>(dS, sW + 32 * sa, SM::LQ, sDUT + 32 * sb * SM::LT, SM::LT); // - W^T dUt
+        if (m.has_s) mma<C, true, false, T>(dS, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT); // - W^T dUt
         lds_barrier();
+    };
+    if (nchunks > 0) fetch(ra, nchunks - 1);
+    if (nchunks > 1) fetch(rb, nchunks - 2);
+    for (int ic = nchunks - 1; ic >= 0; ic -= 2) {
+        step(ra, ic);
+        if (ic - 1 >= 0) step(rb, ic - 1);
     }
-    if (p.dS0 && has_s)
-        acc_store<float>(stgf, p.dS0 + (long)chain * DK * DV + vb, DV, 32 * sa, 32 * sb, DK, dS);
+    if (p.dS0 && m.has_s)
+        acc_store<float>(stgf, p.dS0 + (long)chain * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, dS);
 }
 
 // =============================================================================================

@@ -43,8 +43,8 @@ def test_workspace_query_and_validation_errors():
     fwd_bytes = out.value
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape()), 1, ctypes.byref(out)) == 0
     assert out.value > fwd_bytes > 0
-    # W and U tiles plus the C x C tile tril(Q K^T) for every (chunk, head), bf16
-    assert fwd_bytes == 2 * 2 * 256 * 4 * 128 * 2 + 2 * 256 * 4 * 64 * 2
+    # two C x C tiles (T of Eq. 10 and tril(Q K^T)) for every (chunk, head), bf16
+    assert fwd_bytes == 2 * (2 * 256 * 4 * 64 * 2)
     assert lib.deltanet_workspace_bytes(None, 0, ctypes.byref(out)) == -1
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(H=0)), 0, ctypes.byref(out)) == -2
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(d_k=96)), 0, ctypes.byref(out)) == -3

@@ -134,10 +134,12 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     }
 }
 
-int check_device_lds(const Impl *impl) {
-    int dev = 0, lds = 0;
+int check_device(const Impl *impl, Problem *pb) {
+    int dev = 0, lds = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return DN_ERR_LAUNCH;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return DN_ERR_LAUNCH;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return DN_ERR_LAUNCH;
+    pb->num_cus = cus;
     return (size_t)lds >= impl->lds() ? DN_OK : DN_ERR_UNSUPPORTED;
 }
 
@@ -166,7 +168,7 @@ int deltanet_fwd(const dn_shape *shape, const void *q, const void *k, const void
     Plan pl;
     make_plan(shape, 0, &pl);
     if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
-    if (int rc = check_device_lds(impl)) return rc;
+    if (int rc = check_device(impl, &pl.pb)) return rc;
     Ptrs p;
     memset(&p, 0, sizeof(p));
     p.q = q; p.k = k; p.v = v; p.beta = beta; p.S0 = initial_state; p.o = o; p.ST = final_state;
@@ -188,7 +190,7 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
     Plan pl;
     make_plan(shape, 1, &pl);
     if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
-    if (int rc = check_device_lds(impl)) return rc;
+    if (int rc = check_device(impl, &pl.pb)) return rc;
     Ptrs p;
     memset(&p, 0, sizeof(p));
     p.q = q; p.k = k; p.v = v; p.beta = beta; p.S0 = initial_state; p.d_o = d_o; p.dST = dfinal_state;

@@ -375,10 +375,11 @@ __device__ inline void tri_inverse_64(const float *sA, float *sX, float *sM, int
 // lanes of every wavefront), then 2x2 block merges X21 = -X22 (A21 X11) double the block size
 // 8 -> 16 -> 32 on the vector ALU in fp32 and 32 -> 64 on the matrix cores with operands of type T.
 // sM: 512 floats of scratch.  sOp: 4 x 32 x LO elements of type T, LO >= 32 + 8.  Ends with a barrier.
-template <typename T>
+template <typename T, int NT = NTHR>
 __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *sOp, int LO) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    if (lane < 16) {
+    const bool act = tid < 256; // the fp32 stages are laid out for 256 threads; extra waves only join the barriers
+    if (act && lane < 16) {
         const int b = (2 * wave + (lane >> 3)) * 8, j = lane & 7;
         float x[8];
 #pragma unroll
@@ -393,44 +394,52 @@ __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *s
     }
     lds_barrier();
     { // 8 -> 16: four merges, one output element per thread
-        const int m = tid >> 6, i = (tid >> 3) & 7, j = tid & 7, r0 = 16 * m + 8, c0 = 16 * m;
+        const int m = (tid >> 6) & 3, i = (tid >> 3) & 7, j = tid & 7, r0 = 16 * m + 8, c0 = 16 * m;
         float s = 0.f;
+        if (act) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + c0 + k] * sX[(c0 + k) * ld + c0 + j];
-        sM[tid] = s;
+            for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + c0 + k] * sX[(c0 + k) * ld + c0 + j];
+            sM[tid] = s;
+        }
         lds_barrier();
-        s = 0.f;
+        if (act) {
+            s = 0.f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + r0 + k] * sM[(m << 6) + k * 8 + j];
-        sX[(r0 + i) * ld + c0 + j] = -s;
+            for (int k = 0; k < 8; ++k) s += sX[(r0 + i) * ld + r0 + k] * sM[(m << 6) + k * 8 + j];
+            sX[(r0 + i) * ld + c0 + j] = -s;
+        }
         lds_barrier();
     }
     { // 16 -> 32: two merges, two output elements per thread
-        const int m = tid >> 7, i = (tid >> 3) & 15, j = 2 * (tid & 7), r0 = 32 * m + 16, c0 = 32 * m;
+        const int m = (tid >> 7) & 1, i = (tid >> 3) & 15, j = 2 * (tid & 7), r0 = 32 * m + 16, c0 = 32 * m;
         float s0 = 0.f, s1 = 0.f;
+        if (act) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const float a = sX[(r0 + i) * ld + c0 + k];
-            s0 += a * sX[(c0 + k) * ld + c0 + j];
-            s1 += a * sX[(c0 + k) * ld + c0 + j + 1];
+            for (int k = 0; k < 16; ++k) {
+                const float a = sX[(r0 + i) * ld + c0 + k];
+                s0 += a * sX[(c0 + k) * ld + c0 + j];
+                s1 += a * sX[(c0 + k) * ld + c0 + j + 1];
+            }
+            sM[(m << 8) + i * 16 + j] = s0;
+            sM[(m << 8) + i * 16 + j + 1] = s1;
         }
-        sM[(m << 8) + i * 16 + j] = s0;
-        sM[(m << 8) + i * 16 + j + 1] = s1;
         lds_barrier();
-        s0 = s1 = 0.f;
+        if (act) {
+            s0 = s1 = 0.f;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const float a = sX[(r0 + i) * ld + r0 + k];
-            s0 += a * sM[(m << 8) + k * 16 + j];
-            s1 += a * sM[(m << 8) + k * 16 + j + 1];
+            for (int k = 0; k < 16; ++k) {
+                const float a = sX[(r0 + i) * ld + r0 + k];
+                s0 += a * sM[(m << 8) + k * 16 + j];
+                s1 += a * sM[(m << 8) + k * 16 + j + 1];
+            }
+            sX[(r0 + i) * ld + c0 + j] = -s0;
+            sX[(r0 + i) * ld + c0 + j + 1] = -s1;
         }
-        sX[(r0 + i) * ld + c0 + j] = -s0;
-        sX[(r0 + i) * ld + c0 + j + 1] = -s1;
         lds_barrier();
     }
     // 32 -> 64 on the matrix cores: operands A21, X11^T, X22 and (later) M^T, each 32 x LO
     T *oA = sOp, *oX11T = sOp + 32 * LO, *oX22 = sOp + 64 * LO, *oMT = sOp + 96 * LO;
-    for (int e = tid; e < 32 * 32; e += NTHR) {
+    for (int e = tid; e < 32 * 32; e += NT) {
         const int i = e >> 5, k = e & 31;
         oA[i * LO + k] = from_f32<T>(sX[(32 + i) * ld + k]);
         oX11T[k * LO + i] = from_f32<T>(sX[i * ld + k]);

@@ -12,6 +12,7 @@ struct Problem {
     const int32_t *cu;      // device cu_seqlens or nullptr
     int32_t *coff;          // device chunk-offset prefix [N+1] inside the workspace (packed only)
     hipStream_t stream;
+    int num_cus;            // compute units of the current device
 };
 
 struct Ptrs {

@@ -366,10 +366,38 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
 }
 
 // =============================================================================================
+// The two chunk-parallel backward kernels.  Workgroups of 8 wavefronts are persistent: each walks
+// over (chunk, head) tiles with a grid stride, and fetches the next tile's operands into registers
+// while it works on the current one, so global latency is hidden behind the MFMAs of another tile.
+constexpr int NTC = 512, NWC = 8;
+
+struct TileIter { // grid-stride walk over (global chunk id, head) tiles
+    int id, total, H;
+    __device__ TileIter(int chunks_total, int H_) : id(blockIdx.x), total(chunks_total * H_), H(H_) {}
+    __device__ bool valid() const { return id < total; }
+    __device__ void next() { id += gridDim.x; }
+    __device__ int gid() const { return id / H; }
+    __device__ int head() const { return id % H; }
+};
+struct TilePos { int nvalid, h; long row0, tile; bool ok; };
+__device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
+    TilePos tp;
+    int n, ic, t0, len, cb;
+    tp.ok = sm.chunk(gid, n, ic);
+    tp.h = h; tp.nvalid = 0; tp.row0 = 0; tp.tile = 0;
+    if (tp.ok) {
+        sm.seq(n, t0, len, cb);
+        tp.nvalid = min(C, len - ic * C);
+        tp.row0 = (long)t0 + (long)ic * C;
+        tp.tile = (long)(cb + ic) * H + h;
+    }
+    return tp;
+}
+
 // k_bwd_dqkw: per chunk, with S (chunk-initial state), dS' (gradient w.r.t. the state after the
 // chunk), Ut, dUt:  dP = tril(dO Ut^T); dQ = dO S^T + dP K; dK1 = dP^T Q + Ut dS'^T; dW = -dUt S^T.
 template <typename T, int DK, int DV> struct DqkwSmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C);
+    static constexpr int LK = ldn<T>(DK), LV = ldc<T>(DV), LT = ldn<T>(C);
     static constexpr size_t oDO = 0;
     static constexpr size_t oUt = oDO + align16(sizeof(T) * C * LV);
     static constexpr size_t oDUt = oUt + align16(sizeof(T) * C * LV);
@@ -377,16 +405,17 @@ template <typename T, int DK, int DV> struct DqkwSmem {
     static constexpr size_t oQ = oK + align16(sizeof(T) * C * LK);
     static constexpr size_t oDP = oQ + align16(sizeof(T) * C * LK);
     static constexpr size_t oS = oDP + align16(sizeof(T) * C * LT); // S, then dS'
-    static constexpr size_t oStage = align16(oS + align16(sizeof(T) * DK * LV)); // per-wave output staging tiles
-    static constexpr size_t bytes = oStage + 4 * cmax(sizeof(T) * Stage<T>::ELEMS, 0);
+    static constexpr size_t oStage = oS + align16(sizeof(T) * DK * LV);
+    static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
 };
 
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
+__global__ __launch_bounds__(NTC) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p, int chunks_total) {
     using SM = DqkwSmem<T, DK, DV>;
+    constexpr int KT = 2 * (DK / 32); // 32 x 32 tiles of a C x DK matrix
+    static_assert(KT <= NWC, "one output tile per wave");
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (sizeof(T) * Stage<T>::ELEMS);
-    T *stg = reinterpret_cast<T *>(stg_raw);
+    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + (threadIdx.x >> 6) * Stage<T>::ELEMS;
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
     T *sUt = reinterpret_cast<T *>(smem + SM::oUt);
     T *sDUt = reinterpret_cast<T *>(smem + SM::oDUt);
@@ -394,74 +423,69 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sDP = reinterpret_cast<T *>(smem + SM::oDP);
     T *sS = reinterpret_cast<T *>(smem + SM::oS);
+    const int wave = threadIdx.x >> 6;
+    const int ka = wave / (DK / 32), kb = wave % (DK / 32); // this wave's tile of dQ, dW, dK1
+    const bool has_k = wave < KT;
 
-    int n, ic;
-    if (!sm.chunk(blockIdx.x, n, ic)) return;
-    int t0, len, cb;
-    sm.seq(n, t0, len, cb);
-    const int h = blockIdx.y, tid = threadIdx.x, wave = tid >> 6;
-    const int nvalid = min(C, len - ic * C);
-    const long row0 = (long)t0 + (long)ic * C;
-    const long tile = ((long)(cb + ic) * H + h);
-
-    { // all global loads are issued before the first LDS store, so their latencies overlap
-        TileRegs<T, C, DV> r_do, r_ut, r_dut;
-        TileRegs<T, DK, DV> r_s;
-        TileRegs<T, C, DK> r_k, r_q;
-        r_do.load((const T *)p.d_o + (row0 * H + h) * DV, (long)H * DV, nvalid);
-        r_ut.load((const T *)p.Ut + tile * C * DV, DV, C);
-        r_s.load((const T *)p.Sc + tile * DK * DV, DV, DK);
-        r_dut.load((const T *)p.dUt + tile * C * DV, DV, C);
-        r_k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r_q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r_do.store(sDO, SM::LV); r_ut.store(sUt, SM::LV); r_s.store(sS, SM::LV);
-        r_dut.store(sDUt, SM::LV); r_k.store(sK, SM::LK); r_q.store(sQ, SM::LK);
-    }
-    TileRegs<T, DK, DV> r_ds; // dS' is fetched now and moved into S's place once S is dead
-    r_ds.load((const T *)p.dSc + tile * DK * DV, DV, DK);
-    lds_barrier();
-    { // dP = tril(dO Ut^T)
-        const int a = wave >> 1, b = wave & 1;
-        f32x16 acc = zero16();
-        if (!(a == 0 && b == 1)) mma<DV, false, false, T>(acc, sDO + 32 * a * SM::LV, SM::LV, sUt + 32 * b * SM::LV, SM::LV);
-        acc_each(acc, [&](int r, int c, float &val) { if (32 * b + c > 32 * a + r) val = 0.f; });
-        acc_to_lds<T>(sDP, SM::LT, 32 * a, 32 * b, acc);
-    }
-    constexpr int KT = 2 * (DK / 32), TPW = (KT + NWAVE - 1) / NWAVE;
-    f32x16 part[TPW]; // dO S^T now, dP K after the barrier
-#pragma unroll
-    for (int s = 0; s < TPW; ++s) {
-        part[s] = zero16();
-        const int t = wave + s * NWAVE;
-        if (t < KT) {
-            const int a = t / (DK / 32), b = t % (DK / 32);
-            mma<DV, false, false, T>(part[s], sDO + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
+    struct Regs {
+        TileRegs<T, C, DV, NTC> d_o, ut, dut;
+        TileRegs<T, DK, DV, NTC> s, ds;
+        TileRegs<T, C, DK, NTC> k, q;
+    } r;
+    auto fetch = [&](const TilePos &tp) {
+        if (!tp.ok) return;
+        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
+        r.ut.load((const T *)p.Ut + tp.tile * C * DV, DV, C);
+        r.s.load((const T *)p.Sc + tp.tile * DK * DV, DV, DK);
+        r.dut.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
+        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
+        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
+        r.ds.load((const T *)p.dSc + tp.tile * DK * DV, DV, DK);
+    };
+    TileIter it(chunks_total, H);
+    TilePos cur = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
+    fetch(cur);
+    while (it.valid()) {
+        it.next();
+        const TilePos nxt = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
+        if (!cur.ok) { cur = nxt; fetch(cur); continue; } // past the last real chunk (packed layout bound)
+        r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LV); r.s.store(sS, SM::LV);
+        r.dut.store(sDUt, SM::LV); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
+        const TileRegs<T, DK, DV, NTC> ds_cur = r.ds; // moves into S's place once S is dead
+        lds_barrier();
+        fetch(nxt);
+        if (wave < 4) { // dP = tril(dO Ut^T)
+            const int a = wave >> 1, b = wave & 1;
+            f32x16 acc = zero16();
+            if (!(a == 0 && b == 1)) mma<DV, false, false, T>(acc, sDO + 32 * a * SM::LV, SM::LV, sUt + 32 * b * SM::LV, SM::LV);
+            acc_each(acc, [&](int rr, int c, float &val) { if (32 * b + c > 32 * a + rr) val = 0.f; });
+            acc_to_lds<T>(sDP, SM::LT, 32 * a, 32 * b, acc);
+        }
+        f32x16 dq = zero16();
+        if (has_k) {
+            mma<DV, false, false, T>(dq, sDO + 32 * ka * SM::LV, SM::LV, sS + 32 * kb * SM::LV, SM::LV); // dO S^T
             f32x16 w = zero16(); // dW = -dUt S^T
-            mma<DV, false, false, T>(w, sDUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
+            mma<DV, false, false, T>(w, sDUt + 32 * ka * SM::LV, SM::LV, sS + 32 * kb * SM::LV, SM::LV);
             acc_each(w, [&](int, int, float &val) { val = -val; });
-            acc_store<T>(stg, (T *)p.dW + tile * C * DK, DK, 32 * a, 32 * b, C, w);
+            acc_store<T>(stg, (T *)p.dW + cur.tile * C * DK, DK, 32 * ka, 32 * kb, C, w);
         }
-    }
-    lds_barrier(); // dP visible; S no longer needed
-    r_ds.store(sS, SM::LV);
-#pragma unroll
-    for (int s = 0; s < TPW; ++s) {
-        const int t = wave + s * NWAVE;
-        if (t < KT) {
-            const int a = t / (DK / 32), b = t % (DK / 32);
-            if (a == 0) mma<32, false, true, T>(part[s], sDP, SM::LT, sK + 32 * b, SM::LK);
-            else mma<C, false, true, T>(part[s], sDP + 32 * SM::LT, SM::LT, sK + 32 * b, SM::LK);
-            acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, part[s]);
+        lds_barrier(); // dP visible; S no longer needed
+        ds_cur.store(sS, SM::LV);
+        if (has_k) { // dQ += dP K
+            if (ka == 0) mma<32, false, true, T>(dq, sDP, SM::LT, sK + 32 * kb, SM::LK);
+            else mma<C, false, true, T>(dq, sDP + 32 * SM::LT, SM::LT, sK + 32 * kb, SM::LK);
+            acc_store<T>(stg, (T *)p.dq + (cur.row0 * H + cur.h) * DK, (long)H * DK, 32 * ka, 32 * kb, cur.nvalid, dq);
         }
-    }
-    lds_barrier();
-    for (int t = wave; t < KT; t += NWAVE) {
-        const int a = t / (DK / 32), b = t % (DK / 32);
-        f32x16 acc = zero16(); // dK1 = dP^T Q + Ut dS'^T
-        if (a == 1) mma<32, true, true, T>(acc, sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * b, SM::LK);
-        else mma<C, true, true, T>(acc, sDP, SM::LT, sQ + 32 * b, SM::LK);
-        mma<DV, false, false, T>(acc, sUt + 32 * a * SM::LV, SM::LV, sS + 32 * b * SM::LV, SM::LV);
-        acc_store<T>(stg, (T *)p.dK1 + tile * C * DK, DK, 32 * a, 32 * b, C, acc);
+        lds_barrier();
+        if (has_k) { // dK1 = dP^T Q + Ut dS'^T
+            f32x16 acc = zero16();
+            if (ka == 1) mma<32, true, true, T>(acc, sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb, SM::LK);
+            else mma<C, true, true, T>(acc, sDP, SM::LT, sQ + 32 * kb, SM::LK);
+            mma<DV, false, false, T>(acc, sUt + 32 * ka * SM::LV, SM::LV, sS + 32 * kb * SM::LV, SM::LV);
+            acc_store<T>(stg, (T *)p.dK1 + cur.tile * C * DK, DK, 32 * ka, 32 * kb, C, acc);
+        }
+        lds_barrier(); // every buffer is free for the next tile
+        cur = nxt;
     }
 }
 
@@ -473,7 +497,7 @@ __global__ __launch_bounds__(NTHR) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p) {
 //   dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K;  dV = diag(beta) dVb;
 //   dbeta_i = sum_m X[m][i] dX'[m][i] + sum_j dA[i][j] G[i][j].
 template <typename T, int DK, int DV> struct WySmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40;
+    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40, LK1 = ldc<T>(DK);
     static constexpr bool kXnIsX = sizeof(T) == sizeof(float); // fp32: the inverse itself is the operand
     static constexpr size_t oK = 0;
     static constexpr size_t oV = oK + align16(sizeof(T) * C * LK);            // V, then the fp32 A / X
@@ -485,17 +509,18 @@ template <typename T, int DK, int DV> struct WySmem {
     static constexpr size_t oM = oDX + align16(sizeof(T) * C * LT);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t oDb = oBeta + sizeof(float) * C;
-    static constexpr size_t oStage = align16(oDb + sizeof(float) * 4 * C); // per-wave output staging tiles
-    static constexpr size_t bytes = oStage + 4 * cmax(sizeof(T) * Stage<T>::ELEMS, 0);
+    static constexpr size_t oStage = align16(oDb + sizeof(float) * 4 * C);
+    static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
 };
 
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
+__global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int chunks_total) {
     using SM = WySmem<T, DK, DV>;
     static_assert(!SM::kXnIsX || SM::LT == SM::LF, "fp32 operand copy aliases the inverse");
+    constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);
+    static_assert(KT <= NWC && VT <= NWC, "one output tile per wave");
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * (sizeof(T) * Stage<T>::ELEMS);
-    T *stg = reinterpret_cast<T *>(stg_raw);
+    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + (threadIdx.x >> 6) * Stage<T>::ELEMS;
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sV = reinterpret_cast<T *>(smem + SM::oV);
     float *sX = reinterpret_cast<float *>(smem + SM::oV);
@@ -509,124 +534,127 @@ __global__ __launch_bounds__(NTHR) void k_bwd_wy(SeqMap sm, int H, Ptrs p) {
     float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
+    T *sDK1 = reinterpret_cast<T *>(smem + (SM::kXnIsX ? SM::oXn : SM::oV));
+    static_assert(sizeof(T) * C * SM::LK1 <= (SM::kXnIsX ? SM::szXn : SM::oDW - SM::oV), "dK1 parking space");
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int mi = (wave >> 1) & 1, ni = wave & 1; // waves 0..3: tile of every C x C matrix
+    const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
+    const int ka = wave / (DK / 32), kb = wave % (DK / 32), va = wave / (DV / 32), vbk = wave % (DV / 32);
+    const bool has_k = wave < KT, has_v = wave < VT;
 
-    int n, ic;
-    if (!sm.chunk(blockIdx.x, n, ic)) return;
-    int t0, len, cb;
-    sm.seq(n, t0, len, cb);
-    const int h = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int nvalid = min(C, len - ic * C);
-    const long row0 = (long)t0 + (long)ic * C;
-    const long tile = ((long)(cb + ic) * H + h);
-    const int mi = wave >> 1, ni = wave & 1; // this wave's 32x32 tile of every C x C matrix
-    const bool upper = (mi == 0 && ni == 1);
-
-    { // all global loads are issued before the first LDS store, so their latencies overlap
-        TileRegs<T, C, DK> r_k, r_dw;
-        TileRegs<T, C, DV> r_v, r_du;
-        r_k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r_v.load((const T *)p.v + (row0 * H + h) * DV, (long)H * DV, nvalid);
-        r_dw.load((const T *)p.dW + tile * C * DK, DK, C);
-        r_du.load((const T *)p.dUt + tile * C * DV, DV, C);
-        r_k.store(sK, SM::LK); r_v.store(sV, SM::LV); r_dw.store(sDW, SM::LK); r_du.store(sDU, SM::LV);
-    }
-    if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
-    lds_barrier();
-    f32x16 g = zero16(), dxp = zero16();
-    if (!upper) {
-        mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-        mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-        mma<DV, false, false, T>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
-    }
-    acc_each(g, [&](int r, int c, float &val) { if (32 * ni + c >= 32 * mi + r) val = 0.f; }); // strictly lower G
-    lds_barrier(); // V is dead: its bytes become the fp32 matrix
-    acc_each(g, [&](int r, int c, float &val) { sX[(32 * mi + r) * SM::LF + 32 * ni + c] = sBeta[32 * mi + r] * val; });
-    lds_barrier();
-    tri_inverse_64_inplace<T>(sX, SM::LF, sM, sOp, SM::LO);
-    { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta), X as an operand
-        float part = 0.f;
-        acc_each(dxp, [&](int r, int c, float &val) {
-            const int i = 32 * mi + r, j = 32 * ni + c;
-            part += sX[i * SM::LF + j] * val;
-            val *= sBeta[j];
-        });
-        sDb[(2 * mi + (lane >> 5)) * C + 32 * ni + (lane & 31)] = part; // summed in a fixed order at the end
-        acc_to_lds<T>(sDX, SM::LT, 32 * mi, 32 * ni, dxp);
+    struct Regs {
+        TileRegs<T, C, DK, NTC> k, dw, dk1;
+        TileRegs<T, C, DV, NTC> v, du;
+        float beta;
+    } r;
+    auto fetch = [&](const TilePos &tp) {
+        if (!tp.ok) return;
+        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
+        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
+        r.dw.load((const T *)p.dW + tp.tile * C * DK, DK, C);
+        r.du.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
+        r.dk1.load((const T *)p.dK1 + tp.tile * C * DK, DK, C);
+        r.beta = (tid < tp.nvalid) ? to_f32(((const T *)p.beta)[(tp.row0 + tid) * H + tp.h]) : 0.f;
+    };
+    TileIter it(chunks_total, H);
+    TilePos cur = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
+    fetch(cur);
+    while (it.valid()) {
+        it.next();
+        const TilePos nxt = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
+        if (!cur.ok) { cur = nxt; fetch(cur); continue; }
+        const int nvalid = cur.nvalid, h = cur.h;
+        const long row0 = cur.row0;
+        r.k.store(sK, SM::LK); r.v.store(sV, SM::LV); r.dw.store(sDW, SM::LK); r.du.store(sDU, SM::LV);
+        if (tid < C) sBeta[tid] = r.beta;
+        const TileRegs<T, C, DK, NTC> dk1 = r.dk1; // joins dK at the very end, through this wave's staging tile
+        lds_barrier();
+        fetch(nxt);
+        f32x16 g = zero16(), dxp = zero16();
+        if (cc && !upper) {
+            mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
+            mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
+            mma<DV, false, false, T>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
+        }
+        acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
+        lds_barrier(); // V is dead: its bytes become the fp32 matrix
+        if (cc) acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
+        lds_barrier();
+        tri_inverse_64_inplace<T, NTC>(sX, SM::LF, sM, sOp, SM::LO);
+        if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
+            float part = 0.f;
+            acc_each(dxp, [&](int rr, int c, float &val) {
+                const int i = 32 * mi + rr, j = 32 * ni + c;
+                part += sX[i * SM::LF + j] * val;
+                val *= sBeta[j];
+            });
+            sDb[(2 * mi + (lane >> 5)) * C + 32 * ni + (lane & 31)] = part; // summed in a fixed order at the end
+            acc_to_lds<T>(sDX, SM::LT, 32 * mi, 32 * ni, dxp);
+        }
         if (!SM::kXnIsX)
-            for (int e = tid; e < C * C; e += NTHR) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
-    }
-    lds_barrier();
-    f32x16 m1 = zero16(); // M1 = dX X^T
-    mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
-    constexpr int KB_TILES = 2 * (DK / 32), KB_TPW = (KB_TILES + NWAVE - 1) / NWAVE;
-    f32x16 dKb[KB_TPW];
-#pragma unroll
-    for (int s = 0; s < KB_TPW; ++s) { // dKb = X^T dW (X^T is upper triangular)
-        dKb[s] = zero16();
-        const int t = wave + s * NWAVE;
-        if (t < KB_TILES) {
-            const int a = t / (DK / 32), b = t % (DK / 32);
-            if (a == 1) mma<32, true, true, T>(dKb[s], sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * b, SM::LK);
-            else mma<C, true, true, T>(dKb[s], sXn, SM::LT, sDW + 32 * b, SM::LK);
+            for (int e = tid; e < C * C; e += NTC) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
+        lds_barrier();
+        f32x16 m1 = zero16(); // M1 = dX X^T
+        if (cc) mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
+        f32x16 dKb = zero16(); // dKb = X^T dW (X^T is upper triangular)
+        if (has_k) {
+            if (ka == 1) mma<32, true, true, T>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb, SM::LK);
+            else mma<C, true, true, T>(dKb, sXn, SM::LT, sDW + 32 * kb, SM::LK);
         }
-    }
-    for (int t = wave; t < 2 * (DV / 32); t += NWAVE) { // dV = diag(beta) X^T dU
-        const int a = t / (DV / 32), b = t % (DV / 32);
-        f32x16 acc = zero16();
-        if (a == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * b, SM::LV);
-        else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * b, SM::LV);
-        acc_each(acc, [&](int r, int, float &val) { val *= sBeta[32 * a + r]; });
-        acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * a, 32 * b, nvalid, acc);
-    }
-    lds_barrier(); // dW, dU, dX are dead
-    acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1);
-    lds_barrier();
-    { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah + Ah^T into sDX
-        f32x16 acc = zero16();
-        if (!upper) {
-            if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
-            else mma<C, true, false, T>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
+        if (has_v) { // dV = diag(beta) X^T dU
+            f32x16 acc = zero16();
+            if (va == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * vbk, SM::LV);
+            else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * vbk, SM::LV);
+            acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * va + rr]; });
+            acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va, 32 * vbk, nvalid, acc);
         }
-        const int l31 = lane & 31, hh = lane >> 5;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int i = 32 * mi + 8 * (e >> 2) + 4 * hh + (e & 3), j = 32 * ni + l31;
-            const float da = j < i ? -acc[e] : 0.f;
-            sProd[i * SM::LF + j] = da * g[e];
+        lds_barrier(); // dW, dU, dX are dead
+        if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1);
+        lds_barrier();
+        if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah + Ah^T into sDX
+            f32x16 acc = zero16();
             if (!upper) {
-                if (j < i) {
-                    const T ah = from_f32<T>(sBeta[i] * da);
-                    sDX[i * SM::LT + j] = ah;
-                    sDX[j * SM::LT + i] = ah;
-                } else if (j == i) {
-                    sDX[i * SM::LT + i] = from_f32<T>(0.f);
+                if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
+                else mma<C, true, false, T>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
+            }
+            const int l31 = lane & 31, hh = lane >> 5;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = 32 * mi + 8 * (e >> 2) + 4 * hh + (e & 3), j = 32 * ni + l31;
+                const float da = j < i ? -acc[e] : 0.f;
+                sProd[i * SM::LF + j] = da * g[e];
+                if (!upper) {
+                    if (j < i) {
+                        const T ah = from_f32<T>(sBeta[i] * da);
+                        sDX[i * SM::LT + j] = ah;
+                        sDX[j * SM::LT + i] = ah;
+                    } else if (j == i) {
+                        sDX[i * SM::LT + i] = from_f32<T>(0.f);
+                    }
                 }
             }
         }
-    }
-    lds_barrier();
-#pragma unroll
-    for (int s = 0; s < KB_TPW; ++s) { // dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K
-        const int t = wave + s * NWAVE;
-        if (t < KB_TILES) {
-            const int a = t / (DK / 32), b = t % (DK / 32);
-            const T *k1 = (const T *)p.dK1 + tile * C * DK;
-            acc_each(dKb[s], [&](int r, int c, float &val) {
-                val = val * sBeta[32 * a + r] + to_f32(k1[(32 * a + r) * DK + 32 * b + c]);
+        dk1.store(sDK1, SM::LK1); // dK1 parks where the fp32 inverse (bf16) or the inverse scratch (fp32) used to be
+        lds_barrier();
+        if (has_k) { // dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K
+            acc_each(dKb, [&](int rr, int c, float &val) {
+                val = val * sBeta[32 * ka + rr] + to_f32(sDK1[(32 * ka + rr) * SM::LK1 + 32 * kb + c]);
             });
-            mma<C, false, true, T>(dKb[s], sDX + 32 * a * SM::LT, SM::LT, sK + 32 * b, SM::LK);
-            acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * a, 32 * b, nvalid, dKb[s]);
+            mma<C, false, true, T>(dKb, sDX + 32 * ka * SM::LT, SM::LT, sK + 32 * kb, SM::LK);
+            acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka, 32 * kb, nvalid, dKb);
         }
-    }
-    { // dbeta = column sums from part 1 + row sums of dA o G
-        const int i = tid >> 2, seg = tid & 3;
-        float s = 0.f;
+        if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G
+            const int i = tid >> 2, seg = tid & 3;
+            float s = 0.f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s += sProd[i * SM::LF + seg * 16 + j];
-        s += __shfl_xor(s, 1);
-        s += __shfl_xor(s, 2);
-        if (seg == 0 && i < nvalid)
-            p.dbeta[(row0 + i) * H + h] = s + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+            for (int j = 0; j < 16; ++j) s += sProd[i * SM::LF + seg * 16 + j];
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            if (seg == 0 && i < nvalid)
+                p.dbeta[(row0 + i) * H + h] = s + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+        }
+        lds_barrier();
+        cur = nxt;
     }
 }
 

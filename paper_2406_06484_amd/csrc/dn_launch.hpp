@@ -66,8 +66,12 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
     if (pb.chunks_ub) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     DN_LAUNCH_NT((k_scan_bwd<T, DK, DV>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    if (pb.chunks_ub) DN_LAUNCH((k_bwd_dqkw<T, DK, DV>), gchunk, (DqkwSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    if (pb.chunks_ub) DN_LAUNCH((k_bwd_wy<T, DK, DV>), gchunk, (WySmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if (pb.chunks_ub) {
+        const long tiles = (long)pb.chunks_ub * pb.H;
+        const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
+        DN_LAUNCH_NT((k_bwd_dqkw<T, DK, DV>), gpers, NTC, (DqkwSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        DN_LAUNCH_NT((k_bwd_wy<T, DK, DV>), gpers, NTC, (WySmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+    }
     return 0;
 }
 

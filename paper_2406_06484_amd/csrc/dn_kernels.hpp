@@ -545,7 +545,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
     struct Regs {
         TileRegs<T, C, DK, NTC> k, dw, dk1;
         TileRegs<T, C, DV, NTC> v, du;
-        float beta;
+        T beta; // kept in storage format: converting here would wait for the whole prefetch
     } r;
     auto fetch = [&](const TilePos &tp) {
         if (!tp.ok) return;
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
         r.dw.load((const T *)p.dW + tp.tile * C * DK, DK, C);
         r.du.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
         r.dk1.load((const T *)p.dK1 + tp.tile * C * DK, DK, C);
-        r.beta = (tid < tp.nvalid) ? to_f32(((const T *)p.beta)[(tp.row0 + tid) * H + tp.h]) : 0.f;
+        if (tid < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tid, tp.nvalid - 1)) * H + tp.h];
     };
     TileIter it(chunks_total, H);
     TilePos cur = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
@@ -566,7 +566,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
         r.k.store(sK, SM::LK); r.v.store(sV, SM::LV); r.dw.store(sDW, SM::LK); r.du.store(sDU, SM::LV);
-        if (tid < C) sBeta[tid] = r.beta;
+        if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
         const TileRegs<T, C, DK, NTC> dk1 = r.dk1; // joins dK at the very end, through this wave's staging tile
         lds_barrier();
         fetch(nxt);

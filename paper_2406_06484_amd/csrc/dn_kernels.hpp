@@ -494,7 +494,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p, int 
 // G = K K^T, W = X diag(beta) K, U = X diag(beta) V and incoming dW, dU (= dUt):
 //   dX' = dW K^T + dU V^T;  dX = dX' diag(beta);  dKb = X^T dW;  dVb = X^T dU;
 //   dA = -tril(X^T dX X^T, -1);  Ah = diag(beta) dA;
-//   dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K;  dV = diag(beta) dVb;
+//   dK = dK1 + diag(beta) dKb + Ah K + Ah^T K;  dV = diag(beta) dVb;
 //   dbeta_i = sum_m X[m][i] dX'[m][i] + sum_j dA[i][j] G[i][j].
 template <typename T, int DK, int DV> struct WySmem {
     static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40, LK1 = ldc<T>(DK);
@@ -611,7 +611,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
         lds_barrier(); // dW, dU, dX are dead
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1);
         lds_barrier();
-        if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah + Ah^T into sDX
+        if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {
                 if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
@@ -623,15 +623,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
                 const int i = 32 * mi + 8 * (e >> 2) + 4 * hh + (e & 3), j = 32 * ni + l31;
                 const float da = j < i ? -acc[e] : 0.f;
                 sProd[i * SM::LF + j] = da * g[e];
-                if (!upper) {
-                    if (j < i) {
-                        const T ah = from_f32<T>(sBeta[i] * da);
-                        sDX[i * SM::LT + j] = ah;
-                        sDX[j * SM::LT + i] = ah;
-                    } else if (j == i) {
-                        sDX[i * SM::LT + i] = from_f32<T>(0.f);
-                    }
-                }
+                sDX[i * SM::LT + j] = from_f32<T>(sBeta[i] * da);
             }
         }
         dk1.store(sDK1, SM::LK1); // dK1 parks where the fp32 inverse (bf16) or the inverse scratch (fp32) used to be
@@ -640,7 +632,11 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
             acc_each(dKb, [&](int rr, int c, float &val) {
                 val = val * sBeta[32 * ka + rr] + to_f32(sDK1[(32 * ka + rr) * SM::LK1 + 32 * kb + c]);
             });
-            mma<C, false, true, T>(dKb, sDX + 32 * ka * SM::LT, SM::LT, sK + 32 * kb, SM::LK);
+            // (Ah + Ah^T) K: Ah is strictly lower triangular; its transpose is read through the transposing path
+            if (ka == 0) mma<32, false, true, T>(dKb, sDX, SM::LT, sK + 32 * kb, SM::LK);
+            else mma<C, false, true, T>(dKb, sDX + 32 * SM::LT, SM::LT, sK + 32 * kb, SM::LK);
+            if (ka == 1) mma<32, true, true, T>(dKb, sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb, SM::LK);
+            else mma<C, true, true, T>(dKb, sDX, SM::LT, sK + 32 * kb, SM::LK);
             acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka, 32 * kb, nvalid, dKb);
         }
         if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G

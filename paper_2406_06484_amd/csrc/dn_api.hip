@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_P, off_Ut, off_dUt, off_Sc, off_dSc, off_dW, off_dK1, total;
+    size_t off_coff, off_T, off_P, off_Ut, off_dUt, off_Sc, off_dSc, total;
     size_t esz;
 };
 
@@ -101,7 +101,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
     if (packed && s->L == 0) pb.chunks_ub = 0;
     pl->esz = s->dtype == DN_BF16 ? 2 : 4;
     const size_t tiles = (size_t)pb.chunks_ub * s->H;
-    const size_t tK = up256(tiles * kChunk * s->d_k * pl->esz), tV = up256(tiles * kChunk * s->d_v * pl->esz);
+    const size_t tV = up256(tiles * kChunk * s->d_v * pl->esz);
     const size_t tS = up256(tiles * (size_t)s->d_k * s->d_v * pl->esz);
     size_t o = 0;
     pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * ((size_t)pb.N + 1)) : 0;
@@ -113,8 +113,6 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
         pl->off_dUt = o; o += tV;
         pl->off_Sc = o; o += tS;
         pl->off_dSc = o; o += tS;
-        pl->off_dW = o; o += tK;
-        pl->off_dK1 = o; o += tK;
     }
     pl->total = o;
 }
@@ -130,7 +128,7 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     p->want_pt = want_bwd;
     if (want_bwd) {
         p->Ut = b + pl.off_Ut; p->dUt = b + pl.off_dUt; p->Sc = b + pl.off_Sc;
-        p->dSc = b + pl.off_dSc; p->dW = b + pl.off_dW; p->dK1 = b + pl.off_dK1;
+        p->dSc = b + pl.off_dSc;
     }
 }
 

@@ -135,6 +135,7 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
         const auto b = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
         mfma32(acc, a, b);
     }
+    __builtin_amdgcn_sched_barrier(0); // keep the scheduler from hoisting the next product's operand loads over this one
 }
 
 // A-operand fragments of a 32-row block fetched straight from global memory (row-major, contraction
@@ -164,6 +165,7 @@ __device__ inline void mma_ra(f32x16 &acc, const AFrags<T, KDIM> &a, const T *B,
         const auto b = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
         mfma32(acc, a.f[k0 / KStep<T>::value], b);
     }
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 __device__ inline f32x16 zero16() {

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         TileRegs<T, C, BV, NTS> v;
         AFrags<T, C> t, pf; // rows of T (every wave) and of P = tril(Q K^T) (output waves)
     } ra, rb;
-    auto fetch = [&](Regs &r, int ic) {
+    auto fetch = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         r.t.load((const T *)p.Tm + tile * C * C + 32 * m.ta * C, C, C);
         if (does_o) r.pf.load((const T *)p.P + tile * C * C + 32 * oa * C, C, C);
     };
-    auto step = [&](Regs &r, int ic) {
+    auto step = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         TileRegs<T, C, BV, NTS> d_o;
         AFrags<T, C> t, pt; // rows of T (every wave) and of P^T (the waves that build dUt)
     } ra, rb;
-    auto fetch = [&](Regs &r, int ic) {
+    auto fetch = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         r.t.load((const T *)p.Tm + tile * C * C + 32 * m.ta * C, C, C);
         if (m.does_u) r.pt.load((const T *)p.PT + tile * C * C + 32 * m.ta * C, C, C);
     };
-    auto step = [&](Regs &r, int ic) {
+    auto step = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const long tile = ((long)(cb + ic) * H + h);
         r.q.store(sQ, SM::LQ);
         r.k.store(sK, SM::LK);
@@ -366,10 +366,10 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
 }
 
 // =============================================================================================
-// The two chunk-parallel backward kernels.  Workgroups of 8 wavefronts are persistent: each walks
-// over (chunk, head) tiles with a grid stride, and fetches the next tile's operands into registers
-// while it works on the current one, so global latency is hidden behind the MFMAs of another tile.
-constexpr int NTC = 512, NWC = 8;
+// The chunk-parallel backward kernel.  Workgroups are persistent: each walks over (chunk, head)
+// tiles with a grid stride and requests the next tile's operands (into registers) while it works on
+// the current one, so global latency is hidden behind the second half of the current tile.
+constexpr int NTC = 256, NWC = 4; // one wave per SIMD: the fused kernel wants the whole register file
 
 struct TileIter { // grid-stride walk over (global chunk id, head) tiles
     int id, total, H;
@@ -394,119 +394,30 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
     return tp;
 }
 
-// k_bwd_dqkw: per chunk, with S (chunk-initial state), dS' (gradient w.r.t. the state after the
-// chunk), Ut, dUt:  dP = tril(dO Ut^T); dQ = dO S^T + dP K; dK1 = dP^T Q + Ut dS'^T; dW = -dUt S^T.
-template <typename T, int DK, int DV> struct DqkwSmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldc<T>(DV), LT = ldn<T>(C);
-    static constexpr size_t oDO = 0;
-    static constexpr size_t oUt = oDO + align16(sizeof(T) * C * LV);
-    static constexpr size_t oDUt = oUt + align16(sizeof(T) * C * LV);
-    static constexpr size_t oK = oDUt + align16(sizeof(T) * C * LV);
-    static constexpr size_t oQ = oK + align16(sizeof(T) * C * LK);
-    static constexpr size_t oDP = oQ + align16(sizeof(T) * C * LK);
-    static constexpr size_t oS = oDP + align16(sizeof(T) * C * LT); // S, then dS'
-    static constexpr size_t oStage = oS + align16(sizeof(T) * DK * LV);
-    static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
-};
-
-template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTC) void k_bwd_dqkw(SeqMap sm, int H, Ptrs p, int chunks_total) {
-    using SM = DqkwSmem<T, DK, DV>;
-    constexpr int KT = 2 * (DK / 32); // 32 x 32 tiles of a C x DK matrix
-    static_assert(KT <= NWC, "one output tile per wave");
-    extern __shared__ __align__(16) unsigned char smem[];
-    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + (threadIdx.x >> 6) * Stage<T>::ELEMS;
-    T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
-    T *sUt = reinterpret_cast<T *>(smem + SM::oUt);
-    T *sDUt = reinterpret_cast<T *>(smem + SM::oDUt);
-    T *sK = reinterpret_cast<T *>(smem + SM::oK);
-    T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
-    T *sDP = reinterpret_cast<T *>(smem + SM::oDP);
-    T *sS = reinterpret_cast<T *>(smem + SM::oS);
-    const int wave = threadIdx.x >> 6;
-    const int ka = wave / (DK / 32), kb = wave % (DK / 32); // this wave's tile of dQ, dW, dK1
-    const bool has_k = wave < KT;
-
-    struct Regs {
-        TileRegs<T, C, DV, NTC> d_o, ut, dut;
-        TileRegs<T, DK, DV, NTC> s, ds;
-        TileRegs<T, C, DK, NTC> k, q;
-    } r;
-    auto fetch = [&](const TilePos &tp) {
-        if (!tp.ok) return;
-        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
-        r.ut.load((const T *)p.Ut + tp.tile * C * DV, DV, C);
-        r.s.load((const T *)p.Sc + tp.tile * DK * DV, DV, DK);
-        r.dut.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
-        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
-        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
-        r.ds.load((const T *)p.dSc + tp.tile * DK * DV, DV, DK);
-    };
-    TileIter it(chunks_total, H);
-    TilePos cur = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
-    fetch(cur);
-    while (it.valid()) {
-        it.next();
-        const TilePos nxt = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
-        if (!cur.ok) { cur = nxt; fetch(cur); continue; } // past the last real chunk (packed layout bound)
-        r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LV); r.s.store(sS, SM::LV);
-        r.dut.store(sDUt, SM::LV); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
-        const TileRegs<T, DK, DV, NTC> ds_cur = r.ds; // moves into S's place once S is dead
-        lds_barrier();
-        fetch(nxt);
-        if (wave < 4) { // dP = tril(dO Ut^T)
-            const int a = wave >> 1, b = wave & 1;
-            f32x16 acc = zero16();
-            if (!(a == 0 && b == 1)) mma<DV, false, false, T>(acc, sDO + 32 * a * SM::LV, SM::LV, sUt + 32 * b * SM::LV, SM::LV);
-            acc_each(acc, [&](int rr, int c, float &val) { if (32 * b + c > 32 * a + rr) val = 0.f; });
-            acc_to_lds<T>(sDP, SM::LT, 32 * a, 32 * b, acc);
-        }
-        f32x16 dq = zero16();
-        if (has_k) {
-            mma<DV, false, false, T>(dq, sDO + 32 * ka * SM::LV, SM::LV, sS + 32 * kb * SM::LV, SM::LV); // dO S^T
-            f32x16 w = zero16(); // dW = -dUt S^T
-            mma<DV, false, false, T>(w, sDUt + 32 * ka * SM::LV, SM::LV, sS + 32 * kb * SM::LV, SM::LV);
-            acc_each(w, [&](int, int, float &val) { val = -val; });
-            acc_store<T>(stg, (T *)p.dW + cur.tile * C * DK, DK, 32 * ka, 32 * kb, C, w);
-        }
-        lds_barrier(); // dP visible; S no longer needed
-        ds_cur.store(sS, SM::LV);
-        if (has_k) { // dQ += dP K
-            if (ka == 0) mma<32, false, true, T>(dq, sDP, SM::LT, sK + 32 * kb, SM::LK);
-            else mma<C, false, true, T>(dq, sDP + 32 * SM::LT, SM::LT, sK + 32 * kb, SM::LK);
-            acc_store<T>(stg, (T *)p.dq + (cur.row0 * H + cur.h) * DK, (long)H * DK, 32 * ka, 32 * kb, cur.nvalid, dq);
-        }
-        lds_barrier();
-        if (has_k) { // dK1 = dP^T Q + Ut dS'^T
-            f32x16 acc = zero16();
-            if (ka == 1) mma<32, true, true, T>(acc, sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb, SM::LK);
-            else mma<C, true, true, T>(acc, sDP, SM::LT, sQ + 32 * kb, SM::LK);
-            mma<DV, false, false, T>(acc, sUt + 32 * ka * SM::LV, SM::LV, sS + 32 * kb * SM::LV, SM::LV);
-            acc_store<T>(stg, (T *)p.dK1 + cur.tile * C * DK, DK, 32 * ka, 32 * kb, C, acc);
-        }
-        lds_barrier(); // every buffer is free for the next tile
-        cur = nxt;
-    }
-}
-
-// =============================================================================================
-// k_bwd_wy: adjoint of the UT transform (Eq. 10-11).  With X = (I+A)^-1, A = tril(diag(beta) G,-1),
-// G = K K^T, W = X diag(beta) K, U = X diag(beta) V and incoming dW, dU (= dUt):
-//   dX' = dW K^T + dU V^T;  dX = dX' diag(beta);  dKb = X^T dW;  dVb = X^T dU;
-//   dA = -tril(X^T dX X^T, -1);  Ah = diag(beta) dA;
-//   dK = dK1 + diag(beta) dKb + Ah K + Ah^T K;  dV = diag(beta) dVb;
-//   dbeta_i = sum_m X[m][i] dX'[m][i] + sum_j dA[i][j] G[i][j].
-template <typename T, int DK, int DV> struct WySmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40, LK1 = ldc<T>(DK);
+// k_bwd_chunk: everything of the backward pass that is local to one chunk, given the chunk-initial
+// state S, the gradient dS' w.r.t. the state after the chunk, Ut and dUt from the two scans:
+//   adjoint of Eq. 8-9:  dP = tril(dO Ut^T); dQ = dO S^T + dP K; dK1 = dP^T Q + Ut dS'^T; dW = -dUt S^T
+//   adjoint of Eq. 10-11, with X = (I+A)^-1, A = tril(diag(beta) G,-1), G = K K^T, dU = dUt:
+//     dX' = dW K^T + dU V^T;  dX = dX' diag(beta);  dKb = X^T dW;  dV = diag(beta) X^T dU;
+//     dA = -tril(X^T dX X^T, -1);  Ah = diag(beta) dA;
+//     dK = dK1 + diag(beta) dKb + Ah K + Ah^T K;
+//     dbeta_i = sum_m X[m][i] dX'[m][i] + sum_j dA[i][j] G[i][j].
+// dW and dK1 never leave the chip.  LDS buffers are reused as operands die; V and dS' wait in
+// registers until their buffer is free.
+template <typename T, int DK, int DV> struct ChunkSmem {
+    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40, LSV = ldn<T>(DV);
     static constexpr bool kXnIsX = sizeof(T) == sizeof(float); // fp32: the inverse itself is the operand
-    static constexpr size_t oK = 0;
-    static constexpr size_t oV = oK + align16(sizeof(T) * C * LK);            // V, then the fp32 A / X
-    static constexpr size_t oDW = oV + align16(cmax(sizeof(T) * C * LV, sizeof(float) * C * LF)); // dW, then dA o G (fp32)
-    static constexpr size_t oDU = oDW + align16(cmax(sizeof(T) * C * LK, sizeof(float) * C * LF)); // dU, then M1^T
-    static constexpr size_t oXn = oDU + align16(cmax(sizeof(T) * C * LV, sizeof(T) * C * LT));   // inverse operands, then X as T
-    static constexpr size_t szXn = cmax(kXnIsX ? 0 : sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO);
-    static constexpr size_t oDX = oXn + align16(szXn);                        // dX, later Ah + Ah^T
-    static constexpr size_t oM = oDX + align16(sizeof(T) * C * LT);
+    static constexpr size_t szX = sizeof(float) * C * LF, szCC = sizeof(T) * C * LT;
+    static constexpr size_t oB1 = 0;                                   // dO; V; dA o G (fp32)
+    static constexpr size_t oB2 = oB1 + align16(cmax(sizeof(T) * C * LV, szX));     // Ut; dW
+    static constexpr size_t oB3 = oB2 + align16(cmax(sizeof(T) * C * LV, sizeof(T) * C * LK)); // dUt
+    static constexpr size_t oB4 = oB3 + align16(sizeof(T) * C * LV);   // K
+    static constexpr size_t oB5 = oB4 + align16(sizeof(T) * C * LK);   // Q; inverse scratch; M1^T
+    static constexpr size_t oB6 = oB5 + align16(cmax(sizeof(T) * C * LK, szCC)); // dP; (inverse scratch); dX; Ah
+    static constexpr size_t oB7 = oB6 + align16(szCC);                 // S; dS'; fp32 A / X, then X as T
+    static constexpr size_t szB7 = cmax(sizeof(T) * DK * LSV, align16(szX) + (kXnIsX ? 0 : szCC));
+    static_assert(sizeof(T) * 4 * 32 * LO <= oB7 - oB5, "the inverse's operand scratch spans the dead Q and dP buffers");
+    static constexpr size_t oM = oB7 + align16(szB7);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t oDb = oBeta + sizeof(float) * C;
     static constexpr size_t oStage = align16(oDb + sizeof(float) * 4 * C);
@@ -514,74 +425,118 @@ template <typename T, int DK, int DV> struct WySmem {
 };
 
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int chunks_total) {
-    using SM = WySmem<T, DK, DV>;
+__global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int chunks_total) {
+    using SM = ChunkSmem<T, DK, DV>;
     static_assert(!SM::kXnIsX || SM::LT == SM::LF, "fp32 operand copy aliases the inverse");
-    constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);
-    static_assert(KT <= NWC && VT <= NWC, "one output tile per wave");
+    constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);        // 32 x 32 tiles of a C x DK / C x DV matrix
+    constexpr int KW = (KT + NWC - 1) / NWC, VW = (VT + NWC - 1) / NWC; // ... per wave
     extern __shared__ __align__(16) unsigned char smem[];
     T *stg = reinterpret_cast<T *>(smem + SM::oStage) + (threadIdx.x >> 6) * Stage<T>::ELEMS;
-    T *sK = reinterpret_cast<T *>(smem + SM::oK);
-    T *sV = reinterpret_cast<T *>(smem + SM::oV);
-    float *sX = reinterpret_cast<float *>(smem + SM::oV);
-    T *sDW = reinterpret_cast<T *>(smem + SM::oDW);
-    float *sProd = reinterpret_cast<float *>(smem + SM::oDW);
-    T *sDU = reinterpret_cast<T *>(smem + SM::oDU);
-    T *sM1T = reinterpret_cast<T *>(smem + SM::oDU);
-    T *sOp = reinterpret_cast<T *>(smem + SM::oXn);
-    T *sXn = SM::kXnIsX ? reinterpret_cast<T *>(smem + SM::oV) : reinterpret_cast<T *>(smem + SM::oXn);
-    T *sDX = reinterpret_cast<T *>(smem + SM::oDX);
+    T *sDO = reinterpret_cast<T *>(smem + SM::oB1), *sV = sDO;
+    float *sProd = reinterpret_cast<float *>(smem + SM::oB1);
+    T *sUt = reinterpret_cast<T *>(smem + SM::oB2), *sDW = sUt;
+    T *sDU = reinterpret_cast<T *>(smem + SM::oB3);
+    T *sK = reinterpret_cast<T *>(smem + SM::oB4);
+    T *sQ = reinterpret_cast<T *>(smem + SM::oB5), *sM1T = sQ;
+    T *sOp = reinterpret_cast<T *>(smem + SM::oB5); // Q and dP are dead by the time of the inverse
+    T *sDP = reinterpret_cast<T *>(smem + SM::oB6), *sDX = sDP;
+    T *sS = reinterpret_cast<T *>(smem + SM::oB7);
+    float *sX = reinterpret_cast<float *>(smem + SM::oB7);
+    T *sXn = reinterpret_cast<T *>(smem + SM::oB7 + (SM::kXnIsX ? 0 : align16(SM::szX)));
     float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
-    T *sDK1 = reinterpret_cast<T *>(smem + (SM::kXnIsX ? SM::oXn : SM::oV));
-    static_assert(sizeof(T) * C * SM::LK1 <= (SM::kXnIsX ? SM::szXn : SM::oDW - SM::oV), "dK1 parking space");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int mi = (wave >> 1) & 1, ni = wave & 1; // waves 0..3: tile of every C x C matrix
-    const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
-    const int ka = wave / (DK / 32), kb = wave % (DK / 32), va = wave / (DV / 32), vbk = wave % (DV / 32);
-    const bool has_k = wave < KT, has_v = wave < VT;
+    const int mi = wave >> 1, ni = wave & 1; // this wave's tile of every C x C matrix
+    const bool upper = (mi == 0 && ni == 1);
+    // tile number sI of this wave in a C x DK (C x DV) matrix: row block ka, column block kb
+    auto kt = [&](int sI) __attribute__((always_inline)) { return wave + sI * NWC; };
+    auto ka = [&](int sI) __attribute__((always_inline)) { return kt(sI) / (DK / 32); };
+    auto kb = [&](int sI) __attribute__((always_inline)) { return kt(sI) % (DK / 32); };
+    auto va = [&](int sI) __attribute__((always_inline)) { return kt(sI) / (DV / 32); };
+    auto vbk = [&](int sI) __attribute__((always_inline)) { return kt(sI) % (DV / 32); };
 
     struct Regs {
-        TileRegs<T, C, DK, NTC> k, dw, dk1;
-        TileRegs<T, C, DV, NTC> v, du;
+        TileRegs<T, C, DV, NTC> d_o, ut, dut, v;
+        TileRegs<T, DK, DV, NTC> s, ds;
+        TileRegs<T, C, DK, NTC> k, q;
         T beta; // kept in storage format: converting here would wait for the whole prefetch
     } r;
-    auto fetch = [&](const TilePos &tp) {
+    auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
         if (!tp.ok) return;
+        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
+        r.ut.load((const T *)p.Ut + tp.tile * C * DV, DV, C);
+        r.s.load((const T *)p.Sc + tp.tile * DK * DV, DV, DK);
+        r.dut.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
         r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
-        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
-        r.dw.load((const T *)p.dW + tp.tile * C * DK, DK, C);
-        r.du.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
-        r.dk1.load((const T *)p.dK1 + tp.tile * C * DK, DK, C);
+        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
         if (tid < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tid, tp.nvalid - 1)) * H + tp.h];
+        r.ds.load((const T *)p.dSc + tp.tile * DK * DV, DV, DK);
+        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
     };
-    TileIter it(chunks_total, H);
-    TilePos cur = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
-    fetch(cur);
-    while (it.valid()) {
-        it.next();
-        const TilePos nxt = it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false};
-        if (!cur.ok) { cur = nxt; fetch(cur); continue; }
+    auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
+
+    for (TileIter it(chunks_total, H); it.valid(); it.next()) {
+        const TilePos cur = pos_of(it);
+        if (!cur.ok) continue; // packed layout: past the last real chunk
+        fetch(cur);
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
-        r.k.store(sK, SM::LK); r.v.store(sV, SM::LV); r.dw.store(sDW, SM::LK); r.du.store(sDU, SM::LV);
+        // ---- adjoint of Eq. 8-9
+        r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LV); r.s.store(sS, SM::LSV);
+        r.dut.store(sDU, SM::LV); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
         if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
-        const TileRegs<T, C, DK, NTC> dk1 = r.dk1; // joins dK at the very end, through this wave's staging tile
         lds_barrier();
-        fetch(nxt);
+        { // dP = tril(dO Ut^T)
+            f32x16 acc = zero16();
+            if (!upper) mma<DV, false, false, T>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni * SM::LV, SM::LV);
+            acc_each(acc, [&](int rr, int c, float &val) { if (32 * ni + c > 32 * mi + rr) val = 0.f; });
+            acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc);
+        }
+        f32x16 dq[KW], dw[KW], dk1[KW];
+#pragma unroll
+        for (int sI = 0; sI < KW; ++sI) {
+            dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
+            if (kt(sI) < KT) {
+                mma<DV, false, false, T>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI) * SM::LSV, SM::LSV); // dO S^T
+                mma<DV, false, false, T>(dw[sI], sDU + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI) * SM::LSV, SM::LSV); // dUt S^T
+            }
+        }
+        lds_barrier(); // dP visible; S is dead
+        r.ds.store(sS, SM::LSV);
+#pragma unroll
+        for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dQ += dP K
+            if (ka(sI) == 0) mma<32, false, true, T>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK);
+            else mma<C, false, true, T>(dq[sI], sDP + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
+            acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI]);
+        }
+        lds_barrier();
+#pragma unroll
+        for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
+            if (ka(sI) == 1) mma<32, true, true, T>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK);
+            else mma<C, true, true, T>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK);
+            mma<DV, false, false, T>(dk1[sI], sUt + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI) * SM::LSV, SM::LSV);
+        }
+        lds_barrier(); // dO, Ut, Q, dP, dS' are dead
+        // ---- adjoint of Eq. 10-11
+#pragma unroll
+        for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dW = -dUt S^T, as an operand
+            acc_each(dw[sI], [&](int, int, float &val) { val = -val; });
+            acc_to_lds<T>(sDW, SM::LK, 32 * ka(sI), 32 * kb(sI), dw[sI]);
+        }
+        r.v.store(sV, SM::LV);
+        lds_barrier();
         f32x16 g = zero16(), dxp = zero16();
-        if (cc && !upper) {
+        if (!upper) {
             mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
             mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
             mma<DV, false, false, T>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
         }
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
-        lds_barrier(); // V is dead: its bytes become the fp32 matrix
-        if (cc) acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
-        lds_barrier();
+        acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
+        lds_barrier(); // V is dead
         tri_inverse_64_inplace<T, NTC>(sX, SM::LF, sM, sOp, SM::LO);
-        if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
+        { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
             float part = 0.f;
             acc_each(dxp, [&](int rr, int c, float &val) {
                 const int i = 32 * mi + rr, j = 32 * ni + c;
@@ -595,23 +550,26 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
             for (int e = tid; e < C * C; e += NTC) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
         lds_barrier();
         f32x16 m1 = zero16(); // M1 = dX X^T
-        if (cc) mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
-        f32x16 dKb = zero16(); // dKb = X^T dW (X^T is upper triangular)
-        if (has_k) {
-            if (ka == 1) mma<32, true, true, T>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb, SM::LK);
-            else mma<C, true, true, T>(dKb, sXn, SM::LT, sDW + 32 * kb, SM::LK);
+        mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
+#pragma unroll
+        for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dKb = X^T dW (X^T is upper triangular)
+            f32x16 dKb = zero16();
+            if (ka(sI) == 1) mma<32, true, true, T>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb(sI), SM::LK);
+            else mma<C, true, true, T>(dKb, sXn, SM::LT, sDW + 32 * kb(sI), SM::LK);
+            acc_each(dKb, [&](int rr, int, float &val) { val *= sBeta[32 * ka(sI) + rr]; });
+            dk1[sI] += dKb; // dK1 + diag(beta) dKb
         }
-        if (has_v) { // dV = diag(beta) X^T dU
+#pragma unroll
+        for (int sI = 0; sI < VW; ++sI) if (kt(sI) < VT) { // dV = diag(beta) X^T dU
             f32x16 acc = zero16();
-            if (va == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * vbk, SM::LV);
-            else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * vbk, SM::LV);
-            acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * va + rr]; });
-            acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va, 32 * vbk, nvalid, acc);
+            if (va(sI) == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * vbk(sI), SM::LV);
+            else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * vbk(sI), SM::LV);
+            acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * va(sI) + rr]; });
+            acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
         }
-        lds_barrier(); // dW, dU, dX are dead
-        if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1);
-        lds_barrier();
-        if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
+        acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
+        lds_barrier(); // dX is dead
+        { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {
                 if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
@@ -626,31 +584,26 @@ __global__ __launch_bounds__(NTC) void k_bwd_wy(SeqMap sm, int H, Ptrs p, int ch
                 sDX[i * SM::LT + j] = from_f32<T>(sBeta[i] * da);
             }
         }
-        dk1.store(sDK1, SM::LK1); // dK1 parks where the fp32 inverse (bf16) or the inverse scratch (fp32) used to be
         lds_barrier();
-        if (has_k) { // dK = dK1 + diag(beta) dKb + (Ah + Ah^T) K
-            acc_each(dKb, [&](int rr, int c, float &val) {
-                val = val * sBeta[32 * ka + rr] + to_f32(sDK1[(32 * ka + rr) * SM::LK1 + 32 * kb + c]);
-            });
-            // (Ah + Ah^T) K: Ah is strictly lower triangular; its transpose is read through the transposing path
-            if (ka == 0) mma<32, false, true, T>(dKb, sDX, SM::LT, sK + 32 * kb, SM::LK);
-            else mma<C, false, true, T>(dKb, sDX + 32 * SM::LT, SM::LT, sK + 32 * kb, SM::LK);
-            if (ka == 1) mma<32, true, true, T>(dKb, sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb, SM::LK);
-            else mma<C, true, true, T>(dKb, sDX, SM::LT, sK + 32 * kb, SM::LK);
-            acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka, 32 * kb, nvalid, dKb);
-        }
-        if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G
-            const int i = tid >> 2, seg = tid & 3;
-            float s = 0.f;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s += sProd[i * SM::LF + seg * 16 + j];
-            s += __shfl_xor(s, 1);
-            s += __shfl_xor(s, 2);
-            if (seg == 0 && i < nvalid)
-                p.dbeta[(row0 + i) * H + h] = s + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+        for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK = dK1 + diag(beta) dKb + Ah K + Ah^T K; Ah is strictly lower triangular
+            if (ka(sI) == 0) mma<32, false, true, T>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
+            else mma<C, false, true, T>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
+            if (ka(sI) == 1) mma<32, true, true, T>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK);
+            else mma<C, true, true, T>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
+            acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
         }
-        lds_barrier();
-        cur = nxt;
+        { // dbeta = column sums from part 1 + row sums of dA o G
+            const int i = tid >> 2, seg = tid & 3;
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sum += sProd[i * SM::LF + seg * 16 + j];
+            sum += __shfl_xor(sum, 1);
+            sum += __shfl_xor(sum, 2);
+            if (seg == 0 && i < nvalid)
+                p.dbeta[(row0 + i) * H + h] = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+        }
+        lds_barrier(); // every buffer is free for the next tile
     }
 }
 

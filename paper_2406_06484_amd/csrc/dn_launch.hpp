@@ -38,13 +38,11 @@ template <typename T, int DK, int DV> size_t max_lds_bytes() {
     static_assert(PrepSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_wy_prep LDS");
     static_assert(ScanFwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_fwd LDS");
     static_assert(ScanBwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_bwd LDS");
-    static_assert(DqkwSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_dqkw LDS");
-    static_assert(WySmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_wy LDS");
+    static_assert(ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_chunk LDS");
     size_t m = PrepSmem<T, DK, DV>::bytes;
     if (ScanFwdSmem<T, DK, DV>::bytes > m) m = ScanFwdSmem<T, DK, DV>::bytes;
     if (ScanBwdSmem<T, DK, DV>::bytes > m) m = ScanBwdSmem<T, DK, DV>::bytes;
-    if (DqkwSmem<T, DK, DV>::bytes > m) m = DqkwSmem<T, DK, DV>::bytes;
-    if (WySmem<T, DK, DV>::bytes > m) m = WySmem<T, DK, DV>::bytes;
+    if (ChunkSmem<T, DK, DV>::bytes > m) m = ChunkSmem<T, DK, DV>::bytes;
     return m;
 }
 
@@ -69,8 +67,7 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
-        DN_LAUNCH_NT((k_bwd_dqkw<T, DK, DV>), gpers, NTC, (DqkwSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
-        DN_LAUNCH_NT((k_bwd_wy<T, DK, DV>), gpers, NTC, (WySmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
     }
     return 0;
 }

@@ -81,7 +81,9 @@ int validate_shape(const dn_shape *s, const Impl **impl) {
     }
     // 32-bit row indices and grid limits
     const long long rows = (long long)s->B * s->L;
-    if (rows * s->H >= (1ll << 31) || s->H > 65535) return DN_ERR_SHAPE;
+    // H also bounds the byte extent of one strided tile (128 rows of H * d elements), which must
+    // stay inside the 1 GiB window of a buffer descriptor
+    if (rows * s->H >= (1ll << 31) || s->H > 8192) return DN_ERR_SHAPE;
     const long long nseq = s->cu_seqlens ? s->num_seqs : s->B;
     if (nseq > 65535) return DN_ERR_SHAPE;
     *impl = find_impl(s);

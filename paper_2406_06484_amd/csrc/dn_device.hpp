@@ -24,6 +24,19 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // same launch.
 __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// Global loads go through raw buffer descriptors: one 32-bit per-lane offset serves a whole tile
+// (the row step rides in the scalar offset), and rows past the end of a ragged chunk are masked by
+// pointing their lanes beyond the descriptor's range, which makes the hardware return zeros.
+// This keeps 64-bit per-load address pairs and exec-mask branches out of the prefetch code.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kBufRange = 0x40000000; // bytes covered by a descriptor; offsets >= this read as zero
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, kBufRange, 0x00020000);
+}
+__device__ inline uint4 buf_load16(__amdgpu_buffer_rsrc_t rs, int voff, int soff) {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
+}
+
 // Per-element-type constants: LDS row padding (elements) and elements per 16 bytes.
 template <typename T> struct El;
 template <> struct El<float> { static constexpr int PAD = 4; static constexpr int VEC = 4; };
@@ -143,18 +156,22 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
 template <typename T> struct FragOf;
 template <> struct FragOf<bf16> { typedef bf16x8 type; static constexpr int KPL = 8; };
 template <> struct FragOf<float> { typedef float type; static constexpr int KPL = 1; };
+__device__ inline bf16x8 frag_from_buffer(__amdgpu_buffer_rsrc_t rs, int voff, int soff, bf16 *) {
+    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
+}
+__device__ inline float frag_from_buffer(__amdgpu_buffer_rsrc_t rs, int voff, int soff, float *) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, 0));
+}
 template <typename T, int KDIM> struct AFrags {
     static constexpr int N = KDIM / KStep<T>::value;
     typename FragOf<T>::type f[N];
     // base: row 0 of the block, k = 0; rows >= nvalid read as zero
     __device__ inline void load(const T *base, long ld, int nvalid) {
         const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
-        const T *p = base + (long)r * ld + h * FragOf<T>::KPL;
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(base);
+        const int voff = r < nvalid ? (r * (int)ld + h * FragOf<T>::KPL) * (int)sizeof(T) : kBufRange;
 #pragma unroll
-        for (int s = 0; s < N; ++s) {
-            typename FragOf<T>::type z = {};
-            f[s] = r < nvalid ? *reinterpret_cast<const typename FragOf<T>::type *>(p + s * KStep<T>::value) : z;
-        }
+        for (int s = 0; s < N; ++s) f[s] = frag_from_buffer(rs, voff, s * KStep<T>::value * (int)sizeof(T), (T *)nullptr);
     }
 };
 // acc += A(registers) * B(LDS) over the contraction range [KBEG, KEND)
@@ -265,33 +282,20 @@ __device__ inline void acc_to_global_t(T *dst, long ld, int row0, int col0, cons
 }
 
 // ---------------------------------------------------------------------------------------------
-// Global -> LDS: ROWS x COLS tile, 16-byte loads, rows >= nvalid become zero.
-template <typename T, int ROWS, int COLS>
-__device__ inline void load_tile(T *dst, int ld, const T *src, long row_stride, int nvalid) {
-    constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NTHR / TPR;
-    static_assert(COLS % VEC == 0 && NTHR % TPR == 0 && ROWS % RPI == 0, "tile shape");
-    const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
-#pragma unroll
-    for (int r0 = 0; r0 < ROWS; r0 += RPI) {
-        const int r = r0 + tr;
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (r < nvalid) val = *reinterpret_cast<const uint4 *>(src + (long)r * row_stride + tc);
-        *reinterpret_cast<uint4 *>(dst + r * ld + tc) = val;
-    }
-}
-// The same tile fetched into registers first (to be parked while LDS is busy) and stored later.
+// A ROWS x COLS tile fetched from global memory into registers (16 bytes per lane and step; rows >=
+// nvalid read as zero), to be parked while LDS is busy and stored to LDS later.
 template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
     static constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NT / TPR, NIT = ROWS / RPI;
     static_assert(COLS % VEC == 0 && NT % TPR == 0 && ROWS % RPI == 0, "tile shape");
     uint4 v[NIT];
     __device__ inline void load(const T *src, long row_stride, int nvalid) {
         const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
+        const int rs_bytes = (int)row_stride * (int)sizeof(T);
+        const int voff = tr * rs_bytes + tc * (int)sizeof(T);
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int r = it * RPI + tr;
-            v[it] = make_uint4(0, 0, 0, 0);
-            if (r < nvalid) v[it] = *reinterpret_cast<const uint4 *>(src + (long)r * row_stride + tc);
-        }
+        for (int it = 0; it < NIT; ++it)
+            v[it] = buf_load16(rs, it * RPI + tr < nvalid ? voff : kBufRange, it * RPI * rs_bytes);
     }
     __device__ inline void store(T *dst, int ld) const {
         const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
@@ -299,6 +303,16 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
         for (int it = 0; it < NIT; ++it) *reinterpret_cast<uint4 *>(dst + (it * RPI + tr) * ld + tc) = v[it];
     }
 };
+// ---------------------------------------------------------------------------------------------
+// Global -> LDS: ROWS x COLS tile, 16-byte loads, rows >= nvalid become zero.
+template <typename T, int ROWS, int COLS>
+__device__ inline void load_tile(T *dst, int ld, const T *src, long row_stride, int nvalid) {
+    constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NTHR / TPR;
+    static_assert(COLS % VEC == 0 && NTHR % TPR == 0 && ROWS % RPI == 0, "tile shape");
+    TileRegs<T, ROWS, COLS> regs;
+    regs.load(src, row_stride, nvalid);
+    regs.store(dst, ld);
+}
 // LDS -> global, ROWS x COLS, rows >= nvalid dropped
 template <typename T, int ROWS, int COLS>
 __device__ inline void store_tile(T *dst, long row_stride, const T *src, int ld, int nvalid) {

@@ -33,19 +33,40 @@ def model_flops_per_token_head(d: int, c: int = C):
 
 def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
     """Dense-tile FLOPs one (chunk, head) costs in each kernel (what that kernel contracts)."""
-    if "k_wy_prep" in name:      # K K^T, forward substitution, T K, T V
-        return 6 * c * c * d + (2.0 / 3.0) * c ** 3
-    if "k_scan_fwd" in name and "true" in name:   # state recompute: W S, K^T Ut
-        return 4 * c * d * d
-    if "k_scan_fwd" in name:     # W S, Q S, K^T Ut, Q K^T, P Ut
-        return 6 * c * d * d + 4 * c * c * d
-    if "k_scan_bwd" in name:     # K dS, Q^T dO, W^T dUt, Q K^T, P^T dO
-        return 6 * c * d * d + 4 * c * c * d
-    if "k_bwd_dqkw" in name:     # dO S^T, dUt S^T, Ut dS^T, dO Ut^T, dP K, dP^T Q
+    if "k_wy_prep" in name:      # K K^T, Q K^T, forward substitution
+        return 4 * c * c * d + (2.0 / 3.0) * c ** 3
+    if "k_scan_fwd" in name and "true" in name:   # state recompute: T K, T V, W S, K^T Ut
+        return 4 * c * d * d + 4 * c * c * d
+    if "k_scan_fwd" in name:     # T K, T V, P Ut (3 x 2C^2 d); W S, Q S, K^T Ut (3 x 2Cd^2)
         return 6 * c * d * d + 6 * c * c * d
-    if "k_bwd_wy" in name:       # K K^T, dW K^T, dU V^T, X^T dW, X^T dU, (Ah+Ah^T) K, dX X^T, X^T M1, inverse
-        return 12 * c * c * d + 4 * c ** 3 + (2.0 / 3.0) * c ** 3
+    if "k_scan_bwd" in name:     # T K, P^T dO (2 x 2C^2 d); K dS, Q^T dO, W^T dUt (3 x 2Cd^2)
+        return 6 * c * d * d + 4 * c * c * d
+    if "k_bwd_chunk" in name:
+        # adjoint of Eq. 8-9: dO S^T, dUt S^T, Ut dS^T (3 x 2Cd^2); dO Ut^T, dP K, dP^T Q (3 x 2C^2 d)
+        # adjoint of Eq. 10-11: K K^T, dW K^T, dU V^T, X^T dW, X^T dU, Ah K, Ah^T K (7 x 2C^2 d);
+        #                       dX X^T, X^T M1 (2 x 2C^3); forward substitution (2/3 C^3)
+        return 6 * c * d * d + 20 * c * c * d + 4 * c ** 3 + (2.0 / 3.0) * c ** 3
     return 0.0
+
+
+# HBM bytes per launch of each kernel on this workload: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each
+# scaled by what the same counter reads for a plain 256 MiB device copy (factors 2.000 and 1.000);
+# summary and commands in profiles/hbm_traffic_cfg2_fwd_bwd.txt.  The counters cannot be read from
+# inside this script, so the figures are carried here and refreshed whenever the kernels change.
+MEASURED_HBM_BYTES = {
+    "k_wy_prep": 195.1e6,
+    "k_scan_fwd<T, DK, DV, false>": 344.1e6,
+    "k_scan_fwd<T, DK, DV, true>": 369.7e6,
+    "k_scan_bwd": 478.3e6,
+    "k_bwd_chunk": 886.3e6,
+}
+
+
+def measured_traffic(name: str):
+    for key, val in MEASURED_HBM_BYTES.items():
+        if name.startswith(key):
+            return val
+    return None
 
 
 def main() -> int:
@@ -54,6 +75,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy, as the reference dispatch that scales the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -86,6 +110,12 @@ def main() -> int:
         dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
         return dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -127,8 +157,12 @@ def main() -> int:
     dom = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
     fwd_f, bwd_f = model_flops_per_token_head(d)
     model_tflops = (fwd_f + bwd_f) * H * value / 1e12
+    traffic = measured_traffic(dom)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None}
+                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic}
+    if traffic:  # the same kernel against the HBM roof, from the measured bytes
+        gbs = traffic / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
+        roofline["hbm"] = {"achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4)}
 
     out = {
         "metric": "DeltaNet layer fwd+bwd tokens/s at H=16,d=128,L=2048; % bf16 MFMA peak",

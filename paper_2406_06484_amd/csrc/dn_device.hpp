@@ -288,8 +288,9 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
     static constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NT / TPR, NIT = ROWS / RPI;
     static_assert(COLS % VEC == 0 && NT % TPR == 0 && ROWS % RPI == 0, "tile shape");
     uint4 v[NIT];
-    __device__ inline void load(const T *src, long row_stride, int nvalid) {
-        const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
+    // `t` is the caller's index among the NT threads that share the tile (defaults to the whole workgroup)
+    __device__ inline void load(const T *src, long row_stride, int nvalid, int t = threadIdx.x) {
+        const int tr = t / TPR, tc = (t % TPR) * VEC;
         const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
         const int rs_bytes = (int)row_stride * (int)sizeof(T);
         const int voff = tr * rs_bytes + tc * (int)sizeof(T);
@@ -297,8 +298,8 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
         for (int it = 0; it < NIT; ++it)
             v[it] = buf_load16(rs, it * RPI + tr < nvalid ? voff : kBufRange, it * RPI * rs_bytes);
     }
-    __device__ inline void store(T *dst, int ld) const {
-        const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
+    __device__ inline void store(T *dst, int ld, int t = threadIdx.x) const {
+        const int tr = t / TPR, tc = (t % TPR) * VEC;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) *reinterpret_cast<uint4 *>(dst + (it * RPI + tr) * ld + tc) = v[it];
     }

@@ -108,12 +108,14 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
 
 // =============================================================================================
 // The two chain-serial kernels.  One workgroup of 8 wavefronts owns one chain and BV = 64 columns
-// of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.  Operand tiles
-// are fetched two chunks ahead into two alternating register sets, so global latency overlaps the
-// MFMAs.  W = T K (Eq. 11) is rebuilt per chunk from the 64 x 64 T.  Workgroup ids are laid out so
-// that the v-blocks of one chain land on the same XCD (ids are dealt round-robin over the 8 XCDs)
-// and share its L2 for the Q, K, T tiles they all read.
-constexpr int NTS = 512, NWS = 8; // threads / waves of a scan workgroup
+// of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.
+// Waves 0..3 carry the dependent chain (Ut, then the state update); waves 4..7 have the lighter
+// off-chain work and double as loaders: they alone issue the global loads (two chunks ahead, into
+// two alternating register sets) and move them to LDS, so the chain waves never queue behind the
+// CU's 64 B/clk vector-memory path.  W = T K (Eq. 11) is rebuilt per chunk from the 64 x 64 T.
+// Workgroup ids are laid out so that the v-blocks of one chain land on the same XCD (ids are dealt
+// round-robin over the 8 XCDs) and share its L2 for the Q, K, T tiles they both read.
+constexpr int NTS = 512, NWS = 8, NTL = 256; // threads / waves of a scan workgroup; loader threads
 template <int DV> struct VBlock { static constexpr int BV = DV < 64 ? DV : 64; static constexpr int NV = DV / BV; };
 
 __device__ inline bool chain_of_block(int nchains, int nv, int &chain, int &vbi) {
@@ -125,19 +127,19 @@ __device__ inline bool chain_of_block(int nchains, int nv, int &chain, int &vbi)
 __host__ inline int chain_grid(int nchains, int nv) { return ((nchains + 7) / 8) * 8 * nv; }
 
 // Which tiles a scan wave owns.  State tile (sa, sb): rows 32*sa of d_k, cols 32*sb of the v-block.
-// T row block ta feeds this wave's W tile (ta, wb) and, for waves < U_TILES, its U / Ut tile (ta, ub).
+// W tile: d_k block wk, chunk-row block wi.  Waves < U_TILES own U / Ut tile (ua, ub); waves 4..
+// own the tile of O (forward) of the same shape.
 template <int DK, int BV> struct ScanMap {
-    static constexpr int NVT = BV / 32, S_TILES = (DK / 32) * NVT, U_TILES = 2 * NVT, W_COLS = DK / 32;
-    static_assert(S_TILES <= NWS && U_TILES <= 4 && (NVT == 1 || NVT == 2), "state tiling");
-    int sa, sb, ta, wb, ub;
-    bool has_s, has_w, does_u;
+    static constexpr int NVT = BV / 32, NKT = DK / 32, S_TILES = NKT * NVT, U_TILES = 2 * NVT, W_TILES = 2 * NKT;
+    static_assert(S_TILES <= NWS && U_TILES <= 4 && W_TILES <= NWS, "state tiling");
+    int sa, sb, wk, wi, ua, ub;
+    bool has_s, has_w, does_u, does_o;
     __device__ ScanMap(int wave) {
-        sa = wave / NVT; sb = wave % NVT;
-        has_s = wave < S_TILES;
-        if (NVT == 2) { ta = (wave >> 1) & 1; wb = (wave & 1) + 2 * (wave >> 2); ub = wave & 1; }
-        else { ta = wave & 1; wb = wave >> 1; ub = 0; }
-        has_w = wb < W_COLS;
-        does_u = wave < U_TILES;
+        sa = wave / NVT; sb = wave % NVT; has_s = wave < S_TILES;
+        wk = wave % NKT; wi = wave / NKT; has_w = wave < W_TILES;
+        const int u = wave & 3;
+        ua = u / NVT; ub = u % NVT;
+        does_u = wave < U_TILES; does_o = wave >= 4 && u < U_TILES;
     }
 };
 
@@ -152,9 +154,12 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oW = oV + align16(sizeof(T) * C * LV);
     static constexpr size_t oST = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t oStage = oUT + align16(sizeof(T) * BV * LT); // per-wave output staging tiles
-    static constexpr size_t szStage = cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
-    static constexpr size_t bytes = oStage + NWS * szStage;
+    static constexpr size_t oT = oUT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t oP = oT + align16(sizeof(T) * C * LT);
+    static constexpr size_t oStage = oP + align16(sizeof(T) * C * LT); // per-wave output staging tiles
+    // waves w and w + 4 never stage in the same phase, so they share a tile unless all 8 waves hold state tiles
+    static constexpr int NSTG = (DK / 32) * (BV / 32) > 4 ? NWS : 4;
+    static constexpr size_t bytes = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS;
 };
 
 template <typename T, int DK, int DV, bool STORE>
@@ -163,15 +168,15 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
     using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * SM::szStage;
-    T *stg = reinterpret_cast<T *>(stg_raw);
-    float *stgf = reinterpret_cast<float *>(stg_raw);
+    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + ((threadIdx.x >> 6) % SM::NSTG) * Stage<T>::ELEMS;
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sV = reinterpret_cast<T *>(smem + SM::oV);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
     T *sST = reinterpret_cast<T *>(smem + SM::oST);
     T *sUT = reinterpret_cast<T *>(smem + SM::oUT);
+    T *sT = reinterpret_cast<T *>(smem + SM::oT);
+    T *sP = reinterpret_cast<T *>(smem + SM::oP);
 
     int chain, vbi;
     if (!chain_of_block(sm.N * H, NV, chain, vbi)) return;
@@ -181,10 +186,8 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
     const Map m(wave);
-    // waves 4.. build the output tile (oa, ob) of the same shape as Ut tile (ta, ub) of wave - 4
-    const bool does_o = !STORE && wave >= 4 && wave < 4 + Map::U_TILES;
-    const Map mo(does_o ? wave - 4 : 0);
-    const int oa = mo.ta, ob = mo.ub;
+    const bool loader = wave >= 4, does_o = !STORE && m.does_o;
+    const int lt = threadIdx.x - NTL; // index among the loader threads
 
     f32x16 S = zero16();
     if (m.has_s && p.S0) {
@@ -193,72 +196,78 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     }
 
     struct Regs {
-        TileRegs<T, C, DK, NTS> q, k;
-        TileRegs<T, C, BV, NTS> v;
-        AFrags<T, C> t, pf; // rows of T (every wave) and of P = tril(Q K^T) (output waves)
+        TileRegs<T, C, DK, NTL> q, k;
+        TileRegs<T, C, BV, NTL> v;
+        TileRegs<T, C, C, NTL> t, pm;
     } ra, rb;
     auto fetch = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        if (!STORE) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
-        r.t.load((const T *)p.Tm + tile * C * C + 32 * m.ta * C, C, C);
-        if (does_o) r.pf.load((const T *)p.P + tile * C * C + 32 * oa * C, C, C);
+        if (!STORE) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
+        r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+        if (!STORE) r.pm.load((const T *)p.P + tile * C * C, C, C, lt);
     };
     auto step = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        if (!STORE) r.q.store(sQ, SM::LQ);
-        r.k.store(sK, SM::LK);
-        r.v.store(sV, SM::LV);
-        const AFrags<T, C> tc = r.t, pc = r.pf;
+        if (loader) {
+            if (!STORE) { r.q.store(sQ, SM::LQ, lt); r.pm.store(sP, SM::LT, lt); }
+            r.k.store(sK, SM::LK, lt);
+            r.v.store(sV, SM::LV, lt);
+            r.t.store(sT, SM::LT, lt);
+        }
         if (m.has_s) {
             if (STORE) acc_store<T>(stg, (T *)p.Sc + tile * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, S);
             acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         }
         lds_barrier();
-        if (ic + 2 < nchunks) fetch(r, ic + 2);
-        if (m.has_w) { // W = T K (Eq. 11), T is lower triangular
+        if (m.has_w) { // W = T K (Eq. 11) as W^T = K^T T^T, so the accumulator rows run along d_k; T is lower triangular
             f32x16 w = zero16();
-            if (m.ta == 0) mma_ra<0, 32, true>(w, tc, sK + 32 * m.wb, SM::LK);
-            else mma_ra<0, C, true>(w, tc, sK + 32 * m.wb, SM::LK);
-            acc_to_lds<T>(sW, SM::LQ, 32 * m.ta, 32 * m.wb, w);
+            if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
+            else mma<C, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT + 32 * SM::LT, SM::LT);
+            acc_to_lds_t<T>(sW, SM::LQ, 32 * m.wk, 32 * m.wi, w);
         }
         f32x16 acc = zero16();
         if (m.does_u) { // U = T V
-            if (m.ta == 0) mma_ra<0, 32, true>(acc, tc, sV + 32 * m.ub, SM::LV);
-            else mma_ra<0, C, true>(acc, tc, sV + 32 * m.ub, SM::LV);
+            if (m.ua == 0) mma<32, false, true, T>(acc, sT, SM::LT, sV + 32 * m.ub, SM::LV);
+            else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV);
         } else if (does_o) { // Q S
-            mma<DK, false, false, T>(acc, sQ + 32 * oa * SM::LQ, SM::LQ, sST + 32 * ob * SM::LS, SM::LS);
+            mma<DK, false, false, T>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
             f32x16 ws = zero16();
-            mma<DK, false, false, T>(ws, sW + 32 * m.ta * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
+            mma<DK, false, false, T>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
             acc -= ws;
-            acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ta, 32 * m.ub, acc);
-            if (STORE) acc_store<T>(stg, (T *)p.Ut + tile * C * DV + vb, DV, 32 * m.ta, 32 * m.ub, C, acc);
+            acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
+            if (STORE) acc_store<T>(stg, (T *)p.Ut + tile * C * DV + vb, DV, 32 * m.ua, 32 * m.ub, C, acc);
         }
+        if (loader && ic + 2 < nchunks) fetch(r, ic + 2); // the loader waves are idle here
         lds_barrier();
         if (does_o) { // O = Q S + P Ut (Eq. 9)
-            if (oa == 0) mma_ra<0, 32, false>(acc, pc, sUT + 32 * ob * SM::LT, SM::LT);
-            else mma_ra<0, C, false>(acc, pc, sUT + 32 * ob * SM::LT, SM::LT);
-            acc_store<T>(stg, (T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * oa, 32 * ob, nvalid, acc);
+            if (m.ua == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
+            else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
+            acc_store<T>(stg, (T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub, nvalid, acc);
         }
         if (m.has_s) mma<C, true, false, T>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         lds_barrier();
     };
-    if (nchunks > 0) fetch(ra, 0);
-    if (nchunks > 1) fetch(rb, 1);
+    if (loader) {
+        if (nchunks > 0) fetch(ra, 0);
+        if (nchunks > 1) fetch(rb, 1);
+    }
     for (int ic = 0; ic < nchunks; ic += 2) {
         step(ra, ic);
         if (ic + 1 < nchunks) step(rb, ic + 1);
     }
-    if (!STORE && p.ST && m.has_s)
-        acc_store<float>(stgf, p.ST + (long)chain * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, S);
+    if (!STORE && p.ST && m.has_s) {
+        float *dst = p.ST + (long)chain * DK * DV + vb;
+        acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
+    }
 }
 
 // k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
@@ -272,9 +281,12 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t oDO = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oDST = oDO + align16(sizeof(T) * C * LD);
     static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t oStage = oDUT + align16(sizeof(T) * BV * LT); // per-wave output staging tiles
-    static constexpr size_t szStage = cmax(sizeof(T) * Stage<T>::ELEMS, sizeof(float) * Stage<float>::ELEMS);
-    static constexpr size_t bytes = oStage + NWS * szStage;
+    static constexpr size_t oT = oDUT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t oPT = oT + align16(sizeof(T) * C * LT);
+    static constexpr size_t oStage = oPT + align16(sizeof(T) * C * LT); // per-wave output staging tiles
+    // waves w and w + 4 never stage in the same phase, so they share a tile unless all 8 waves hold state tiles
+    static constexpr int NSTG = (DK / 32) * (BV / 32) > 4 ? NWS : 4;
+    static constexpr size_t bytes = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS;
 };
 
 template <typename T, int DK, int DV>
@@ -283,15 +295,15 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
     using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stg_raw = smem + SM::oStage + (threadIdx.x >> 6) * SM::szStage;
-    T *stg = reinterpret_cast<T *>(stg_raw);
-    float *stgf = reinterpret_cast<float *>(stg_raw);
+    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + ((threadIdx.x >> 6) % SM::NSTG) * Stage<T>::ELEMS;
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
     T *sDST = reinterpret_cast<T *>(smem + SM::oDST);
     T *sDUT = reinterpret_cast<T *>(smem + SM::oDUT);
+    T *sT = reinterpret_cast<T *>(smem + SM::oT);
+    T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
 
     int chain, vbi;
     if (!chain_of_block(sm.N * H, NV, chain, vbi)) return;
@@ -301,6 +313,8 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
     const Map m(wave);
+    const bool loader = wave >= 4;
+    const int lt = threadIdx.x - NTL;
 
     f32x16 dS = zero16();
     if (m.has_s && p.dST) {
@@ -309,60 +323,64 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     }
 
     struct Regs {
-        TileRegs<T, C, DK, NTS> q, k;
-        TileRegs<T, C, BV, NTS> d_o;
-        AFrags<T, C> t, pt; // rows of T (every wave) and of P^T (the waves that build dUt)
+        TileRegs<T, C, DK, NTL> q, k;
+        TileRegs<T, C, BV, NTL> d_o;
+        TileRegs<T, C, C, NTL> t, pt;
     } ra, rb;
     auto fetch = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid);
-        r.t.load((const T *)p.Tm + tile * C * C + 32 * m.ta * C, C, C);
-        if (m.does_u) r.pt.load((const T *)p.PT + tile * C * C + 32 * m.ta * C, C, C);
+        r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
+        r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+        r.pt.load((const T *)p.PT + tile * C * C, C, C, lt);
     };
     auto step = [&](Regs &r, int ic) __attribute__((always_inline)) {
         const long tile = ((long)(cb + ic) * H + h);
-        r.q.store(sQ, SM::LQ);
-        r.k.store(sK, SM::LK);
-        r.d_o.store(sDO, SM::LD);
-        const AFrags<T, C> tc = r.t, ptc = r.pt;
+        if (loader) {
+            r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
+            r.t.store(sT, SM::LT, lt); r.pt.store(sPT, SM::LT, lt);
+        }
         if (m.has_s) { // dS' (gradient w.r.t. the state after this chunk)
             acc_store<T>(stg, (T *)p.dSc + tile * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, dS);
             acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS);
         }
         lds_barrier();
-        if (ic - 2 >= 0) fetch(r, ic - 2);
-        if (m.has_w) { // W = T K (Eq. 11)
+        if (m.has_w) { // W = T K (Eq. 11), computed as W^T = K^T T^T
             f32x16 w = zero16();
-            if (m.ta == 0) mma_ra<0, 32, true>(w, tc, sK + 32 * m.wb, SM::LK);
-            else mma_ra<0, C, true>(w, tc, sK + 32 * m.wb, SM::LK);
-            acc_to_lds<T>(sW, SM::LQ, 32 * m.ta, 32 * m.wb, w);
+            if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
+            else mma<C, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT + 32 * SM::LT, SM::LT);
+            acc_to_lds_t<T>(sW, SM::LQ, 32 * m.wk, 32 * m.wi, w);
         }
-        if (m.does_u) { // dUt tile (ta, ub); P^T is upper triangular
+        if (m.does_u) { // dUt tile (ua, ub); P^T is upper triangular
             f32x16 acc = zero16();
-            if (m.ta == 0) mma_ra<0, C, true>(acc, ptc, sDO + 32 * m.ub, SM::LD);
-            else mma_ra<32, C, true>(acc, ptc, sDO + 32 * m.ub, SM::LD);
-            mma<DK, false, false, T>(acc, sK + 32 * m.ta * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
-            acc_store<T>(stg, (T *)p.dUt + tile * C * DV + vb, DV, 32 * m.ta, 32 * m.ub, C, acc);
+            if (m.ua == 0) mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
+            else mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LD + 32 * m.ub, SM::LD);
+            mma<DK, false, false, T>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+            acc_store<T>(stg, (T *)p.dUt + tile * C * DV + vb, DV, 32 * m.ua, 32 * m.ub, C, acc);
             acc_each(acc, [&](int, int, float &val) { val = -val; });
-            acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ta, 32 * m.ub, acc);
+            acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
+        if (loader && ic - 2 >= 0) fetch(r, ic - 2); // the loader waves have the shorter phase
         lds_barrier();
         if (m.has_s) mma<C, true, false, T>(dS, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT); // - W^T dUt
         lds_barrier();
     };
-    if (nchunks > 0) fetch(ra, nchunks - 1);
-    if (nchunks > 1) fetch(rb, nchunks - 2);
+    if (loader) {
+        if (nchunks > 0) fetch(ra, nchunks - 1);
+        if (nchunks > 1) fetch(rb, nchunks - 2);
+    }
     for (int ic = nchunks - 1; ic >= 0; ic -= 2) {
         step(ra, ic);
         if (ic - 1 >= 0) step(rb, ic - 1);
     }
-    if (p.dS0 && m.has_s)
-        acc_store<float>(stgf, p.dS0 + (long)chain * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, dS);
+    if (p.dS0 && m.has_s) {
+        float *dst = p.dS0 + (long)chain * DK * DV + vb;
+        acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
+    }
 }
 
 // =============================================================================================

@@ -326,6 +326,17 @@ __device__ inline void store_tile(T *dst, long row_stride, const T *src, int ld,
             *reinterpret_cast<uint4 *>(dst + (long)r * row_stride + tc) = *reinterpret_cast<const uint4 *>(src + r * ld + tc);
     }
 }
+// LDS -> global copy of a ROWS x COLS tile by NT cooperating threads (t = index among them); the
+// destination is a contiguous row-major block
+template <typename T, int ROWS, int COLS, int NT>
+__device__ inline void copy_out(T *dst, const T *src, int ld, int t) {
+    constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NT / TPR;
+    static_assert(COLS % VEC == 0 && NT % TPR == 0 && ROWS % RPI == 0, "tile shape");
+    const int tr = t / TPR, tc = (t % TPR) * VEC;
+#pragma unroll
+    for (int r0 = 0; r0 < ROWS; r0 += RPI)
+        *reinterpret_cast<uint4 *>(dst + (long)(r0 + tr) * COLS + tc) = *reinterpret_cast<const uint4 *>(src + (r0 + tr) * ld + tc);
+}
 // LDS -> LDS transpose of a C x COLS tile: dstT[c][r] = src[r][c].  Lanes run along r so that the
 // narrow stores of one instruction fall into consecutive addresses.
 template <typename T, int COLS>

@@ -157,8 +157,7 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oT = oUT + align16(sizeof(T) * BV * LT);
     static constexpr size_t oP = oT + align16(sizeof(T) * C * LT);
     static constexpr size_t oStage = oP + align16(sizeof(T) * C * LT); // per-wave output staging tiles
-    // waves w and w + 4 never stage in the same phase, so they share a tile unless all 8 waves hold state tiles
-    static constexpr int NSTG = (DK / 32) * (BV / 32) > 4 ? NWS : 4;
+    static constexpr int NSTG = 4; // only the four output waves stage tiles
     static constexpr size_t bytes = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS;
 };
 
@@ -220,11 +219,10 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
             r.v.store(sV, SM::LV, lt);
             r.t.store(sT, SM::LT, lt);
         }
-        if (m.has_s) {
-            if (STORE) acc_store<T>(stg, (T *)p.Sc + tile * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, S);
-            acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
-        }
+        if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         lds_barrier();
+        // the chunk-initial state leaves through the loader waves, transposed as it sits in LDS
+        if (STORE && loader) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
         if (m.has_w) { // W = T K (Eq. 11) as W^T = K^T T^T, so the accumulator rows run along d_k; T is lower triangular
             f32x16 w = zero16();
             if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
@@ -244,10 +242,10 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
             mma<DK, false, false, T>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
             acc -= ws;
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
-            if (STORE) acc_store<T>(stg, (T *)p.Ut + tile * C * DV + vb, DV, 32 * m.ua, 32 * m.ub, C, acc);
         }
         if (loader && ic + 2 < nchunks) fetch(r, ic + 2); // the loader waves are idle here
         lds_barrier();
+        if (STORE && loader) copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, sUT, SM::LT, lt); // Ut^T
         if (does_o) { // O = Q S + P Ut (Eq. 9)
             if (m.ua == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -272,6 +270,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
 
 // k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
 //   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
+// Per chunk it leaves dS'^T and dUt^T in the workspace (the transposed LDS copies, written out by the loader waves).
 template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr int BV = VBlock<DV>::BV;
     static constexpr int LQ = ldn<T>(DK), LK = ldn<T>(DK), LD = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
@@ -283,10 +282,7 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LS);
     static constexpr size_t oT = oDUT + align16(sizeof(T) * BV * LT);
     static constexpr size_t oPT = oT + align16(sizeof(T) * C * LT);
-    static constexpr size_t oStage = oPT + align16(sizeof(T) * C * LT); // per-wave output staging tiles
-    // waves w and w + 4 never stage in the same phase, so they share a tile unless all 8 waves hold state tiles
-    static constexpr int NSTG = (DK / 32) * (BV / 32) > 4 ? NWS : 4;
-    static constexpr size_t bytes = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS;
+    static constexpr size_t bytes = oPT + align16(sizeof(T) * C * LT);
 };
 
 template <typename T, int DK, int DV>
@@ -295,7 +291,6 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
     using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
-    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + ((threadIdx.x >> 6) % SM::NSTG) * Stage<T>::ELEMS;
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
@@ -343,11 +338,9 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
             r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
             r.t.store(sT, SM::LT, lt); r.pt.store(sPT, SM::LT, lt);
         }
-        if (m.has_s) { // dS' (gradient w.r.t. the state after this chunk)
-            acc_store<T>(stg, (T *)p.dSc + tile * DK * DV + vb, DV, 32 * m.sa, 32 * m.sb, DK, dS);
-            acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS);
-        }
+        if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' (gradient w.r.t. the state after this chunk)
         lds_barrier();
+        if (loader) copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
         if (m.has_w) { // W = T K (Eq. 11), computed as W^T = K^T T^T
             f32x16 w = zero16();
             if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
@@ -359,14 +352,17 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
             if (m.ua == 0) mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
             else mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LD + 32 * m.ub, SM::LD);
             mma<DK, false, false, T>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
-            acc_store<T>(stg, (T *)p.dUt + tile * C * DV + vb, DV, 32 * m.ua, 32 * m.ub, C, acc);
-            acc_each(acc, [&](int, int, float &val) { val = -val; });
             acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         if (loader && ic - 2 >= 0) fetch(r, ic - 2); // the loader waves have the shorter phase
         lds_barrier();
-        if (m.has_s) mma<C, true, false, T>(dS, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT); // - W^T dUt
+        if (loader) copy_out<T, BV, C, NTL>((T *)p.dUt + (tile * DV + vb) * C, sDUT, SM::LT, lt); // dUt^T to the workspace
+        if (m.has_s) { // - W^T dUt
+            f32x16 wd = zero16();
+            mma<C, true, false, T>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
+            dS -= wd;
+        }
         lds_barrier();
     };
     if (loader) {
@@ -413,7 +409,8 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
 }
 
 // k_bwd_chunk: everything of the backward pass that is local to one chunk, given the chunk-initial
-// state S, the gradient dS' w.r.t. the state after the chunk, Ut and dUt from the two scans:
+// state S, the gradient dS' w.r.t. the state after the chunk, Ut and dUt from the two scans (all four
+// arrive transposed, [d_v][d_k] and [d_v][C], as the scans hold them in LDS):
 //   adjoint of Eq. 8-9:  dP = tril(dO Ut^T); dQ = dO S^T + dP K; dK1 = dP^T Q + Ut dS'^T; dW = -dUt S^T
 //   adjoint of Eq. 10-11, with X = (I+A)^-1, A = tril(diag(beta) G,-1), G = K K^T, dU = dUt:
 //     dX' = dW K^T + dU V^T;  dX = dX' diag(beta);  dKb = X^T dW;  dV = diag(beta) X^T dU;
@@ -423,17 +420,18 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
 // dW and dK1 never leave the chip.  LDS buffers are reused as operands die; V and dS' wait in
 // registers until their buffer is free.
 template <typename T, int DK, int DV> struct ChunkSmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40, LSV = ldn<T>(DV);
+    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40;
+    static constexpr int LU = ldn<T>(C), LSK = ldn<T>(DK); // rows of Ut^T / dUt^T ([d_v][C]) and of S^T / dS'^T ([d_v][d_k])
     static constexpr bool kXnIsX = sizeof(T) == sizeof(float); // fp32: the inverse itself is the operand
     static constexpr size_t szX = sizeof(float) * C * LF, szCC = sizeof(T) * C * LT;
     static constexpr size_t oB1 = 0;                                   // dO; V; dA o G (fp32)
-    static constexpr size_t oB2 = oB1 + align16(cmax(sizeof(T) * C * LV, szX));     // Ut; dW
-    static constexpr size_t oB3 = oB2 + align16(cmax(sizeof(T) * C * LV, sizeof(T) * C * LK)); // dUt
-    static constexpr size_t oB4 = oB3 + align16(sizeof(T) * C * LV);   // K
+    static constexpr size_t oB2 = oB1 + align16(cmax(sizeof(T) * C * LV, szX));     // Ut^T; dW
+    static constexpr size_t oB3 = oB2 + align16(cmax(sizeof(T) * DV * LU, sizeof(T) * C * LK)); // dUt^T
+    static constexpr size_t oB4 = oB3 + align16(sizeof(T) * DV * LU);  // K
     static constexpr size_t oB5 = oB4 + align16(sizeof(T) * C * LK);   // Q; inverse scratch; M1^T
     static constexpr size_t oB6 = oB5 + align16(cmax(sizeof(T) * C * LK, szCC)); // dP; (inverse scratch); dX; Ah
-    static constexpr size_t oB7 = oB6 + align16(szCC);                 // S; dS'; fp32 A / X, then X as T
-    static constexpr size_t szB7 = cmax(sizeof(T) * DK * LSV, align16(szX) + (kXnIsX ? 0 : szCC));
+    static constexpr size_t oB7 = oB6 + align16(szCC);                 // S^T; dS'^T; fp32 A / X, then X as T
+    static constexpr size_t szB7 = cmax(sizeof(T) * DV * LSK, align16(szX) + (kXnIsX ? 0 : szCC));
     static_assert(sizeof(T) * 4 * 32 * LO <= oB7 - oB5, "the inverse's operand scratch spans the dead Q and dP buffers");
     static constexpr size_t oM = oB7 + align16(szB7);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
@@ -475,21 +473,22 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     auto vbk = [&](int sI) __attribute__((always_inline)) { return kt(sI) % (DV / 32); };
 
     struct Regs {
-        TileRegs<T, C, DV, NTC> d_o, ut, dut, v;
-        TileRegs<T, DK, DV, NTC> s, ds;
+        TileRegs<T, C, DV, NTC> d_o, v;
+        TileRegs<T, DV, C, NTC> ut, dut;
+        TileRegs<T, DV, DK, NTC> s, ds;
         TileRegs<T, C, DK, NTC> k, q;
         T beta; // kept in storage format: converting here would wait for the whole prefetch
     } r;
     auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
         if (!tp.ok) return;
         r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
-        r.ut.load((const T *)p.Ut + tp.tile * C * DV, DV, C);
-        r.s.load((const T *)p.Sc + tp.tile * DK * DV, DV, DK);
-        r.dut.load((const T *)p.dUt + tp.tile * C * DV, DV, C);
+        r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV);
+        r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV);
+        r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV);
         r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
         r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
         if (tid < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tid, tp.nvalid - 1)) * H + tp.h];
-        r.ds.load((const T *)p.dSc + tp.tile * DK * DV, DV, DK);
+        r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV);
         r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
     };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
@@ -501,13 +500,13 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
         // ---- adjoint of Eq. 8-9
-        r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LV); r.s.store(sS, SM::LSV);
-        r.dut.store(sDU, SM::LV); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
+        r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LU); r.s.store(sS, SM::LSK);
+        r.dut.store(sDU, SM::LU); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
         if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
         lds_barrier();
         { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
-            if (!upper) mma<DV, false, false, T>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni * SM::LV, SM::LV);
+            if (!upper) mma<DV, false, true, T>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni, SM::LU);
             acc_each(acc, [&](int rr, int c, float &val) { if (32 * ni + c > 32 * mi + rr) val = 0.f; });
             acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc);
         }
@@ -516,12 +515,12 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         for (int sI = 0; sI < KW; ++sI) {
             dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
             if (kt(sI) < KT) {
-                mma<DV, false, false, T>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI) * SM::LSV, SM::LSV); // dO S^T
-                mma<DV, false, false, T>(dw[sI], sDU + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI) * SM::LSV, SM::LSV); // dUt S^T
+                mma<DV, false, true, T>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI), SM::LSK); // dO S^T
+                mma<DV, true, true, T>(dw[sI], sDU + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);           // dUt S^T
             }
         }
         lds_barrier(); // dP visible; S is dead
-        r.ds.store(sS, SM::LSV);
+        r.ds.store(sS, SM::LSK);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dQ += dP K
             if (ka(sI) == 0) mma<32, false, true, T>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK);
@@ -533,7 +532,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
             if (ka(sI) == 1) mma<32, true, true, T>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK);
             else mma<C, true, true, T>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK);
-            mma<DV, false, false, T>(dk1[sI], sUt + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI) * SM::LSV, SM::LSV);
+            mma<DV, true, true, T>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
         }
         lds_barrier(); // dO, Ut, Q, dP, dS' are dead
         // ---- adjoint of Eq. 10-11
@@ -548,7 +547,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (!upper) {
             mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
             mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-            mma<DV, false, false, T>(dxp, sDU + 32 * mi * SM::LV, SM::LV, sV + 32 * ni * SM::LV, SM::LV);
+            mma<DV, true, false, T>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV);
         }
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
         acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
@@ -580,8 +579,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
 #pragma unroll
         for (int sI = 0; sI < VW; ++sI) if (kt(sI) < VT) { // dV = diag(beta) X^T dU
             f32x16 acc = zero16();
-            if (va(sI) == 1) mma<32, true, true, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * SM::LV + 32 * vbk(sI), SM::LV);
-            else mma<C, true, true, T>(acc, sXn, SM::LT, sDU + 32 * vbk(sI), SM::LV);
+            if (va(sI) == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * vbk(sI) * SM::LU + 32, SM::LU);
+            else mma<C, true, false, T>(acc, sXn, SM::LT, sDU + 32 * vbk(sI) * SM::LU, SM::LU);
             acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * va(sI) + rr]; });
             acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
         }

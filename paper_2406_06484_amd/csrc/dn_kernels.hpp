@@ -116,7 +116,12 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
 // Workgroup ids are laid out so that the v-blocks of one chain land on the same XCD (ids are dealt
 // round-robin over the 8 XCDs) and share its L2 for the Q, K, T tiles they both read.
 constexpr int NTS = 512, NWS = 8, NTL = 256; // threads / waves of a scan workgroup; loader threads
-template <int DV> struct VBlock { static constexpr int BV = DV < 64 ? DV : 64; static constexpr int NV = DV / BV; };
+// bf16 workgroups own 64 state columns; fp32 ones 32, so that the fp32 tiles still fit the 160 KB of LDS
+template <typename T, int DV> struct VBlock {
+    static constexpr int WANT = sizeof(T) == 2 ? 64 : 32;
+    static constexpr int BV = DV < WANT ? DV : WANT;
+    static constexpr int NV = DV / BV;
+};
 
 __device__ inline bool chain_of_block(int nchains, int nv, int &chain, int &vbi) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -146,7 +151,7 @@ template <int DK, int BV> struct ScanMap {
 // k_scan_fwd: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
 // writes every chunk-initial state and Ut to the workspace instead of O.
 template <typename T, int DK, int DV> struct ScanFwdSmem {
-    static constexpr int BV = VBlock<DV>::BV;
+    static constexpr int BV = VBlock<T, DV>::BV;
     static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LV = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
@@ -154,7 +159,8 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oW = oV + align16(sizeof(T) * C * LV);
     static constexpr size_t oST = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oUT = oST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t oT = oUT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t szUT = align16(sizeof(T) * BV * LT);     // two Ut^T buffers, alternating by chunk parity
+    static constexpr size_t oT = oUT + 2 * szUT;
     static constexpr size_t oP = oT + align16(sizeof(T) * C * LT);
     static constexpr size_t oStage = oP + align16(sizeof(T) * C * LT); // per-wave output staging tiles
     static constexpr int NSTG = 4; // only the four output waves stage tiles
@@ -164,7 +170,7 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
 template <typename T, int DK, int DV, bool STORE>
 __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     using SM = ScanFwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
+    constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
     using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
     T *stg = reinterpret_cast<T *>(smem + SM::oStage) + ((threadIdx.x >> 6) % SM::NSTG) * Stage<T>::ELEMS;
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     T *sV = reinterpret_cast<T *>(smem + SM::oV);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
     T *sST = reinterpret_cast<T *>(smem + SM::oST);
-    T *sUT = reinterpret_cast<T *>(smem + SM::oUT);
+    T *sUT0 = reinterpret_cast<T *>(smem + SM::oUT), *sUT1 = reinterpret_cast<T *>(smem + SM::oUT + SM::szUT);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sP = reinterpret_cast<T *>(smem + SM::oP);
 
@@ -198,8 +204,8 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         TileRegs<T, C, DK, NTL> q, k;
         TileRegs<T, C, BV, NTL> v;
         TileRegs<T, C, C, NTL> t, pm;
-    } ra, rb;
-    auto fetch = [&](Regs &r, int ic) __attribute__((always_inline)) {
+    } r;
+    auto fetch = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
@@ -209,10 +215,22 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
         if (!STORE) r.pm.load((const T *)p.P + tile * C * C, C, C, lt);
     };
-    auto step = [&](Regs &r, int ic) __attribute__((always_inline)) {
-        const int nvalid = min(C, len - ic * C);
-        const long row0 = (long)t0 + (long)ic * C;
+    // Everything that touches global memory is issued by the loader waves in one burst right after
+    // the first barrier of a step: the loads for the next chunk, then the stores of what the previous
+    // step left in LDS (its Ut^T, or its staged output tile).  The compiler drains the memory counter
+    // when the loaded registers are moved to LDS at the top of the next step; by then all of it is a
+    // full step old.
+    auto flush_prev = [&](int icp) __attribute__((always_inline)) { // results of chunk icp, still in LDS
+        const long tile = ((long)(cb + icp) * H + h);
+        if (STORE) copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt); // Ut^T
+        else if (m.does_o)
+            stage_flush<T>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
+                           min(C, len - icp * C));
+    };
+    if (loader && nchunks > 0) fetch(0);
+    for (int ic = 0; ic < nchunks; ++ic) {
         const long tile = ((long)(cb + ic) * H + h);
+        T *sUT = (ic & 1) ? sUT1 : sUT0;
         if (loader) {
             if (!STORE) { r.q.store(sQ, SM::LQ, lt); r.pm.store(sP, SM::LT, lt); }
             r.k.store(sK, SM::LK, lt);
@@ -221,8 +239,12 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         }
         if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         lds_barrier();
-        // the chunk-initial state leaves through the loader waves, transposed as it sits in LDS
-        if (STORE && loader) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+        if (loader) {
+            if (ic + 1 < nchunks) fetch(ic + 1);
+            // the chunk-initial state leaves transposed, as it sits in LDS
+            if (STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (ic > 0) flush_prev(ic - 1);
+        }
         if (m.has_w) { // W = T K (Eq. 11) as W^T = K^T T^T, so the accumulator rows run along d_k; T is lower triangular
             f32x16 w = zero16();
             if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
@@ -243,25 +265,16 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
             acc -= ws;
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
-        if (loader && ic + 2 < nchunks) fetch(r, ic + 2); // the loader waves are idle here
         lds_barrier();
-        if (STORE && loader) copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, sUT, SM::LT, lt); // Ut^T
-        if (does_o) { // O = Q S + P Ut (Eq. 9)
+        if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
-            acc_store<T>(stg, (T *)p.o + (row0 * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub, nvalid, acc);
+            acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc);
         }
         if (m.has_s) mma<C, true, false, T>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         lds_barrier();
-    };
-    if (loader) {
-        if (nchunks > 0) fetch(ra, 0);
-        if (nchunks > 1) fetch(rb, 1);
     }
-    for (int ic = 0; ic < nchunks; ic += 2) {
-        step(ra, ic);
-        if (ic + 1 < nchunks) step(rb, ic + 1);
-    }
+    if (loader && nchunks > 0) flush_prev(nchunks - 1);
     if (!STORE && p.ST && m.has_s) {
         float *dst = p.ST + (long)chain * DK * DV + vb;
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
@@ -272,7 +285,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
 //   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
 // Per chunk it leaves dS'^T and dUt^T in the workspace (the transposed LDS copies, written out by the loader waves).
 template <typename T, int DK, int DV> struct ScanBwdSmem {
-    static constexpr int BV = VBlock<DV>::BV;
+    static constexpr int BV = VBlock<T, DV>::BV;
     static constexpr int LQ = ldn<T>(DK), LK = ldn<T>(DK), LD = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
@@ -280,7 +293,8 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t oDO = oW + align16(sizeof(T) * C * LQ);
     static constexpr size_t oDST = oDO + align16(sizeof(T) * C * LD);
     static constexpr size_t oDUT = oDST + align16(sizeof(T) * BV * LS);
-    static constexpr size_t oT = oDUT + align16(sizeof(T) * BV * LT);
+    static constexpr size_t szDUT = align16(sizeof(T) * BV * LT);    // two dUt^T buffers, alternating by chunk parity
+    static constexpr size_t oT = oDUT + 2 * szDUT;
     static constexpr size_t oPT = oT + align16(sizeof(T) * C * LT);
     static constexpr size_t bytes = oPT + align16(sizeof(T) * C * LT);
 };
@@ -288,7 +302,7 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     using SM = ScanBwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NV = VBlock<DV>::NV;
+    constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
     using Map = ScanMap<DK, BV>;
     extern __shared__ __align__(16) unsigned char smem[];
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
@@ -296,7 +310,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
     T *sDO = reinterpret_cast<T *>(smem + SM::oDO);
     T *sDST = reinterpret_cast<T *>(smem + SM::oDST);
-    T *sDUT = reinterpret_cast<T *>(smem + SM::oDUT);
+    T *sDUT0 = reinterpret_cast<T *>(smem + SM::oDUT), *sDUT1 = reinterpret_cast<T *>(smem + SM::oDUT + SM::szDUT);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
 
@@ -321,8 +335,8 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         TileRegs<T, C, DK, NTL> q, k;
         TileRegs<T, C, BV, NTL> d_o;
         TileRegs<T, C, C, NTL> t, pt;
-    } ra, rb;
-    auto fetch = [&](Regs &r, int ic) __attribute__((always_inline)) {
+    } r;
+    auto fetch = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
@@ -332,15 +346,26 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
         r.pt.load((const T *)p.PT + tile * C * C, C, C, lt);
     };
-    auto step = [&](Regs &r, int ic) __attribute__((always_inline)) {
+    auto flush_dut = [&](int icp) __attribute__((always_inline)) { // dUt^T of chunk icp, still in LDS
+        copy_out<T, BV, C, NTL>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, lt);
+    };
+    // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
+    // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
+    if (loader && nchunks > 0) fetch(nchunks - 1);
+    for (int ic = nchunks - 1; ic >= 0; --ic) {
         const long tile = ((long)(cb + ic) * H + h);
+        T *sDUT = (ic & 1) ? sDUT1 : sDUT0;
         if (loader) {
             r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
             r.t.store(sT, SM::LT, lt); r.pt.store(sPT, SM::LT, lt);
         }
         if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' (gradient w.r.t. the state after this chunk)
         lds_barrier();
-        if (loader) copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
+        if (loader) {
+            if (ic > 0) fetch(ic - 1);
+            copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
+            if (ic + 1 < nchunks) flush_dut(ic + 1);
+        }
         if (m.has_w) { // W = T K (Eq. 11), computed as W^T = K^T T^T
             f32x16 w = zero16();
             if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
@@ -355,24 +380,15 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
             acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
-        if (loader && ic - 2 >= 0) fetch(r, ic - 2); // the loader waves have the shorter phase
         lds_barrier();
-        if (loader) copy_out<T, BV, C, NTL>((T *)p.dUt + (tile * DV + vb) * C, sDUT, SM::LT, lt); // dUt^T to the workspace
         if (m.has_s) { // - W^T dUt
             f32x16 wd = zero16();
             mma<C, true, false, T>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
             dS -= wd;
         }
         lds_barrier();
-    };
-    if (loader) {
-        if (nchunks > 0) fetch(ra, nchunks - 1);
-        if (nchunks > 1) fetch(rb, nchunks - 2);
     }
-    for (int ic = nchunks - 1; ic >= 0; ic -= 2) {
-        step(ra, ic);
-        if (ic - 1 >= 0) step(rb, ic - 1);
-    }
+    if (loader && nchunks > 0) flush_dut(0);
     if (p.dS0 && m.has_s) {
         float *dst = p.dS0 + (long)chain * DK * DV + vb;
         acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });

@@ -50,7 +50,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     if (pb.N == 0 || pb.chunks_ub == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<DV>::NV));
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
     DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;
@@ -60,7 +60,7 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (pb.N == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<DV>::NV));
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
     if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
     if (pb.chunks_ub) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     DN_LAUNCH_NT((k_scan_bwd<T, DK, DV>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);

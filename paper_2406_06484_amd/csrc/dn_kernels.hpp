@@ -199,6 +199,9 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         const float *src = p.S0 + (long)chain * DK * DV + vb;
         acc_each(S, [&](int r, int c, float &val) { val = src[(long)(32 * m.sa + r) * DV + 32 * m.sb + c]; });
     }
+    // settle these loads here: otherwise the compiler keeps "state registers may still be in flight"
+    // alive around the loop and drains the memory counter (and with it the prefetch) in every step
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
 
     struct Regs {
         TileRegs<T, C, DK, NTL> q, k;
@@ -330,6 +333,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         const float *src = p.dST + (long)chain * DK * DV + vb;
         acc_each(dS, [&](int r, int c, float &val) { val = src[(long)(32 * m.sa + r) * DV + 32 * m.sb + c]; });
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): see k_scan_fwd
 
     struct Regs {
         TileRegs<T, C, DK, NTL> q, k;

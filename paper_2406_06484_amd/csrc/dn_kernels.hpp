@@ -403,7 +403,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
 // The chunk-parallel backward kernel.  Workgroups are persistent: each walks over (chunk, head)
 // tiles with a grid stride and requests the next tile's operands (into registers) while it works on
 // the current one, so global latency is hidden behind the second half of the current tile.
-constexpr int NTC = 256, NWC = 4; // one wave per SIMD: the fused kernel wants the whole register file
+constexpr int NTC = 512, NWC = 8;
 
 struct TileIter { // grid-stride walk over (global chunk id, head) tiles
     int id, total, H;
@@ -441,7 +441,7 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
 // registers until their buffer is free.
 template <typename T, int DK, int DV> struct ChunkSmem {
     static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40;
-    static constexpr int LU = ldn<T>(C), LSK = ldn<T>(DK); // rows of Ut^T / dUt^T ([d_v][C]) and of S^T / dS'^T ([d_v][d_k])
+    static constexpr int LU = ldc<T>(C), LSK = ldn<T>(DK); // rows of Ut^T / dUt^T ([d_v][C]) and of S^T / dS'^T ([d_v][d_k])
     static constexpr bool kXnIsX = sizeof(T) == sizeof(float); // fp32: the inverse itself is the operand
     static constexpr size_t szX = sizeof(float) * C * LF, szCC = sizeof(T) * C * LT;
     static constexpr size_t oB1 = 0;                                   // dO; V; dA o G (fp32)
@@ -483,8 +483,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int mi = wave >> 1, ni = wave & 1; // this wave's tile of every C x C matrix
-    const bool upper = (mi == 0 && ni == 1);
+    const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
+    const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
     // tile number sI of this wave in a C x DK (C x DV) matrix: row block ka, column block kb
     auto kt = [&](int sI) __attribute__((always_inline)) { return wave + sI * NWC; };
     auto ka = [&](int sI) __attribute__((always_inline)) { return kt(sI) / (DK / 32); };
@@ -524,7 +524,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         r.dut.store(sDU, SM::LU); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
         if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
         lds_barrier();
-        { // dP = tril(dO Ut^T)
+        if (cc) { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
             if (!upper) mma<DV, false, true, T>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni, SM::LU);
             acc_each(acc, [&](int rr, int c, float &val) { if (32 * ni + c > 32 * mi + rr) val = 0.f; });
@@ -564,16 +564,16 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         r.v.store(sV, SM::LV);
         lds_barrier();
         f32x16 g = zero16(), dxp = zero16();
-        if (!upper) {
+        if (cc && !upper) {
             mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
             mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
             mma<DV, true, false, T>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV);
         }
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
-        acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
+        if (cc) acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
         lds_barrier(); // V is dead
         tri_inverse_64_inplace<T, NTC>(sX, SM::LF, sM, sOp, SM::LO);
-        { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
+        if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
             float part = 0.f;
             acc_each(dxp, [&](int rr, int c, float &val) {
                 const int i = 32 * mi + rr, j = 32 * ni + c;
@@ -587,7 +587,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             for (int e = tid; e < C * C; e += NTC) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
         lds_barrier();
         f32x16 m1 = zero16(); // M1 = dX X^T
-        mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
+        if (cc) mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dKb = X^T dW (X^T is upper triangular)
             f32x16 dKb = zero16();
@@ -604,9 +604,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * va(sI) + rr]; });
             acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
         }
-        acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
+        if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
         lds_barrier(); // dX is dead
-        { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
+        if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {
                 if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
@@ -630,7 +630,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             else mma<C, true, true, T>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
             acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
         }
-        { // dbeta = column sums from part 1 + row sums of dA o G
+        if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G
             const int i = tid >> 2, seg = tid & 3;
             float sum = 0.f;
 #pragma unroll

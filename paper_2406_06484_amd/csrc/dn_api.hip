@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_P, off_Ut, off_dUt, off_Sc, off_dSc, total;
+    size_t off_coff, off_T, off_P, off_X, off_Ut, off_dUt, off_Sc, off_dSc, total;
     size_t esz;
 };
 
@@ -111,6 +111,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
     pl->off_T = o; o += tC; // T of Eq. 10
     pl->off_P = o; o += tC; // tril(Q K^T) (forward) or its transpose (backward)
     if (want_bwd) {
+        pl->off_X = o; o += tC; // (I + A)^-1 of Eq. 10, reused by the chunk kernel
         pl->off_Ut = o; o += tV;
         pl->off_dUt = o; o += tV;
         pl->off_Sc = o; o += tS;
@@ -129,6 +130,7 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     p->want_p = !want_bwd;
     p->want_pt = want_bwd;
     if (want_bwd) {
+        p->Xm = b + pl.off_X;
         p->Ut = b + pl.off_Ut; p->dUt = b + pl.off_dUt; p->Sc = b + pl.off_Sc;
         p->dSc = b + pl.off_dSc;
     }

@@ -22,7 +22,7 @@ struct Ptrs {
     void *o, *dq, *dk, *dv;
     float *ST, *dbeta, *dS0;
     // workspace tiles, indexed by (global chunk * H + head)
-    void *Tm, *P, *PT, *Ut, *dUt, *Sc, *dSc;
+    void *Tm, *Xm, *P, *PT, *Ut, *dUt, *Sc, *dSc;
     int want_p, want_pt; // which of tril(Q K^T) / its transpose k_wy_prep should write
 };
 

@@ -42,7 +42,8 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
 // k_wy_prep: per chunk, T = (I + tril(diag(beta) K K^T, -1))^-1 diag(beta) (Eq. 10) and
 // P = tril(Q K^T) (the causal intra-chunk scores of Eq. 9), stored row-major and/or transposed.
 // W = T K and U = T V (Eq. 11) are rebuilt from T inside the scan kernels: T is 8 KB per chunk
-// where W and U are 32 KB.
+// where W and U are 32 KB.  In the backward pass the inverse X itself is stored as well, so that the
+// chunk kernel does not have to invert again.
 template <typename T, int DK, int DV> struct PrepSmem {
     static constexpr int LD = ldc<T>(DK), LT = ldc<T>(C), LF = C + 4, LO = 40;
     static constexpr size_t oK = 0;
@@ -98,12 +99,16 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     }
     lds_barrier();
     tri_inverse_64_inplace<T>(sX, SM::LF, sM, sT, SM::LO);
+    T *sXo = sK; // K is dead: its bytes stage X for the backward's chunk kernel
     for (int e = tid; e < C * C; e += NTHR) { // T = X diag(beta)
         const int i = e >> 6, j = e & 63;
-        sT[i * SM::LT + j] = from_f32<T>(sX[i * SM::LF + j] * sBeta[j]);
+        const float x = sX[i * SM::LF + j];
+        sT[i * SM::LT + j] = from_f32<T>(x * sBeta[j]);
+        if (p.want_pt) sXo[i * SM::LT + j] = from_f32<T>(x);
     }
     lds_barrier();
     store_tile<T, C, C>((T *)p.Tm + tile * C * C, C, sT, SM::LT, C);
+    if (p.want_pt) store_tile<T, C, C>((T *)p.Xm + tile * C * C, C, sXo, SM::LT, C);
 }
 
 // =============================================================================================
@@ -432,7 +437,7 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
 // state S, the gradient dS' w.r.t. the state after the chunk, Ut and dUt from the two scans (all four
 // arrive transposed, [d_v][d_k] and [d_v][C], as the scans hold them in LDS):
 //   adjoint of Eq. 8-9:  dP = tril(dO Ut^T); dQ = dO S^T + dP K; dK1 = dP^T Q + Ut dS'^T; dW = -dUt S^T
-//   adjoint of Eq. 10-11, with X = (I+A)^-1, A = tril(diag(beta) G,-1), G = K K^T, dU = dUt:
+//   adjoint of Eq. 10-11, with X = (I+A)^-1 (read back from k_wy_prep), A = tril(diag(beta) G,-1), G = K K^T, dU = dUt:
 //     dX' = dW K^T + dU V^T;  dX = dX' diag(beta);  dKb = X^T dW;  dV = diag(beta) X^T dU;
 //     dA = -tril(X^T dX X^T, -1);  Ah = diag(beta) dA;
 //     dK = dK1 + diag(beta) dKb + Ah K + Ah^T K;
@@ -440,21 +445,18 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
 // dW and dK1 never leave the chip.  LDS buffers are reused as operands die; V and dS' wait in
 // registers until their buffer is free.
 template <typename T, int DK, int DV> struct ChunkSmem {
-    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4, LO = 40;
+    static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4;
     static constexpr int LU = ldc<T>(C), LSK = ldn<T>(DK); // rows of Ut^T / dUt^T ([d_v][C]) and of S^T / dS'^T ([d_v][d_k])
-    static constexpr bool kXnIsX = sizeof(T) == sizeof(float); // fp32: the inverse itself is the operand
     static constexpr size_t szX = sizeof(float) * C * LF, szCC = sizeof(T) * C * LT;
     static constexpr size_t oB1 = 0;                                   // dO; V; dA o G (fp32)
     static constexpr size_t oB2 = oB1 + align16(cmax(sizeof(T) * C * LV, szX));     // Ut^T; dW
     static constexpr size_t oB3 = oB2 + align16(cmax(sizeof(T) * DV * LU, sizeof(T) * C * LK)); // dUt^T
     static constexpr size_t oB4 = oB3 + align16(sizeof(T) * DV * LU);  // K
-    static constexpr size_t oB5 = oB4 + align16(sizeof(T) * C * LK);   // Q; inverse scratch; M1^T
-    static constexpr size_t oB6 = oB5 + align16(cmax(sizeof(T) * C * LK, szCC)); // dP; (inverse scratch); dX; Ah
-    static constexpr size_t oB7 = oB6 + align16(szCC);                 // S^T; dS'^T; fp32 A / X, then X as T
-    static constexpr size_t szB7 = cmax(sizeof(T) * DV * LSK, align16(szX) + (kXnIsX ? 0 : szCC));
-    static_assert(sizeof(T) * 4 * 32 * LO <= oB7 - oB5, "the inverse's operand scratch spans the dead Q and dP buffers");
-    static constexpr size_t oM = oB7 + align16(szB7);
-    static constexpr size_t oBeta = oM + sizeof(float) * 512;
+    static constexpr size_t oB5 = oB4 + align16(sizeof(T) * C * LK);   // Q; M1^T
+    static constexpr size_t oB6 = oB5 + align16(cmax(sizeof(T) * C * LK, szCC)); // dP; dX; Ah
+    static constexpr size_t oB7 = oB6 + align16(szCC);                 // S^T; dS'^T; X
+    static constexpr size_t szB7 = cmax(sizeof(T) * DV * LSK, szCC);
+    static constexpr size_t oBeta = oB7 + align16(szB7);
     static constexpr size_t oDb = oBeta + sizeof(float) * C;
     static constexpr size_t oStage = align16(oDb + sizeof(float) * 4 * C);
     static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
@@ -463,7 +465,6 @@ template <typename T, int DK, int DV> struct ChunkSmem {
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int chunks_total) {
     using SM = ChunkSmem<T, DK, DV>;
-    static_assert(!SM::kXnIsX || SM::LT == SM::LF, "fp32 operand copy aliases the inverse");
     constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);        // 32 x 32 tiles of a C x DK / C x DV matrix
     constexpr int KW = (KT + NWC - 1) / NWC, VW = (VT + NWC - 1) / NWC; // ... per wave
     extern __shared__ __align__(16) unsigned char smem[];
@@ -474,12 +475,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     T *sDU = reinterpret_cast<T *>(smem + SM::oB3);
     T *sK = reinterpret_cast<T *>(smem + SM::oB4);
     T *sQ = reinterpret_cast<T *>(smem + SM::oB5), *sM1T = sQ;
-    T *sOp = reinterpret_cast<T *>(smem + SM::oB5); // Q and dP are dead by the time of the inverse
     T *sDP = reinterpret_cast<T *>(smem + SM::oB6), *sDX = sDP;
     T *sS = reinterpret_cast<T *>(smem + SM::oB7);
-    float *sX = reinterpret_cast<float *>(smem + SM::oB7);
-    T *sXn = reinterpret_cast<T *>(smem + SM::oB7 + (SM::kXnIsX ? 0 : align16(SM::szX)));
-    float *sM = reinterpret_cast<float *>(smem + SM::oM);
+    T *sXn = reinterpret_cast<T *>(smem + SM::oB7); // X = (I + A)^-1 as computed by k_wy_prep
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -497,6 +495,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         TileRegs<T, DV, C, NTC> ut, dut;
         TileRegs<T, DV, DK, NTC> s, ds;
         TileRegs<T, C, DK, NTC> k, q;
+        TileRegs<T, C, C, NTC> x;
         T beta; // kept in storage format: converting here would wait for the whole prefetch
     } r;
     auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
@@ -510,6 +509,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (tid < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tid, tp.nvalid - 1)) * H + tp.h];
         r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV);
         r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
+        r.x.load((const T *)p.Xm + tp.tile * C * C, C, C);
     };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
 
@@ -570,21 +570,19 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             mma<DV, true, false, T>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV);
         }
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
-        if (cc) acc_each(g, [&](int rr, int c, float &val) { sX[(32 * mi + rr) * SM::LF + 32 * ni + c] = sBeta[32 * mi + rr] * val; });
-        lds_barrier(); // V is dead
-        tri_inverse_64_inplace<T, NTC>(sX, SM::LF, sM, sOp, SM::LO);
+        lds_barrier(); // V and dS' are dead
+        r.x.store(sXn, SM::LT);
+        lds_barrier();
         if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
             float part = 0.f;
             acc_each(dxp, [&](int rr, int c, float &val) {
                 const int i = 32 * mi + rr, j = 32 * ni + c;
-                part += sX[i * SM::LF + j] * val;
+                part += to_f32(sXn[i * SM::LT + j]) * val;
                 val *= sBeta[j];
             });
             sDb[(2 * mi + (lane >> 5)) * C + 32 * ni + (lane & 31)] = part; // summed in a fixed order at the end
             acc_to_lds<T>(sDX, SM::LT, 32 * mi, 32 * ni, dxp);
         }
-        if (!SM::kXnIsX)
-            for (int e = tid; e < C * C; e += NTC) sXn[(e >> 6) * SM::LT + (e & 63)] = from_f32<T>(sX[(e >> 6) * SM::LF + (e & 63)]);
         lds_barrier();
         f32x16 m1 = zero16(); // M1 = dX X^T
         if (cc) mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);

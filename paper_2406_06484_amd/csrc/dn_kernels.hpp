@@ -513,6 +513,12 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
 
+    // Workgroups that start together stay in lockstep: every CU issues its tile's load burst at the same
+    // moment and then all of them compute while HBM idles.  When each workgroup has several tiles to
+    // walk, delay it by (blockIdx mod 4) quarter-tiles (one s_sleep(127) is about 8K cycles) so the
+    // bursts of neighbouring CUs interleave with each other's MFMA phases.
+    if ((long)chunks_total * H >= 4l * gridDim.x)
+        for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(127);
     for (TileIter it(chunks_total, H); it.valid(); it.next()) {
         const TilePos cur = pos_of(it);
         if (!cur.ok) continue; // packed layout: past the last real chunk

@@ -45,12 +45,14 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
 // where W and U are 32 KB.  In the backward pass the inverse X itself is stored as well, so that the
 // chunk kernel does not have to invert again.
 template <typename T, int DK, int DV> struct PrepSmem {
-    static constexpr int LD = ldc<T>(DK), LT = ldc<T>(C), LF = C + 4, LO = 40;
-    static constexpr size_t oK = 0;
-    static constexpr size_t oX = oK + align16(sizeof(T) * C * LD);
-    static constexpr size_t oT = oX + align16(sizeof(float) * C * LF); // P staging, inverse operands, then T
-    static constexpr size_t szT = cmax(cmax(sizeof(T) * C * LT, sizeof(T) * 4 * 32 * LO), NWAVE * sizeof(T) * Stage<T>::ELEMS);
-    static constexpr size_t oM = oT + align16(szT);
+    static constexpr int LD = ldc<T>(DK), LF = C + 4, LO = 40;
+    // region 1: K while the two Gram products run, then the fp32 matrix that is inverted in place
+    static constexpr size_t oK = 0, oX = 0;
+    static constexpr size_t sz1 = cmax(sizeof(T) * C * LD, sizeof(float) * C * LF);
+    // region 2: per-wave staging of the P tiles, then the operands of the inverse's MFMA stage
+    static constexpr size_t oOp = oX + align16(sz1);
+    static constexpr size_t sz2 = cmax(sizeof(T) * 4 * 32 * LO, NWAVE * sizeof(T) * Stage<T>::ELEMS);
+    static constexpr size_t oM = oOp + align16(sz2);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t bytes = oBeta + sizeof(float) * C;
 };
@@ -61,10 +63,10 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     extern __shared__ __align__(16) unsigned char smem[];
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     float *sX = reinterpret_cast<float *>(smem + SM::oX);
-    T *sT = reinterpret_cast<T *>(smem + SM::oT);
+    T *sOp = reinterpret_cast<T *>(smem + SM::oOp);
     float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
-    T *stg = sT + (threadIdx.x >> 6) * Stage<T>::ELEMS;
+    T *stg = sOp + (threadIdx.x >> 6) * Stage<T>::ELEMS;
 
     int n, ic;
     if (!sm.chunk(blockIdx.x, n, ic)) return;
@@ -82,33 +84,37 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     load_tile<T, C, DK>(sK, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
     lds_barrier();
-    { // A = tril(diag(beta) K K^T, -1)
-        f32x16 g = zero16();
-        if (!upper) mma<DK, false, false, T>(g, sK + 32 * mi * SM::LD, SM::LD, sK + 32 * ni * SM::LD, SM::LD);
-        acc_each(g, [&](int r, int c, float &val) {
-            const int i = 32 * mi + r, j = 32 * ni + c;
-            sX[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
-        });
+    f32x16 g = zero16(), acc = zero16();
+    if (!upper) {
+        mma<DK, false, false, T>(g, sK + 32 * mi * SM::LD, SM::LD, sK + 32 * ni * SM::LD, SM::LD); // K K^T
+        mma_ra<0, DK, false>(acc, qf, sK + 32 * ni * SM::LD, SM::LD);                               // Q K^T
     }
+    lds_barrier(); // K is dead from here on; its bytes take the fp32 matrix
+    acc_each(g, [&](int r, int c, float &val) { // A = tril(diag(beta) K K^T, -1)
+        const int i = 32 * mi + r, j = 32 * ni + c;
+        sX[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
+    });
     if (!upper) { // P = tril(Q K^T), diagonal included
-        f32x16 acc = zero16();
-        mma_ra<0, DK, false>(acc, qf, sK + 32 * ni * SM::LD, SM::LD);
         acc_each(acc, [&](int r, int c, float &val) { if (32 * ni + c > 32 * mi + r) val = 0.f; });
         if (p.want_p) acc_store<T>(stg, (T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
         if (p.want_pt) acc_store_t<T>(stg, (T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
     }
     lds_barrier();
-    tri_inverse_64_inplace<T>(sX, SM::LF, sM, sT, SM::LO);
-    T *sXo = sK; // K is dead: its bytes stage X for the backward's chunk kernel
-    for (int e = tid; e < C * C; e += NTHR) { // T = X diag(beta)
-        const int i = e >> 6, j = e & 63;
-        const float x = sX[i * SM::LF + j];
-        sT[i * SM::LT + j] = from_f32<T>(x * sBeta[j]);
-        if (p.want_pt) sXo[i * SM::LT + j] = from_f32<T>(x);
+    tri_inverse_64_inplace<T>(sX, SM::LF, sM, sOp, SM::LO);
+    // T = X diag(beta), and X itself for the backward pass, converted and written 16 bytes at a time
+    constexpr int VEC = El<T>::VEC, SEGS = C / VEC;
+    for (int e = tid; e < C * SEGS; e += NTHR) {
+        const int i = e / SEGS, j0 = (e % SEGS) * VEC;
+        alignas(16) T tv[VEC], xv[VEC];
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            const float x = sX[i * SM::LF + j0 + u];
+            tv[u] = from_f32<T>(x * sBeta[j0 + u]);
+            xv[u] = from_f32<T>(x);
+        }
+        *reinterpret_cast<uint4 *>((T *)p.Tm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(tv);
+        if (p.want_pt) *reinterpret_cast<uint4 *>((T *)p.Xm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(xv);
     }
-    lds_barrier();
-    store_tile<T, C, C>((T *)p.Tm + tile * C * C, C, sT, SM::LT, C);
-    if (p.want_pt) store_tile<T, C, C>((T *)p.Xm + tile * C * C, C, sXo, SM::LT, C);
 }
 
 // =============================================================================================
@@ -235,16 +241,16 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
             stage_flush<T>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
                            min(C, len - icp * C));
     };
-    if (loader && nchunks > 0) fetch(0);
+    auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
+        if (!STORE) { r.q.store(sQ, SM::LQ, lt); r.pm.store(sP, SM::LT, lt); }
+        r.k.store(sK, SM::LK, lt);
+        r.v.store(sV, SM::LV, lt);
+        r.t.store(sT, SM::LT, lt);
+    };
+    if (loader && nchunks > 0) { fetch(0); stash(); }
     for (int ic = 0; ic < nchunks; ++ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sUT = (ic & 1) ? sUT1 : sUT0;
-        if (loader) {
-            if (!STORE) { r.q.store(sQ, SM::LQ, lt); r.pm.store(sP, SM::LT, lt); }
-            r.k.store(sK, SM::LK, lt);
-            r.v.store(sV, SM::LV, lt);
-            r.t.store(sT, SM::LT, lt);
-        }
         if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         lds_barrier();
         if (loader) {
@@ -281,6 +287,9 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         }
         if (m.has_s) mma<C, true, false, T>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         lds_barrier();
+        // The next chunk's tiles move to LDS here, in the iteration that requested them: the wait the
+        // compiler puts in front counts the stores issued after the loads and lets those stay in flight.
+        if (loader && ic + 1 < nchunks) stash();
     }
     if (loader && nchunks > 0) flush_prev(nchunks - 1);
     if (!STORE && p.ST && m.has_s) {
@@ -360,14 +369,14 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     };
     // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
-    if (loader && nchunks > 0) fetch(nchunks - 1);
+    auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
+        r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
+        r.t.store(sT, SM::LT, lt); r.pt.store(sPT, SM::LT, lt);
+    };
+    if (loader && nchunks > 0) { fetch(nchunks - 1); stash(); }
     for (int ic = nchunks - 1; ic >= 0; --ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sDUT = (ic & 1) ? sDUT1 : sDUT0;
-        if (loader) {
-            r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
-            r.t.store(sT, SM::LT, lt); r.pt.store(sPT, SM::LT, lt);
-        }
         if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' (gradient w.r.t. the state after this chunk)
         lds_barrier();
         if (loader) {
@@ -396,6 +405,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
             dS -= wd;
         }
         lds_barrier();
+        if (loader && ic > 0) stash(); // see k_scan_fwd
     }
     if (loader && nchunks > 0) flush_dut(0);
     if (p.dS0 && m.has_s) {

@@ -35,12 +35,10 @@ def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
     """Dense-tile FLOPs one (chunk, head) costs in each kernel (what that kernel contracts)."""
     if "k_wy_prep" in name:      # K K^T, Q K^T, forward substitution
         return 4 * c * c * d + (2.0 / 3.0) * c ** 3
-    if "k_scan_fwd" in name and "true" in name:   # state recompute: T K, T V, W S, K^T Ut
-        return 4 * c * d * d + 4 * c * c * d
+    if "k_scan_pair" in name:    # recompute scan: T K, T V, W S, K^T Ut; reverse scan: T K, P^T dO, K dS, Q^T dO, W^T dUt
+        return (4 * c * d * d + 4 * c * c * d) + (6 * c * d * d + 4 * c * c * d)
     if "k_scan_fwd" in name:     # T K, T V, P Ut (3 x 2C^2 d); W S, Q S, K^T Ut (3 x 2Cd^2)
         return 6 * c * d * d + 6 * c * c * d
-    if "k_scan_bwd" in name:     # T K, P^T dO (2 x 2C^2 d); K dS, Q^T dO, W^T dUt (3 x 2Cd^2)
-        return 6 * c * d * d + 4 * c * c * d
     if "k_bwd_chunk" in name:
         # adjoint of Eq. 8-9: dO S^T, dUt S^T, Ut dS^T (3 x 2Cd^2); dO Ut^T, dP K, dP^T Q (3 x 2C^2 d)
         # adjoint of Eq. 10-11: K K^T, dW K^T, dU V^T, X^T dW, X^T dU, Ah K, Ah^T K (7 x 2C^2 d);
@@ -55,9 +53,8 @@ def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
 # inside this script, so the figures are carried here and refreshed whenever the kernels change.
 MEASURED_HBM_BYTES = {
     "k_wy_prep": 195.1e6,
-    "k_scan_fwd<T, DK, DV, false>": 344.1e6,
-    "k_scan_fwd<T, DK, DV, true>": 369.7e6,
-    "k_scan_bwd": 478.3e6,
+    "k_scan_fwd": 344.1e6,
+    "k_scan_pair": 848.0e6,
     "k_bwd_chunk": 886.3e6,
 }
 

@@ -134,8 +134,8 @@ template <typename T, int DV> struct VBlock {
     static constexpr int NV = DV / BV;
 };
 
-__device__ inline bool chain_of_block(int nchains, int nv, int &chain, int &vbi) {
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+__device__ inline bool chain_of_block(int bid, int nchains, int nv, int &chain, int &vbi) {
+    const int xcd = bid & 7, slot = bid >> 3;
     vbi = slot % nv;
     chain = (slot / nv) * 8 + xcd;
     return chain < nchains;
@@ -179,7 +179,7 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
 };
 
 template <typename T, int DK, int DV, bool STORE>
-__global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
+__device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanFwdSmem<T, DK, DV>;
     constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
     using Map = ScanMap<DK, BV>;
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     T *sP = reinterpret_cast<T *>(smem + SM::oP);
 
     int chain, vbi;
-    if (!chain_of_block(sm.N * H, NV, chain, vbi)) return;
+    if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
     const int n = chain / H, h = chain - n * H, vb = vbi * BV;
     const int wave = threadIdx.x >> 6;
     int t0, len, cb;
@@ -297,6 +297,10 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
 }
+template <typename T, int DK, int DV>
+__global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
+    scan_fwd_body<T, DK, DV, false>(sm, H, p, blockIdx.x);
+}
 
 // k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
 //   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
@@ -317,7 +321,7 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
 };
 
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
+__device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanBwdSmem<T, DK, DV>;
     constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
     using Map = ScanMap<DK, BV>;
@@ -332,7 +336,7 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
 
     int chain, vbi;
-    if (!chain_of_block(sm.N * H, NV, chain, vbi)) return;
+    if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
     const int n = chain / H, h = chain - n * H, vb = vbi * BV;
     const int wave = threadIdx.x >> 6;
     int t0, len, cb;
@@ -412,6 +416,16 @@ __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
         float *dst = p.dS0 + (long)chain * DK * DV + vb;
         acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
+}
+
+// The backward pass's two scans in one launch.  They do not depend on each other (the recompute
+// scan needs T; the reverse scan needs T and P^T), so the first half of the grid runs the reverse
+// scan and the second half the recompute scan: a CU picks up one of each with no kernel boundary
+// in between.  `half` = workgroups per scan.
+template <typename T, int DK, int DV>
+__global__ __launch_bounds__(NTS) void k_scan_pair(SeqMap sm, int H, Ptrs p, int half) {
+    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV>(sm, H, p, blockIdx.x);
+    else scan_fwd_body<T, DK, DV, true>(sm, H, p, blockIdx.x - half);
 }
 
 // =============================================================================================

@@ -52,7 +52,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH_NT((k_scan_fwd<T, DK, DV>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;
 }
 
@@ -62,8 +62,11 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
     if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    if (pb.chunks_ub) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    DN_LAUNCH_NT((k_scan_bwd<T, DK, DV>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    { // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
+        constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
+        const dim3 gpair(2 * gchain.x);
+        DN_LAUNCH_NT((k_scan_pair<T, DK, DV>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
+    }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU

@@ -47,15 +47,31 @@ def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
     return 0.0
 
 
+def kernel_bytes_per_chunk_head(name: str, d: int, c: int = C, es: int = 2) -> float:
+    """Operand bytes one (chunk, head) costs in each kernel: every tile it must read or write, once.
+
+    tile = C x d elements, cc = C x C, st = d x d (states leave the scans in the element type)."""
+    tile, cc, st, beta = c * d * es, c * c * es, d * d * es, c * es
+    if "k_wy_prep" in name:      # mean of its two launches: K, Q, beta -> T, P (forward) / T, X, P^T (backward);
+        return 2 * tile + beta + 2.25 * cc   # the all-zero upper 32 x 32 block of P is never stored
+    if "k_scan_pair" in name:    # K, V, T -> Ut, S   and   Q, K, dO, T, P^T -> dUt, dS'
+        return (2 * tile + cc + tile + st) + (3 * tile + 2 * cc + tile + st)
+    if "k_scan_fwd" in name:     # Q, K, V, T, P -> O
+        return 3 * tile + 2 * cc + tile
+    if "k_bwd_chunk" in name:    # dO, Ut, dUt, K, Q, V, S, dS', X, beta -> dQ, dK, dV, dbeta
+        return 6 * tile + 2 * st + cc + beta + 3 * tile + c * 4
+    return 0.0
+
+
 # HBM bytes per launch of each kernel on this workload: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each
 # scaled by what the same counter reads for a plain 256 MiB device copy (factors 2.000 and 1.000);
 # summary and commands in profiles/hbm_traffic_cfg2_fwd_bwd.txt.  The counters cannot be read from
 # inside this script, so the figures are carried here and refreshed whenever the kernels change.
 MEASURED_HBM_BYTES = {
-    "k_wy_prep": 195.1e6,
+    "k_wy_prep": 212.2e6,
     "k_scan_fwd": 344.1e6,
-    "k_scan_pair": 848.0e6,
-    "k_bwd_chunk": 886.3e6,
+    "k_scan_pair": 844.9e6,
+    "k_bwd_chunk": 919.1e6,
 }
 
 
@@ -148,18 +164,20 @@ def main() -> int:
         nm = name.strip("()")
         avg = ms / n
         fl = kernel_flops_per_chunk_head(nm, d) * chunk_heads
+        by = kernel_bytes_per_chunk_head(nm, d) * chunk_heads
         kernels[nm] = {"avg_ms": round(avg, 4), "launches_per_step": n // args.steps,
-                       "tflops": round(fl / (avg * 1e-3) / 1e12, 2)}
+                       "tflops": round(fl / (avg * 1e-3) / 1e12, 2), "gbs": round(by / (avg * 1e-3) / 1e9, 1)}
     # k_wy_prep runs twice per step (forward and backward); weight by launches per step
     dom = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
     fwd_f, bwd_f = model_flops_per_token_head(d)
     model_tflops = (fwd_f + bwd_f) * H * value / 1e12
-    traffic = measured_traffic(dom)
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic}
-    if traffic:  # the same kernel against the HBM roof, from the measured bytes
-        gbs = traffic / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
-        roofline["hbm"] = {"achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    # Every kernel of the path sits nearer the HBM roof than the MFMA roof (its operand bytes / 8 TB/s
+    # exceed its FLOPs / 2.5 PFLOP/s), so the dominant kernel is placed against HBM; the same kernel
+    # against the bf16 MFMA roof rides along.
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(kernels[dom]["gbs"] / PEAK_HBM_GBS, 4), "traffic": measured_traffic(dom),
+                "mfma": {"achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4)}}
 
     out = {
         "metric": "DeltaNet layer fwd+bwd tokens/s at H=16,d=128,L=2048; % bf16 MFMA peak",

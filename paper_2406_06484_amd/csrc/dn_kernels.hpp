@@ -1,11 +1,11 @@
-// The five kernels of the chunkwise DeltaNet forward/backward (gfx950), templated on the element
+// The kernels of the chunkwise DeltaNet forward/backward (gfx950), templated on the element
 // type T (float: fp32 MFMA; bf16: bf16 MFMA with fp32 accumulation) and the head dims.
 //
-//   k_wy_prep    per chunk            A = tril(diag(beta) K K^T,-1); X = (I+A)^-1; W = X diag(beta) K; U = X diag(beta) V   (Eq. 10-11)
-//   k_scan_fwd   per chain x v-block  serial over chunks: Ut = U - W S; O = Q S + tril(Q K^T) Ut; S += K^T Ut          (Eq. 8-9)
-//   k_scan_bwd   per chain x v-block  reverse over chunks: dUt = P^T dO + K dS'; dS = dS' + Q^T dO - W^T dUt
-//   k_bwd_dqkw   per chunk            dQ, the part of dK that comes through Eq. 8-9, and dW = -dUt S^T
-//   k_bwd_wy     per chunk            adjoint of Eq. 10-11: dK, dV, dbeta
+//   k_wy_prep    per chunk            A = tril(diag(beta) K K^T,-1); X = (I+A)^-1; T = X diag(beta); P = tril(Q K^T)   (Eq. 10)
+//   k_scan_fwd   per chain x v-block  serial over chunks: W = T K, U = T V (Eq. 11); Ut = U - W S; O = Q S + P Ut; S += K^T Ut  (Eq. 8-9)
+//   k_scan_pair  per chain x v-block  backward: the state-recompute scan (stores chunk-initial S and Ut) and the reverse
+//                                     scan (dUt = P^T dO + K dS'; dS = dS' + Q^T dO - W^T dUt) as one grid
+//   k_bwd_chunk  per chunk            adjoint of Eq. 8-9 given S, dS', Ut, dUt, then adjoint of Eq. 10-11: dQ, dK, dV, dbeta
 //
 // State S is [d_k][d_v] (orientation of the paper's pseudocode listing), fp32 in registers.
 #pragma once
@@ -120,10 +120,11 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
 // =============================================================================================
 // The two chain-serial kernels.  One workgroup of 8 wavefronts owns one chain and BV = 64 columns
 // of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.
-// Waves 0..3 carry the dependent chain (Ut, then the state update); waves 4..7 have the lighter
-// off-chain work and double as loaders: they alone issue the global loads (two chunks ahead, into
-// two alternating register sets) and move them to LDS, so the chain waves never queue behind the
-// CU's 64 B/clk vector-memory path.  W = T K (Eq. 11) is rebuilt per chunk from the 64 x 64 T.
+// Waves 0..3 own the Ut / dUt tiles of the dependent chain; waves 4..7 have the lighter work between
+// barriers and double as loaders: they alone touch global memory, one burst per step (the next
+// chunk's tiles into registers, the previous chunk's results out of LDS), so the chain waves never
+// queue behind the CU's 64 B/clk vector-memory path.  W = T K (Eq. 11) is rebuilt per chunk from
+// the 64 x 64 T.
 // Workgroup ids are laid out so that the v-blocks of one chain land on the same XCD (ids are dealt
 // round-robin over the 8 XCDs) and share its L2 for the Q, K, T tiles they both read.
 constexpr int NTS = 512, NWS = 8, NTL = 256; // threads / waves of a scan workgroup; loader threads
@@ -159,7 +160,7 @@ template <int DK, int BV> struct ScanMap {
     }
 };
 
-// k_scan_fwd: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
+// scan_fwd_body: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
 // writes every chunk-initial state and Ut to the workspace instead of O.
 template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr int BV = VBlock<T, DV>::BV;
@@ -302,7 +303,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
     scan_fwd_body<T, DK, DV, false>(sm, H, p, blockIdx.x);
 }
 
-// k_scan_bwd: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
+// scan_bwd_body: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
 //   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
 // Per chunk it leaves dS'^T and dUt^T in the workspace (the transposed LDS copies, written out by the loader waves).
 template <typename T, int DK, int DV> struct ScanBwdSmem {
@@ -430,8 +431,8 @@ __global__ __launch_bounds__(NTS) void k_scan_pair(SeqMap sm, int H, Ptrs p, int
 
 // =============================================================================================
 // The chunk-parallel backward kernel.  Workgroups are persistent: each walks over (chunk, head)
-// tiles with a grid stride and requests the next tile's operands (into registers) while it works on
-// the current one, so global latency is hidden behind the second half of the current tile.
+// tiles with a grid stride; a tile's operands (168 KB in bf16 at d = 128) fill the whole LDS, so
+// overlap of loads and MFMA work comes from the CUs running out of step with each other.
 constexpr int NTC = 512, NWC = 8;
 
 struct TileIter { // grid-stride walk over (global chunk id, head) tiles

@@ -33,12 +33,12 @@ def model_flops_per_token_head(d: int, c: int = C):
 
 def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
     """Dense-tile FLOPs one (chunk, head) costs in each kernel (what that kernel contracts)."""
-    if "k_wy_prep" in name:      # K K^T, Q K^T, forward substitution
-        return 4 * c * c * d + (2.0 / 3.0) * c ** 3
-    if "k_scan_pair" in name:    # recompute scan: T K, T V, W S, K^T Ut; reverse scan: T K, P^T dO, K dS, Q^T dO, W^T dUt
-        return (4 * c * d * d + 4 * c * c * d) + (6 * c * d * d + 4 * c * c * d)
-    if "k_scan_fwd" in name:     # T K, T V, P Ut (3 x 2C^2 d); W S, Q S, K^T Ut (3 x 2Cd^2)
-        return 6 * c * d * d + 6 * c * c * d
+    if "k_wy_prep" in name:      # K K^T, forward substitution
+        return 2 * c * c * d + (2.0 / 3.0) * c ** 3
+    if "k_scan_pair" in name:    # recompute scan: T K, T V, W S, K^T Ut; reverse scan: T K, K Q^T, P^T dO, K dS, Q^T dO, W^T dUt
+        return (4 * c * d * d + 4 * c * c * d) + (6 * c * d * d + 6 * c * c * d)
+    if "k_scan_fwd" in name:     # T K, T V, Q K^T, P Ut (4 x 2C^2 d); W S, Q S, K^T Ut (3 x 2Cd^2)
+        return 6 * c * d * d + 8 * c * c * d
     if "k_bwd_chunk" in name:
         # adjoint of Eq. 8-9: dO S^T, dUt S^T, Ut dS^T (3 x 2Cd^2); dO Ut^T, dP K, dP^T Q (3 x 2C^2 d)
         # adjoint of Eq. 10-11: K K^T, dW K^T, dU V^T, X^T dW, X^T dU, Ah K, Ah^T K (7 x 2C^2 d);
@@ -52,12 +52,12 @@ def kernel_bytes_per_chunk_head(name: str, d: int, c: int = C, es: int = 2) -> f
 
     tile = C x d elements, cc = C x C, st = d x d (states leave the scans in the element type)."""
     tile, cc, st, beta = c * d * es, c * c * es, d * d * es, c * es
-    if "k_wy_prep" in name:      # mean of its two launches: K, Q, beta -> T, P (forward) / T, X, P^T (backward);
-        return 2 * tile + beta + 2.25 * cc   # the all-zero upper 32 x 32 block of P is never stored
-    if "k_scan_pair" in name:    # K, V, T -> Ut, S   and   Q, K, dO, T, P^T -> dUt, dS'
-        return (2 * tile + cc + tile + st) + (3 * tile + 2 * cc + tile + st)
-    if "k_scan_fwd" in name:     # Q, K, V, T, P -> O
-        return 3 * tile + 2 * cc + tile
+    if "k_wy_prep" in name:      # mean of its two launches: K, beta -> T (forward) / T, X (backward)
+        return tile + beta + 1.5 * cc
+    if "k_scan_pair" in name:    # K, V, T -> Ut, S   and   Q, K, dO, T -> dUt, dS'
+        return (2 * tile + cc + tile + st) + (3 * tile + cc + tile + st)
+    if "k_scan_fwd" in name:     # Q, K, V, T -> O
+        return 3 * tile + cc + tile
     if "k_bwd_chunk" in name:    # dO, Ut, dUt, K, Q, V, S, dS', X, beta -> dQ, dK, dV, dbeta
         return 6 * tile + 2 * st + cc + beta + 3 * tile + c * 4
     return 0.0

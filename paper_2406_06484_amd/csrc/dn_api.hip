@@ -109,7 +109,6 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
     pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * ((size_t)pb.N + 1)) : 0;
     const size_t tC = up256(tiles * kChunk * kChunk * pl->esz);
     pl->off_T = o; o += tC; // T of Eq. 10
-    pl->off_P = o; o += tC; // tril(Q K^T) (forward) or its transpose (backward)
     if (want_bwd) {
         pl->off_X = o; o += tC; // (I + A)^-1 of Eq. 10, reused by the chunk kernel
         pl->off_Ut = o; o += tV;
@@ -126,9 +125,7 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     unsigned char *b = static_cast<unsigned char *>(ws);
     pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
     p->Tm = b + pl.off_T;
-    p->P = p->PT = b + pl.off_P;
-    p->want_p = !want_bwd;
-    p->want_pt = want_bwd;
+    p->want_x = want_bwd;
     if (want_bwd) {
         p->Xm = b + pl.off_X;
         p->Ut = b + pl.off_Ut; p->dUt = b + pl.off_dUt; p->Sc = b + pl.off_Sc;

@@ -22,8 +22,8 @@ struct Ptrs {
     void *o, *dq, *dk, *dv;
     float *ST, *dbeta, *dS0;
     // workspace tiles, indexed by (global chunk * H + head)
-    void *Tm, *Xm, *P, *PT, *Ut, *dUt, *Sc, *dSc;
-    int want_p, want_pt; // which of tril(Q K^T) / its transpose k_wy_prep should write
+    void *Tm, *Xm, *Ut, *dUt, *Sc, *dSc;
+    int want_x; // backward: k_wy_prep also stores the inverse X for the chunk kernel
 };
 
 // Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is

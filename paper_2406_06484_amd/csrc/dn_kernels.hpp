@@ -39,8 +39,7 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
 }
 
 // =============================================================================================
-// k_wy_prep: per chunk, T = (I + tril(diag(beta) K K^T, -1))^-1 diag(beta) (Eq. 10) and
-// P = tril(Q K^T) (the causal intra-chunk scores of Eq. 9), stored row-major and/or transposed.
+// k_wy_prep: per chunk, T = (I + tril(diag(beta) K K^T, -1))^-1 diag(beta) (Eq. 10).
 // W = T K and U = T V (Eq. 11) are rebuilt from T inside the scan kernels: T is 8 KB per chunk
 // where W and U are 32 KB.  In the backward pass the inverse X itself is stored as well, so that the
 // chunk kernel does not have to invert again.
@@ -49,9 +48,9 @@ template <typename T, int DK, int DV> struct PrepSmem {
     // region 1: K while the two Gram products run, then the fp32 matrix that is inverted in place
     static constexpr size_t oK = 0, oX = 0;
     static constexpr size_t sz1 = cmax(sizeof(T) * C * LD, sizeof(float) * C * LF);
-    // region 2: per-wave staging of the P tiles, then the operands of the inverse's MFMA stage
+    // region 2: the operands of the inverse's MFMA stage
     static constexpr size_t oOp = oX + align16(sz1);
-    static constexpr size_t sz2 = cmax(sizeof(T) * 4 * 32 * LO, NWAVE * sizeof(T) * Stage<T>::ELEMS);
+    static constexpr size_t sz2 = sizeof(T) * 4 * 32 * LO;
     static constexpr size_t oM = oOp + align16(sz2);
     static constexpr size_t oBeta = oM + sizeof(float) * 512;
     static constexpr size_t bytes = oBeta + sizeof(float) * C;
@@ -66,7 +65,6 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     T *sOp = reinterpret_cast<T *>(smem + SM::oOp);
     float *sM = reinterpret_cast<float *>(smem + SM::oM);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
-    T *stg = sOp + (threadIdx.x >> 6) * Stage<T>::ELEMS;
 
     int n, ic;
     if (!sm.chunk(blockIdx.x, n, ic)) return;
@@ -79,26 +77,16 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     const int mi = wave >> 1, ni = wave & 1; // this wave's 32 x 32 tile of the C x C matrices
     const bool upper = mi == 0 && ni == 1;
 
-    AFrags<T, DK> qf; // Q rows straight from global memory
-    if (!upper) qf.load((const T *)p.q + ((row0 + 32 * mi) * H + h) * DK, (long)H * DK, nvalid - 32 * mi);
     load_tile<T, C, DK>(sK, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
     lds_barrier();
-    f32x16 g = zero16(), acc = zero16();
-    if (!upper) {
-        mma<DK, false, false, T>(g, sK + 32 * mi * SM::LD, SM::LD, sK + 32 * ni * SM::LD, SM::LD); // K K^T
-        mma_ra<0, DK, false>(acc, qf, sK + 32 * ni * SM::LD, SM::LD);                               // Q K^T
-    }
+    f32x16 g = zero16();
+    if (!upper) mma<DK, false, false, T>(g, sK + 32 * mi * SM::LD, SM::LD, sK + 32 * ni * SM::LD, SM::LD); // K K^T
     lds_barrier(); // K is dead from here on; its bytes take the fp32 matrix
     acc_each(g, [&](int r, int c, float &val) { // A = tril(diag(beta) K K^T, -1)
         const int i = 32 * mi + r, j = 32 * ni + c;
         sX[i * SM::LF + j] = j < i ? sBeta[i] * val : 0.f;
     });
-    if (!upper) { // P = tril(Q K^T), diagonal included
-        acc_each(acc, [&](int r, int c, float &val) { if (32 * ni + c > 32 * mi + r) val = 0.f; });
-        if (p.want_p) acc_store<T>(stg, (T *)p.P + tile * C * C, C, 32 * mi, 32 * ni, C, acc);
-        if (p.want_pt) acc_store_t<T>(stg, (T *)p.PT + tile * C * C, C, 32 * mi, 32 * ni, acc);
-    }
     lds_barrier();
     tri_inverse_64_inplace<T>(sX, SM::LF, sM, sOp, SM::LO);
     // T = X diag(beta), and X itself for the backward pass, converted and written 16 bytes at a time
@@ -113,7 +101,7 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
             xv[u] = from_f32<T>(x);
         }
         *reinterpret_cast<uint4 *>((T *)p.Tm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(tv);
-        if (p.want_pt) *reinterpret_cast<uint4 *>((T *)p.Xm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(xv);
+        if (p.want_x) *reinterpret_cast<uint4 *>((T *)p.Xm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(xv);
     }
 }
 
@@ -149,11 +137,10 @@ __host__ inline int chain_grid(int nchains, int nv) { return ((nchains + 7) / 8)
 template <int DK, int BV> struct ScanMap {
     static constexpr int NVT = BV / 32, NKT = DK / 32, S_TILES = NKT * NVT, U_TILES = 2 * NVT, W_TILES = 2 * NKT;
     static_assert(S_TILES <= NWS && U_TILES <= 4 && W_TILES <= NWS, "state tiling");
-    int sa, sb, wk, wi, ua, ub;
-    bool has_s, has_w, does_u, does_o;
+    int sa, sb, ua, ub;
+    bool has_s, does_u, does_o;
     __device__ ScanMap(int wave) {
         sa = wave / NVT; sb = wave % NVT; has_s = wave < S_TILES;
-        wk = wave % NKT; wi = wave / NKT; has_w = wave < W_TILES;
         const int u = wave & 3;
         ua = u / NVT; ub = u % NVT;
         does_u = wave < U_TILES; does_o = wave >= 4 && u < U_TILES;
@@ -205,6 +192,9 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     const Map m(wave);
     const bool loader = wave >= 4, does_o = !STORE && m.does_o;
     const int lt = threadIdx.x - NTL; // index among the loader threads
+    // waves 0, 1, 2 build the three non-zero tiles (0,0), (1,0), (1,1) of P
+    const bool does_p = !STORE && wave < 3;
+    const int pmi = wave > 0, pni = wave > 1;
 
     f32x16 S = zero16();
     if (m.has_s && p.S0) {
@@ -218,7 +208,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     struct Regs {
         TileRegs<T, C, DK, NTL> q, k;
         TileRegs<T, C, BV, NTL> v;
-        TileRegs<T, C, C, NTL> t, pm;
+        TileRegs<T, C, C, NTL> t;
     } r;
     auto fetch = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
@@ -228,7 +218,6 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
-        if (!STORE) r.pm.load((const T *)p.P + tile * C * C, C, C, lt);
     };
     // Everything that touches global memory is issued by the loader waves in one burst right after
     // the first barrier of a step: the loads for the next chunk, then the stores of what the previous
@@ -243,7 +232,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
                            min(C, len - icp * C));
     };
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
-        if (!STORE) { r.q.store(sQ, SM::LQ, lt); r.pm.store(sP, SM::LT, lt); }
+        if (!STORE) r.q.store(sQ, SM::LQ, lt);
         r.k.store(sK, SM::LK, lt);
         r.v.store(sV, SM::LV, lt);
         r.t.store(sT, SM::LT, lt);
@@ -260,18 +249,26 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             if (STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
             if (ic > 0) flush_prev(ic - 1);
         }
-        if (m.has_w) { // W = T K (Eq. 11) as W^T = K^T T^T, so the accumulator rows run along d_k; T is lower triangular
-            f32x16 w = zero16();
-            if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
-            else mma<C, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT + 32 * SM::LT, SM::LT);
-            acc_to_lds_t<T>(sW, SM::LQ, 32 * m.wk, 32 * m.wi, w);
-        }
         f32x16 acc = zero16();
-        if (m.does_u) { // U = T V
-            if (m.ua == 0) mma<32, false, true, T>(acc, sT, SM::LT, sV + 32 * m.ub, SM::LV);
-            else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV);
-        } else if (does_o) { // Q S
-            mma<DK, false, false, T>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
+        if (!loader) { // what does not depend on the state, while the loader waves are busy with the burst
+#pragma unroll
+            for (int t = wave; t < Map::W_TILES; t += 4) { // W = T K (Eq. 11) as W^T = K^T T^T; T is lower triangular
+                const int wk = t % Map::NKT, wi = t / Map::NKT;
+                f32x16 w = zero16();
+                if (wi == 0) mma<32, true, false, T>(w, sK + 32 * wk, SM::LK, sT, SM::LT);
+                else mma<C, true, false, T>(w, sK + 32 * wk, SM::LK, sT + 32 * SM::LT, SM::LT);
+                acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w);
+            }
+            if (m.does_u) { // U = T V
+                if (m.ua == 0) mma<32, false, true, T>(acc, sT, SM::LT, sV + 32 * m.ub, SM::LV);
+                else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV);
+            }
+            if (does_p) { // P = tril(Q K^T): the causal intra-chunk scores of Eq. 9, one 32 x 32 tile per wave
+                f32x16 pa = zero16();
+                mma<DK, false, false, T>(pa, sQ + 32 * pmi * SM::LQ, SM::LQ, sK + 32 * pni * SM::LK, SM::LK);
+                if (pmi == pni) acc_each(pa, [&](int r, int c, float &val) { if (c > r) val = 0.f; });
+                acc_to_lds<T>(sP, SM::LT, 32 * pmi, 32 * pni, pa);
+            }
         }
         lds_barrier();
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
@@ -279,6 +276,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             mma<DK, false, false, T>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
             acc -= ws;
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
+        } else if (does_o) { // Q S
+            mma<DK, false, false, T>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
@@ -346,6 +345,9 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     const Map m(wave);
     const bool loader = wave >= 4;
     const int lt = threadIdx.x - NTL;
+    // waves 0, 1, 2 build the three non-zero tiles (0,0), (0,1), (1,1) of P^T
+    const bool does_p = wave < 3;
+    const int pmi = wave > 1, pni = wave > 0;
 
     f32x16 dS = zero16();
     if (m.has_s && p.dST) {
@@ -357,7 +359,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     struct Regs {
         TileRegs<T, C, DK, NTL> q, k;
         TileRegs<T, C, BV, NTL> d_o;
-        TileRegs<T, C, C, NTL> t, pt;
+        TileRegs<T, C, C, NTL> t;
     } r;
     auto fetch = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
@@ -367,7 +369,6 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
-        r.pt.load((const T *)p.PT + tile * C * C, C, C, lt);
     };
     auto flush_dut = [&](int icp) __attribute__((always_inline)) { // dUt^T of chunk icp, still in LDS
         copy_out<T, BV, C, NTL>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, lt);
@@ -376,7 +377,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
         r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
-        r.t.store(sT, SM::LT, lt); r.pt.store(sPT, SM::LT, lt);
+        r.t.store(sT, SM::LT, lt);
     };
     if (loader && nchunks > 0) { fetch(nchunks - 1); stash(); }
     for (int ic = nchunks - 1; ic >= 0; --ic) {
@@ -389,17 +390,29 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
             copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
             if (ic + 1 < nchunks) flush_dut(ic + 1);
         }
-        if (m.has_w) { // W = T K (Eq. 11), computed as W^T = K^T T^T
-            f32x16 w = zero16();
-            if (m.wi == 0) mma<32, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT, SM::LT);
-            else mma<C, true, false, T>(w, sK + 32 * m.wk, SM::LK, sT + 32 * SM::LT, SM::LT);
-            acc_to_lds_t<T>(sW, SM::LQ, 32 * m.wk, 32 * m.wi, w);
+        f32x16 acc = zero16();
+        if (!loader) { // the loader waves are busy with the burst meanwhile
+            if (does_p) { // P^T = triu(K Q^T): transposed causal scores, one 32 x 32 tile per wave
+                f32x16 pa = zero16();
+                mma<DK, false, false, T>(pa, sK + 32 * pmi * SM::LK, SM::LK, sQ + 32 * pni * SM::LQ, SM::LQ);
+                if (pmi == pni) acc_each(pa, [&](int r, int c, float &val) { if (c < r) val = 0.f; });
+                acc_to_lds<T>(sPT, SM::LT, 32 * pmi, 32 * pni, pa);
+            }
+            if (m.does_u) // K dS' part of the dUt tile (ua, ub)
+                mma<DK, false, false, T>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+#pragma unroll
+            for (int t = wave; t < Map::W_TILES; t += 4) { // W = T K (Eq. 11), computed as W^T = K^T T^T
+                const int wk = t % Map::NKT, wi = t / Map::NKT;
+                f32x16 w = zero16();
+                if (wi == 0) mma<32, true, false, T>(w, sK + 32 * wk, SM::LK, sT, SM::LT);
+                else mma<C, true, false, T>(w, sK + 32 * wk, SM::LK, sT + 32 * SM::LT, SM::LT);
+                acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w);
+            }
         }
-        if (m.does_u) { // dUt tile (ua, ub); P^T is upper triangular
-            f32x16 acc = zero16();
+        lds_barrier();
+        if (m.does_u) { // + P^T dO; P^T is upper triangular
             if (m.ua == 0) mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
             else mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LD + 32 * m.ub, SM::LD);
-            mma<DK, false, false, T>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
             acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO

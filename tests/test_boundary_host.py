@@ -43,8 +43,8 @@ def test_workspace_query_and_validation_errors():
     fwd_bytes = out.value
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape()), 1, ctypes.byref(out)) == 0
     assert out.value > fwd_bytes > 0
-    # two C x C tiles (T of Eq. 10 and tril(Q K^T)) for every (chunk, head), bf16
-    assert fwd_bytes == 2 * (2 * 256 * 4 * 64 * 2)
+    # one C x C tile (T of Eq. 10) for every (chunk, head), bf16
+    assert fwd_bytes == 2 * 256 * 4 * 64 * 2
     assert lib.deltanet_workspace_bytes(None, 0, ctypes.byref(out)) == -1
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(H=0)), 0, ctypes.byref(out)) == -2
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(d_k=96)), 0, ctypes.byref(out)) == -3

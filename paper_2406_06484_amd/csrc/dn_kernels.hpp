@@ -210,14 +210,18 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         TileRegs<T, C, BV, NTL> v;
         TileRegs<T, C, C, NTL> t;
     } r;
-    auto fetch = [&](int ic) __attribute__((always_inline)) {
+    auto fetch_a = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        if (!STORE) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+    };
+    auto fetch_b = [&](int ic) __attribute__((always_inline)) {
+        const int nvalid = min(C, len - ic * C);
+        const long row0 = (long)t0 + (long)ic * C;
+        if (!STORE) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
     };
     // Everything that touches global memory is issued by the loader waves in one burst right after
     // the first barrier of a step: the loads for the next chunk, then the stores of what the previous
@@ -237,18 +241,13 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         r.v.store(sV, SM::LV, lt);
         r.t.store(sT, SM::LT, lt);
     };
-    if (loader && nchunks > 0) { fetch(0); stash(); }
+    if (loader && nchunks > 0) { fetch_a(0); fetch_b(0); stash(); }
     for (int ic = 0; ic < nchunks; ++ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sUT = (ic & 1) ? sUT1 : sUT0;
         if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         lds_barrier();
-        if (loader) {
-            if (ic + 1 < nchunks) fetch(ic + 1);
-            // the chunk-initial state leaves transposed, as it sits in LDS
-            if (STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
-            if (ic > 0) flush_prev(ic - 1);
-        }
+        if (loader && ic + 1 < nchunks) fetch_a(ic + 1);
         f32x16 acc = zero16();
         if (!loader) { // what does not depend on the state, while the loader waves are busy with the burst
 #pragma unroll
@@ -271,6 +270,12 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             }
         }
         lds_barrier();
+        if (loader) {
+            if (ic + 1 < nchunks) fetch_b(ic + 1);
+            // the chunk-initial state leaves transposed, as it sits in LDS
+            if (STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (!STORE && ic > 0) flush_prev(ic - 1);
+        }
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
             f32x16 ws = zero16();
             mma<DK, false, false, T>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
@@ -280,6 +285,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             mma<DK, false, false, T>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
+        if (STORE && loader && ic > 0) flush_prev(ic - 1);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -361,12 +367,16 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         TileRegs<T, C, BV, NTL> d_o;
         TileRegs<T, C, C, NTL> t;
     } r;
-    auto fetch = [&](int ic) __attribute__((always_inline)) {
+    auto fetch_a = [&](int ic) __attribute__((always_inline)) {
+        const int nvalid = min(C, len - ic * C);
+        const long row0 = (long)t0 + (long)ic * C;
+        r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+    };
+    auto fetch_b = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
-        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
     };
@@ -379,17 +389,13 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
         r.t.store(sT, SM::LT, lt);
     };
-    if (loader && nchunks > 0) { fetch(nchunks - 1); stash(); }
+    if (loader && nchunks > 0) { fetch_a(nchunks - 1); fetch_b(nchunks - 1); stash(); }
     for (int ic = nchunks - 1; ic >= 0; --ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sDUT = (ic & 1) ? sDUT1 : sDUT0;
         if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' (gradient w.r.t. the state after this chunk)
         lds_barrier();
-        if (loader) {
-            if (ic > 0) fetch(ic - 1);
-            copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
-            if (ic + 1 < nchunks) flush_dut(ic + 1);
-        }
+        if (loader && ic > 0) fetch_a(ic - 1);
         f32x16 acc = zero16();
         if (!loader) { // the loader waves are busy with the burst meanwhile
             if (does_p) { // P^T = triu(K Q^T): transposed causal scores, one 32 x 32 tile per wave
@@ -410,6 +416,10 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
             }
         }
         lds_barrier();
+        if (loader) {
+            if (ic > 0) fetch_b(ic - 1);
+            copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
+        }
         if (m.does_u) { // + P^T dO; P^T is upper triangular
             if (m.ua == 0) mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
             else mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LD + 32 * m.ub, SM::LD);
@@ -417,6 +427,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         }
         if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         lds_barrier();
+        if (loader && ic + 1 < nchunks) flush_dut(ic + 1);
         if (m.has_s) { // - W^T dUt
             f32x16 wd = zero16();
             mma<C, true, false, T>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);

@@ -135,27 +135,54 @@ __device__ inline float frag_ks(const float *base, int ld, int k0) {
 }
 __device__ inline void mfma32(f32x16 &acc, bf16x8 a, bf16x8 b) { acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0); }
 __device__ inline void mfma32(f32x16 &acc, float a, float b) { acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0); }
+template <typename T> struct FragOf;
+template <> struct FragOf<bf16> { typedef bf16x8 type; static constexpr int KPL = 8; };
+template <> struct FragOf<float> { typedef float type; static constexpr int KPL = 1; };
 template <typename T> struct KStep;
 template <> struct KStep<bf16> { static constexpr int value = 16; };
 template <> struct KStep<float> { static constexpr int value = 2; };
 
-// acc(32x32) += A * B over KDIM contraction steps; AKS / BKS select the storage order of each operand
-template <int KDIM, bool AKS, bool BKS, typename T>
+// acc(32x32) += A * B over KDIM contraction steps; AKS / BKS select the storage order of each operand.
+// The operand fragments of up to BATCH steps are requested from LDS before the first MFMA of the
+// batch issues (and the next batch's before this batch's MFMAs), so one LDS latency is exposed per
+// product instead of one per pair of steps, which is what the compiler's own schedule gives.
+template <typename T> struct MmaBatch;
+template <> struct MmaBatch<bf16> { static constexpr int value = 8; };   // 8 steps x 2 operands x 4 VGPRs
+template <> struct MmaBatch<float> { static constexpr int value = 16; }; // 16 steps x 2 operands x 1 VGPR
+template <int KDIM, bool AKS, bool BKS, typename T, bool FENCE = true, int BATCH_ = 0>
 __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb) {
-#pragma unroll 8
-    for (int k0 = 0; k0 < KDIM; k0 += KStep<T>::value) {
-        const auto a = AKS ? frag_ks(A, lda, k0) : frag_kc(A, lda, k0);
-        const auto b = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
-        mfma32(acc, a, b);
+    constexpr int KS = KStep<T>::value, N = KDIM / KS;
+    constexpr int WANT = BATCH_ ? BATCH_ : MmaBatch<T>::value;
+    constexpr int BATCH = N < WANT ? N : WANT, NB = (N + BATCH - 1) / BATCH;
+    static_assert(N % BATCH == 0, "contraction length must be a multiple of the batch");
+    typedef typename FragOf<T>::type frag_t;
+    frag_t a[2][BATCH], b[2][BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+        a[0][j] = AKS ? frag_ks(A, lda, j * KS) : frag_kc(A, lda, j * KS);
+        b[0][j] = BKS ? frag_ks(B, ldb, j * KS) : frag_kc(B, ldb, j * KS);
     }
-    __builtin_amdgcn_sched_barrier(0); // keep the scheduler from hoisting the next product's operand loads over this one
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+        if (ib + 1 < NB) {
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const int k0 = ((ib + 1) * BATCH + j) * KS;
+                a[(ib + 1) & 1][j] = AKS ? frag_ks(A, lda, k0) : frag_kc(A, lda, k0);
+                b[(ib + 1) & 1][j] = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) mfma32(acc, a[ib & 1][j], b[ib & 1][j]);
+    }
+    // FENCE keeps the scheduler from hoisting the next product's operand loads over this one (register
+    // pressure); without it the next product's loads may overlap this product's MFMAs.
+    if (FENCE) __builtin_amdgcn_sched_barrier(0);
 }
 
 // A-operand fragments of a 32-row block fetched straight from global memory (row-major, contraction
 // index contiguous) into registers: for operands that exactly one wavefront consumes, this skips LDS.
-template <typename T> struct FragOf;
-template <> struct FragOf<bf16> { typedef bf16x8 type; static constexpr int KPL = 8; };
-template <> struct FragOf<float> { typedef float type; static constexpr int KPL = 1; };
 __device__ inline bf16x8 frag_from_buffer(__amdgpu_buffer_rsrc_t rs, int voff, int soff, bf16 *) {
     return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
 }

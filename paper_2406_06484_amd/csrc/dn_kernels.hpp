@@ -171,6 +171,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     using SM = ScanFwdSmem<T, DK, DV>;
     constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
     using Map = ScanMap<DK, BV>;
+    constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
     extern __shared__ __align__(16) unsigned char smem[];
     T *stg = reinterpret_cast<T *>(smem + SM::oStage) + ((threadIdx.x >> 6) % SM::NSTG) * Stage<T>::ELEMS;
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
@@ -192,9 +193,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     const Map m(wave);
     const bool loader = wave >= 4, does_o = !STORE && m.does_o;
     const int lt = threadIdx.x - NTL; // index among the loader threads
-    // waves 0, 1, 2 build the three non-zero tiles (0,0), (1,0), (1,1) of P
-    const bool does_p = !STORE && wave < 3;
-    const int pmi = wave > 0, pni = wave > 1;
+    // waves 0..3 build the tiles (pmi, pni) = (0,0), (1,0), (1,1), (0,1) of P; the last one is all zero
+    const int pmi = (wave == 1) | (wave == 2), pni = wave >> 1;
 
     f32x16 S = zero16();
     if (m.has_s && p.S0) {
@@ -249,24 +249,31 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader && ic + 1 < nchunks) fetch_a(ic + 1);
         f32x16 acc = zero16();
-        if (!loader) { // what does not depend on the state, while the loader waves are busy with the burst
+        if (!loader) {
+            // What does not depend on the state, while the loader waves are busy with global memory.
+            // Straight-line on purpose (full contraction length even where T's zero block makes half
+            // of it idle, a masked all-zero P tile on wave 3): independent products in one basic
+            // block are what lets the scheduler overlap one product's LDS and MFMA latency with the next.
+            f32x16 w[NWT];
 #pragma unroll
-            for (int t = wave; t < Map::W_TILES; t += 4) { // W = T K (Eq. 11) as W^T = K^T T^T; T is lower triangular
-                const int wk = t % Map::NKT, wi = t / Map::NKT;
-                f32x16 w = zero16();
-                if (wi == 0) mma<32, true, false, T>(w, sK + 32 * wk, SM::LK, sT, SM::LT);
-                else mma<C, true, false, T>(w, sK + 32 * wk, SM::LK, sT + 32 * SM::LT, SM::LT);
-                acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w);
+            for (int i = 0; i < NWT; ++i) { // W = T K (Eq. 11) as W^T = K^T T^T
+                const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
+                w[i] = zero16();
+                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES)
+                    mma<C, true, false, T, false>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
             }
-            if (m.does_u) { // U = T V
-                if (m.ua == 0) mma<32, false, true, T>(acc, sT, SM::LT, sV + 32 * m.ub, SM::LV);
-                else mma<C, false, true, T>(acc, sT + 32 * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV);
+            if (m.does_u) mma<C, false, true, T, false>(acc, sT + 32 * m.ua * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV); // U = T V
+            f32x16 pa = zero16();
+            if (!STORE) // P = tril(Q K^T), the causal intra-chunk scores of Eq. 9, as the tile (pni, pmi) of P^T
+                mma<DK, false, false, T, false>(pa, sK + 32 * pni * SM::LK, SM::LK, sQ + 32 * pmi * SM::LQ, SM::LQ);
+#pragma unroll
+            for (int i = 0; i < NWT; ++i) {
+                const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
+                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
             }
-            if (does_p) { // P = tril(Q K^T): the causal intra-chunk scores of Eq. 9, one 32 x 32 tile per wave
-                f32x16 pa = zero16();
-                mma<DK, false, false, T>(pa, sQ + 32 * pmi * SM::LQ, SM::LQ, sK + 32 * pni * SM::LK, SM::LK);
-                if (pmi == pni) acc_each(pa, [&](int r, int c, float &val) { if (c > r) val = 0.f; });
-                acc_to_lds<T>(sP, SM::LT, 32 * pmi, 32 * pni, pa);
+            if (!STORE) {
+                acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r > 32 * pmi + c) val = 0.f; });
+                acc_to_lds_t<T>(sP, SM::LT, 32 * pni, 32 * pmi, pa);
             }
         }
         lds_barrier();
@@ -331,6 +338,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     using SM = ScanBwdSmem<T, DK, DV>;
     constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
     using Map = ScanMap<DK, BV>;
+    constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
     extern __shared__ __align__(16) unsigned char smem[];
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
@@ -351,9 +359,8 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     const Map m(wave);
     const bool loader = wave >= 4;
     const int lt = threadIdx.x - NTL;
-    // waves 0, 1, 2 build the three non-zero tiles (0,0), (0,1), (1,1) of P^T
-    const bool does_p = wave < 3;
-    const int pmi = wave > 1, pni = wave > 0;
+    // waves 0..3 build the tiles (pmi, pni) = (0,0), (0,1), (1,1), (1,0) of P^T; the last one is all zero
+    const int pmi = wave >> 1, pni = (wave == 1) | (wave == 2);
 
     f32x16 dS = zero16();
     if (m.has_s && p.dST) {
@@ -397,22 +404,25 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader && ic > 0) fetch_a(ic - 1);
         f32x16 acc = zero16();
-        if (!loader) { // the loader waves are busy with the burst meanwhile
-            if (does_p) { // P^T = triu(K Q^T): transposed causal scores, one 32 x 32 tile per wave
-                f32x16 pa = zero16();
-                mma<DK, false, false, T>(pa, sK + 32 * pmi * SM::LK, SM::LK, sQ + 32 * pni * SM::LQ, SM::LQ);
-                if (pmi == pni) acc_each(pa, [&](int r, int c, float &val) { if (c < r) val = 0.f; });
-                acc_to_lds<T>(sPT, SM::LT, 32 * pmi, 32 * pni, pa);
-            }
+        if (!loader) { // straight-line, as in the forward scan; the loader waves are busy with global memory meanwhile
+            f32x16 pa = zero16(); // P^T = triu(K Q^T), the transposed causal scores, computed as the tile (pni, pmi) of P
+            mma<DK, false, false, T, false>(pa, sQ + 32 * pni * SM::LQ, SM::LQ, sK + 32 * pmi * SM::LK, SM::LK);
             if (m.does_u) // K dS' part of the dUt tile (ua, ub)
-                mma<DK, false, false, T>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+                mma<DK, false, false, T, false>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+            f32x16 w[NWT];
 #pragma unroll
-            for (int t = wave; t < Map::W_TILES; t += 4) { // W = T K (Eq. 11), computed as W^T = K^T T^T
-                const int wk = t % Map::NKT, wi = t / Map::NKT;
-                f32x16 w = zero16();
-                if (wi == 0) mma<32, true, false, T>(w, sK + 32 * wk, SM::LK, sT, SM::LT);
-                else mma<C, true, false, T>(w, sK + 32 * wk, SM::LK, sT + 32 * SM::LT, SM::LT);
-                acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w);
+            for (int i = 0; i < NWT; ++i) { // W = T K (Eq. 11), computed as W^T = K^T T^T
+                const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
+                w[i] = zero16();
+                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES)
+                    mma<C, true, false, T, false>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+            }
+            acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r < 32 * pmi + c) val = 0.f; });
+            acc_to_lds_t<T>(sPT, SM::LT, 32 * pni, 32 * pmi, pa);
+#pragma unroll
+            for (int i = 0; i < NWT; ++i) {
+                const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
+                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
             }
         }
         lds_barrier();

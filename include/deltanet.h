@@ -90,6 +90,21 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
                  size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Forward pass in the recurrent (token-serial) form: the delta-rule update and read-out of
+ * section 2.2 applied one token after the other, state in fp32 registers, no chunking, no matrix
+ * cores and no workspace.  It computes the same o and final_state as deltanet_fwd (fp32 arithmetic
+ * on the fp32 or bf16 inputs) and is what a decoder calls with L = 1 per step, handing
+ * final_state back in as initial_state; it is also the baseline the paper's chunkwise form is
+ * timed against (section 3.3).  Same layouts, pointer rules and return codes as deltanet_fwd.
+ * Compiled for d_k in {32, 64, 128, 256} and any d_v that is a multiple of 16, both dtypes
+ * (else DN_ERR_UNSUPPORTED).  `chunk` is not used but must hold a supported value.
+ * initial_state may be NULL (zeros); final_state may be NULL (not written); the two may alias.
+ */
+int deltanet_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v,
+                           const void *beta, const float *initial_state, void *o, float *final_state,
+                           void *hip_stream);
+
+/*
  * Measurement aid (not part of the method): per-kernel device time.  After
  * deltanet_profile_enable(1), every kernel launch of deltanet_fwd / deltanet_bwd is bracketed by a
  * pair of HIP events recorded on the launch stream.  deltanet_profile_collect waits for those

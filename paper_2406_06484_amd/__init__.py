@@ -1,6 +1,6 @@
 """MI355X-native chunkwise-parallel DeltaNet forward/backward (hand-written HIP behind a C ABI).
 
-``deltanet_fwd`` / ``deltanet_bwd`` are thin argument-marshalling bindings over
+``deltanet_fwd`` / ``deltanet_bwd`` / ``deltanet_recurrent_fwd`` are thin argument-marshalling bindings over
 ``libdeltanet_hip.so`` (see ``include/deltanet.h``).  There is no CPU or PyTorch fallback: if the
 library has not been built, calling them raises.
 """
@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     deltanet_bwd,
     deltanet_fwd,
     deltanet_profile_collect,
+    deltanet_recurrent_fwd,
     deltanet_profile_enable,
     deltanet_status_string,
     deltanet_workspace_bytes,

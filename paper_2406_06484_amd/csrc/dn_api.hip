@@ -65,7 +65,7 @@ const Impl *find_impl(const dn_shape *s) {
     return nullptr;
 }
 
-int validate_shape(const dn_shape *s, const Impl **impl) {
+int validate_shape(const dn_shape *s, const Impl **impl, bool need_impl = true) {
     if (!s) return DN_ERR_NULL;
     if (s->B <= 0 || s->L < 0 || s->H <= 0 || s->d_k <= 0 || s->d_v <= 0) return DN_ERR_SHAPE;
     if (s->dtype != DN_F32 && s->dtype != DN_BF16) return DN_ERR_UNSUPPORTED;
@@ -86,6 +86,7 @@ int validate_shape(const dn_shape *s, const Impl **impl) {
     if (rows * s->H >= (1ll << 31) || s->H > 8192) return DN_ERR_SHAPE;
     const long long nseq = s->cu_seqlens ? s->num_seqs : s->B;
     if (nseq > 65535) return DN_ERR_SHAPE;
+    if (!need_impl) return DN_OK;
     *impl = find_impl(s);
     return *impl ? DN_OK : DN_ERR_UNSUPPORTED;
 }
@@ -197,6 +198,24 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     bind_workspace(pl, workspace, &p, &pl.pb, true);
     return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+}
+
+int deltanet_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                           const float *initial_state, void *o, float *final_state, void *hip_stream) {
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl, false)) return rc;
+    if (!q || !k || !v || !beta || !o) return DN_ERR_NULL;
+    const void *al[] = {q, k, v, beta, initial_state, o, final_state, shape->cu_seqlens};
+    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
+    if (shape->d_v % 16 != 0) return DN_ERR_UNSUPPORTED;
+    if (shape->d_k != 32 && shape->d_k != 64 && shape->d_k != 128 && shape->d_k != 256) return DN_ERR_UNSUPPORTED;
+    RecArgs a;
+    a.q = q; a.k = k; a.v = v; a.beta = beta; a.S0 = initial_state; a.o = o; a.ST = final_state;
+    a.cu = shape->cu_seqlens;
+    a.N = shape->cu_seqlens ? shape->num_seqs : shape->B;
+    a.L = shape->L; a.H = shape->H; a.DV = shape->d_v;
+    const int rc = run_recurrent_fwd(shape->dtype == DN_BF16 ? 1 : 0, shape->d_k, a, static_cast<hipStream_t>(hip_stream));
+    return rc == 0 ? DN_OK : (rc < 0 ? DN_ERR_UNSUPPORTED : DN_ERR_LAUNCH);
 }
 
 int deltanet_profile_enable(int on) {

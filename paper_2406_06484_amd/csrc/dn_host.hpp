@@ -37,4 +37,16 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
 // largest dynamic LDS any kernel of this instantiation needs
 template <typename T, int DK, int DV> size_t max_lds_bytes();
 
+// Token-serial forward (dn_recurrent.hip).  dtype: 0 = fp32, 1 = bf16.  Returns 0, a hipError_t
+// (> 0), or -1 when (dtype, d_k) has no compiled kernel.  d_v must be a multiple of 16.
+struct RecArgs {
+    const void *q, *k, *v, *beta;
+    const float *S0;
+    void *o;
+    float *ST;
+    const int32_t *cu; // device cu_seqlens or nullptr
+    int N, L, H, DV;
+};
+int run_recurrent_fwd(int dtype, int d_k, const RecArgs &a, hipStream_t stream);
+
 } // namespace dn

@@ -20,7 +20,8 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(LIB)
     syms = header_symbols()
-    assert {"deltanet_fwd", "deltanet_bwd", "deltanet_workspace_bytes", "deltanet_status_string"} <= set(syms)
+    assert {"deltanet_fwd", "deltanet_bwd", "deltanet_recurrent_fwd", "deltanet_workspace_bytes",
+            "deltanet_status_string"} <= set(syms)
     for s in syms:
         assert hasattr(lib, s), s
 
@@ -68,6 +69,11 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     assert lib.deltanet_fwd(ctypes.byref(s), odd, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -4
     assert lib.deltanet_fwd(ctypes.byref(s), *args, fake, 16, None) == -5
     assert lib.deltanet_fwd(ctypes.byref(s), *args, None, 0, None) == -5
+    rargs = [fake] * 4 + [None, fake, None, None]
+    assert lib.deltanet_recurrent_fwd(ctypes.byref(s), None, fake, fake, fake, None, fake, None, None) == -1
+    assert lib.deltanet_recurrent_fwd(ctypes.byref(s), odd, fake, fake, fake, None, fake, None, None) == -4
+    assert lib.deltanet_recurrent_fwd(ctypes.byref(_shape(d_k=96)), *rargs) == -3
+    assert lib.deltanet_recurrent_fwd(ctypes.byref(_shape(d_v=72)), *rargs) == -3
     bargs = [fake] * 4 + [None, fake, None, fake, fake, fake, fake, None]
     assert lib.deltanet_bwd(ctypes.byref(s), *bargs, fake, 16, None) == -5
     bargs[10] = None  # dbeta is required

@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # published fp32 vector rate (counts packed FMA; plain FMA code reaches half)
 C = 64
 
 
@@ -193,6 +194,23 @@ def main() -> int:
         "kernels": kernels,
         "roofline": roofline,
     }
+
+    # The same forward in the recurrent (token-serial) form, the baseline the paper times the chunkwise
+    # form against; vector-ALU bound: 3 fused multiply-adds per state element per token.
+    rec_steps = max(1, min(args.steps, 10))
+    for _ in range(2):
+        dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(rec_steps):
+        dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST)
+    torch.cuda.synchronize()
+    rec_ms = 1e3 * (time.perf_counter() - t0) / rec_steps
+    rec_tflops = 6.0 * d * d * H * tokens / (rec_ms * 1e-3) / 1e12
+    out["recurrent_fwd"] = {"ms": round(rec_ms, 4), "tokens_per_s": round(tokens / (rec_ms * 1e-3), 1), "steps": rec_steps,
+                            "chunkwise_fwd_ms": round(fw, 4), "chunkwise_speedup": round(rec_ms / fw, 2),
+                            "roofline": {"bound": "alu", "achieved": round(rec_tflops, 2), "peak": PEAK_FP32_VECTOR_TFLOPS,
+                                         "unit": "TFLOP/s", "frac": round(rec_tflops / PEAK_FP32_VECTOR_TFLOPS, 4), "traffic": None}}
 
     if not args.no_cpu_baseline:
         import oracle

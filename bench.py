@@ -69,10 +69,11 @@ def kernel_bytes_per_chunk_head(name: str, d: int, c: int = C, es: int = 2) -> f
 # summary and commands in profiles/hbm_traffic_cfg2_fwd_bwd.txt.  The counters cannot be read from
 # inside this script, so the figures are carried here and refreshed whenever the kernels change.
 MEASURED_HBM_BYTES = {
-    "k_wy_prep": 212.2e6,
-    "k_scan_fwd": 344.1e6,
-    "k_scan_pair": 844.9e6,
-    "k_bwd_chunk": 919.1e6,
+    "k_wy_prep": 118.3e6,
+    "k_scan_fwd": 310.5e6,
+    "k_scan_pair": 821.0e6,
+    "k_bwd_chunk": 919.2e6,
+    "k_recurrent_fwd": 281.2e6,
 }
 
 
@@ -210,7 +211,8 @@ def main() -> int:
     out["recurrent_fwd"] = {"ms": round(rec_ms, 4), "tokens_per_s": round(tokens / (rec_ms * 1e-3), 1), "steps": rec_steps,
                             "chunkwise_fwd_ms": round(fw, 4), "chunkwise_speedup": round(rec_ms / fw, 2),
                             "roofline": {"bound": "alu", "achieved": round(rec_tflops, 2), "peak": PEAK_FP32_VECTOR_TFLOPS,
-                                         "unit": "TFLOP/s", "frac": round(rec_tflops / PEAK_FP32_VECTOR_TFLOPS, 4), "traffic": None}}
+                                         "unit": "TFLOP/s", "frac": round(rec_tflops / PEAK_FP32_VECTOR_TFLOPS, 4),
+                                         "traffic": measured_traffic("k_recurrent_fwd")}}
 
     if not args.no_cpu_baseline:
         import oracle

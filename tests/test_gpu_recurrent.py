@@ -85,3 +85,9 @@ def test_recurrent_rejects_unsupported_head_sizes():
     with pytest.raises(dn.DeltaNetError) as e:
         dn.deltanet_recurrent_fwd(d["q"], d["k"], d["v"], d["beta"])
     assert e.value.status == -3
+
+
+def test_recurrent_full_size_configs():
+    # the benchmark shape and the packed variable-length batch, every element against the oracle
+    check(make_config(1), "recurrent cfg1")
+    check(make_config(4), "recurrent cfg4")

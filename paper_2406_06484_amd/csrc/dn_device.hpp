@@ -1,6 +1,6 @@
 // Device-side building blocks for the gfx950 DeltaNet kernels: MFMA tile products from LDS,
 // accumulator <-> LDS/global movers, tile loaders, the 64x64 unit-lower-triangular inverse.
-// Every kernel here runs with 256 threads (4 wavefronts of 64) and a chunk of C = 64 tokens.
+// The chunk is C = 64 tokens; the prep kernel runs 4 wavefronts, the scans and the chunk kernel 8.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -74,32 +74,10 @@ struct SeqMap {
 };
 
 // ---------------------------------------------------------------------------------------------
-// acc(32x32) += A(32 x KDIM) * B(32 x KDIM)^T, both operands in LDS with the contraction index
-// contiguous.  v_mfma_f32_32x32x16_bf16: lane l feeds row/col (l & 31) and 8 consecutive k starting
-// at 8*(l >> 5); v_mfma_f32_32x32x2_f32: one k = (l >> 5).  The accumulator holds, for lane l,
-// column (l & 31) and rows 8*g + 4*(l >> 5) + i at index 4*g + i.
-template <int KDIM>
-__device__ inline void mma_nt(f32x16 &acc, const bf16 *A, int lda, const bf16 *B, int ldb) {
-    const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
-    const bf16 *pa = A + r * lda + h * 8;
-    const bf16 *pb = B + r * ldb + h * 8;
-#pragma unroll
-    for (int k0 = 0; k0 < KDIM; k0 += 16) {
-        bf16x8 a = *reinterpret_cast<const bf16x8 *>(pa + k0);
-        bf16x8 b = *reinterpret_cast<const bf16x8 *>(pb + k0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
-    }
-}
-template <int KDIM>
-__device__ inline void mma_nt(f32x16 &acc, const float *A, int lda, const float *B, int ldb) {
-    const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
-    const float *pa = A + r * lda + h;
-    const float *pb = B + r * ldb + h;
-#pragma unroll 8
-    for (int k0 = 0; k0 < KDIM; k0 += 2)
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k0], pb[k0], acc, 0, 0, 0);
-}
-
+// The 32x32 MFMAs.  v_mfma_f32_32x32x16_bf16: lane l feeds row/col (l & 31) and 8 consecutive k
+// starting at 8*(l >> 5); v_mfma_f32_32x32x2_f32: one k = (l >> 5).  The accumulator holds, for
+// lane l, column (l & 31) and rows 8*g + 4*(l >> 5) + i at index 4*g + i.
+//
 // Operand fragments for the 32x32 MFMAs, from LDS, in two storage orders:
 //   KC  storage [n][k], contraction index contiguous  (one 16-byte read per lane in bf16)
 //   KS  storage [k][n], contraction index strided     (bf16: two ds_read_b64_tr_b16, the CDNA4
@@ -181,37 +159,6 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
     if (FENCE) __builtin_amdgcn_sched_barrier(0);
 }
 
-// A-operand fragments of a 32-row block fetched straight from global memory (row-major, contraction
-// index contiguous) into registers: for operands that exactly one wavefront consumes, this skips LDS.
-__device__ inline bf16x8 frag_from_buffer(__amdgpu_buffer_rsrc_t rs, int voff, int soff, bf16 *) {
-    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
-}
-__device__ inline float frag_from_buffer(__amdgpu_buffer_rsrc_t rs, int voff, int soff, float *) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, 0));
-}
-template <typename T, int KDIM> struct AFrags {
-    static constexpr int N = KDIM / KStep<T>::value;
-    typename FragOf<T>::type f[N];
-    // base: row 0 of the block, k = 0; rows >= nvalid read as zero
-    __device__ inline void load(const T *base, long ld, int nvalid) {
-        const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
-        const __amdgpu_buffer_rsrc_t rs = make_rsrc(base);
-        const int voff = r < nvalid ? (r * (int)ld + h * FragOf<T>::KPL) * (int)sizeof(T) : kBufRange;
-#pragma unroll
-        for (int s = 0; s < N; ++s) f[s] = frag_from_buffer(rs, voff, s * KStep<T>::value * (int)sizeof(T), (T *)nullptr);
-    }
-};
-// acc += A(registers) * B(LDS) over the contraction range [KBEG, KEND)
-template <int KBEG, int KEND, bool BKS, typename T, int KDIM>
-__device__ inline void mma_ra(f32x16 &acc, const AFrags<T, KDIM> &a, const T *B, int ldb) {
-#pragma unroll
-    for (int k0 = KBEG; k0 < KEND; k0 += KStep<T>::value) {
-        const auto b = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
-        mfma32(acc, a.f[k0 / KStep<T>::value], b);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-}
-
 __device__ inline f32x16 zero16() {
     f32x16 z;
 #pragma unroll
@@ -255,14 +202,6 @@ template <typename T> __device__ inline void acc_to_lds_t(T *dstT, int ldT, int 
         st4(dstT + (col0 + c) * ldT + row0 + r, a, b, cc, d);
     });
 }
-// tile -> global, rows >= nvalid dropped; dst points at (row 0, col 0) of the C-row block
-template <typename T>
-__device__ inline void acc_to_global(T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc) {
-    acc_each(acc, [&](int r, int c, float &v) {
-        if (row0 + r < nvalid) dst[(long)(row0 + r) * row_stride + col0 + c] = from_f32<T>(v);
-    });
-}
-
 // Wave-private LDS staging for coalesced tile stores.  A 32 x 32 accumulator tile is first laid
 // out row-major in LDS (cheap narrow LDS writes), then each lane moves 16 bytes at a time to global
 // memory, so a store instruction covers whole 64-byte (bf16) or 128-byte (fp32) row segments.
@@ -293,21 +232,6 @@ __device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, in
     acc_to_lds<T>(stage, Stage<T>::LD, 0, 0, acc);
     stage_flush<T>(stage, dst, row_stride, row0, col0, nvalid);
 }
-// dst[col0 + c][row0 + r] = acc(r, c)  (transposed tile), no masking
-template <typename T>
-__device__ inline void acc_store_t(T *stage, T *dst, long row_stride, int row0, int col0, const f32x16 &acc) {
-    acc_to_lds_t<T>(stage, Stage<T>::LD, 0, 0, acc);
-    stage_flush<T>(stage, dst, row_stride, col0, row0, 1 << 30);
-}
-
-// tile -> global, transposed: dst[col][row], 4 consecutive rows per store (no row masking)
-template <typename T>
-__device__ inline void acc_to_global_t(T *dst, long ld, int row0, int col0, const f32x16 &acc) {
-    acc_each4(acc, [&](int r, int c, float a, float b, float cc, float d) {
-        st4(dst + (long)(col0 + c) * ld + row0 + r, a, b, cc, d);
-    });
-}
-
 // ---------------------------------------------------------------------------------------------
 // A ROWS x COLS tile fetched from global memory into registers (16 bytes per lane and step; rows >=
 // nvalid read as zero), to be parked while LDS is busy and stored to LDS later.
@@ -341,18 +265,6 @@ __device__ inline void load_tile(T *dst, int ld, const T *src, long row_stride, 
     regs.load(src, row_stride, nvalid);
     regs.store(dst, ld);
 }
-// LDS -> global, ROWS x COLS, rows >= nvalid dropped
-template <typename T, int ROWS, int COLS>
-__device__ inline void store_tile(T *dst, long row_stride, const T *src, int ld, int nvalid) {
-    constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NTHR / TPR;
-    const int tr = threadIdx.x / TPR, tc = (threadIdx.x % TPR) * VEC;
-#pragma unroll
-    for (int r0 = 0; r0 < ROWS; r0 += RPI) {
-        const int r = r0 + tr;
-        if (r < nvalid)
-            *reinterpret_cast<uint4 *>(dst + (long)r * row_stride + tc) = *reinterpret_cast<const uint4 *>(src + r * ld + tc);
-    }
-}
 // LDS -> global copy of a ROWS x COLS tile by NT cooperating threads (t = index among them); the
 // destination is a contiguous row-major block
 template <typename T, int ROWS, int COLS, int NT>
@@ -364,67 +276,10 @@ __device__ inline void copy_out(T *dst, const T *src, int ld, int t) {
     for (int r0 = 0; r0 < ROWS; r0 += RPI)
         *reinterpret_cast<uint4 *>(dst + (long)(r0 + tr) * COLS + tc) = *reinterpret_cast<const uint4 *>(src + (r0 + tr) * ld + tc);
 }
-// LDS -> LDS transpose of a C x COLS tile: dstT[c][r] = src[r][c].  Lanes run along r so that the
-// narrow stores of one instruction fall into consecutive addresses.
-template <typename T, int COLS>
-__device__ inline void transpose_tile(T *dstT, int ldT, const T *src, int ld) {
-    constexpr int VEC = El<T>::VEC, NG = COLS / VEC;
-    const int r = threadIdx.x & 63, g0 = threadIdx.x >> 6;
-#pragma unroll
-    for (int g = g0; g < NG; g += NWAVE) {
-        alignas(16) T tmp[VEC];
-        *reinterpret_cast<uint4 *>(tmp) = *reinterpret_cast<const uint4 *>(src + r * ld + g * VEC);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) dstT[(g * VEC + i) * ldT + r] = tmp[i];
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
-// X = (I + A)^{-1} for a 64x64 strictly-lower-triangular A (fp32, LDS, leading dimension ld).
-// Forward substitution (section 3.2, "inverse of lower triangular matrices ... forward
-// substitution") done blockwise: the four 16x16 diagonal blocks column by column inside one
-// wavefront each, then block row a = 1..3 from X_ab = -X_aa * sum_{c=b}^{a-1} A_ac X_cb.
-// sM is scratch of 16 x ldm floats, ldm >= 48.  Ends with a barrier; sX holds the full matrix.
-__device__ inline void tri_inverse_64(const float *sA, float *sX, float *sM, int ld, int ldm) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    for (int e = tid; e < C * C; e += NTHR) sX[(e >> 6) * ld + (e & 63)] = 0.f;
-    lds_barrier();
-    if (lane < 16) {
-        const int b = wave * 16, j = lane;
-        float x[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float s = (i == j) ? 1.f : 0.f;
-#pragma unroll
-            for (int m = 0; m < i; ++m) s -= sA[(b + i) * ld + b + m] * x[m];
-            x[i] = (i < j) ? 0.f : s;
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sX[(b + i) * ld + b + j] = x[i];
-    }
-    lds_barrier();
-    const int i = tid >> 4, j = tid & 15;
-    for (int a = 1; a < 4; ++a) {
-        for (int b = 0; b < a; ++b) {
-            float s = 0.f;
-            for (int c = b; c < a; ++c)
-#pragma unroll
-                for (int m = 0; m < 16; ++m) s += sA[(16 * a + i) * ld + 16 * c + m] * sX[(16 * c + m) * ld + 16 * b + j];
-            sM[i * ldm + 16 * b + j] = s;
-        }
-        lds_barrier();
-        for (int b = 0; b < a; ++b) {
-            float s = 0.f;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) s += sX[(16 * a + i) * ld + 16 * a + m] * sM[m * ldm + 16 * b + j];
-            sX[(16 * a + i) * ld + 16 * b + j] = -s;
-        }
-        lds_barrier();
-    }
-}
-
-
-// In-place variant used by the fast kernels.  On entry sX (fp32, leading dimension ld) holds the
+// X = (I + A)^{-1} for a 64x64 strictly-lower-triangular A (section 3.2: the inverse of the unit
+// lower-triangular matrix of Eq. 10 by forward substitution), done blockwise and in place.
+// On entry sX (fp32, leading dimension ld) holds the
 // strictly lower triangular A with zeros elsewhere; on exit it holds X = (I + A)^{-1}.
 // Blocked forward substitution: the eight 8x8 diagonal blocks are solved column by column (16
 // lanes of every wavefront), then 2x2 block merges X21 = -X22 (A21 X11) double the block size

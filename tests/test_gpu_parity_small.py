@@ -104,3 +104,25 @@ def test_results_are_deterministic_and_ignore_workspace_contents():
         outs.append([t.clone() for t in g])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_many_tiny_packed_sequences():
+    # thousands of sequences of 0..3 tokens: every chain is one ragged chunk, the chunk-offset prefix and
+    # the chunk -> sequence search see their extreme shape
+    rng = np.random.default_rng(5)
+    lens = rng.integers(0, 4, size=6000)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    inp = make_inputs(21, H=2, dk=64, dv=64, dtype="f32", cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)
+    check_fwd_bwd(inp, label="6000 tiny sequences")
+
+
+def test_many_heads_and_the_sequence_count_limit():
+    inp = make_inputs(22, B=1, L=70, H=300, dk=64, dv=64, dtype="bf16", with_dfinal_state=True)
+    check_fwd_bwd(inp, label="H=300")
+    # more sequences than the grid mapping supports is refused before any launch
+    q = torch.zeros((4, 1, 64), dtype=torch.float32, device="cuda")
+    cu = torch.zeros(65537 + 1, dtype=torch.int32, device="cuda")
+    cu[-1] = 4
+    with pytest.raises(dn.DeltaNetError) as e:
+        dn.deltanet_fwd(q, q, q, q[..., 0].contiguous(), cu_seqlens=cu)
+    assert e.value.status == -2

@@ -41,6 +41,10 @@ def _load():
         lib.dn_oracle_fwd.argtypes = [ctypes.c_int, ip] + [ctypes.c_int] * 3 + [dp] * 7 + [ctypes.c_int]
         lib.dn_oracle_bwd.restype = ctypes.c_int
         lib.dn_oracle_bwd.argtypes = [ctypes.c_int, ip] + [ctypes.c_int] * 3 + [dp] * 12 + [ctypes.c_int]
+        lib.dn_oracle_gated_fwd.restype = ctypes.c_int
+        lib.dn_oracle_gated_fwd.argtypes = [ctypes.c_int, ip] + [ctypes.c_int] * 3 + [dp] * 8 + [ctypes.c_int]
+        lib.dn_oracle_gated_bwd.restype = ctypes.c_int
+        lib.dn_oracle_gated_bwd.argtypes = [ctypes.c_int, ip] + [ctypes.c_int] * 3 + [dp] * 14 + [ctypes.c_int]
         lib.dn_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -120,3 +124,52 @@ def bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, cu_seqlens=No
         dq = dq.reshape(shape + (H, dk)); dkk = dkk.reshape(shape + (H, dk))
         dvv = dvv.reshape(shape + (H, dv)); db = db.reshape(shape + (H,))
     return dq, dkk, dvv, db, dS0
+
+
+def _gate(g, shape, T, H):
+    g = _f64(g)
+    return g.reshape(T, H)
+
+
+def gated_fwd(q, k, v, beta, g, initial_state=None, cu_seqlens=None, nthreads: int = 0):
+    """(o, final_state) of the gated recurrence S_t = exp(g_t) S_{t-1} (I - beta k k^T) + beta k v^T (listing orientation)."""
+    lib = _load()
+    q, k, v, beta, cu, shape, (T, H, dk, dv) = _pack(q, k, v, beta, cu_seqlens)
+    g = _gate(g, shape, T, H)
+    N = len(cu) - 1
+    S0 = _f64(initial_state)
+    if S0 is not None:
+        assert S0.shape == (N, H, dk, dv)
+    o = np.empty((T, H, dv), dtype=np.float64)
+    ST = np.empty((N, H, dk, dv), dtype=np.float64)
+    rc = lib.dn_oracle_gated_fwd(N, cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), H, dk, dv,
+                                 _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(g), _ptr(S0), _ptr(o), _ptr(ST), nthreads)
+    if rc != 0:
+        raise RuntimeError("dn_oracle_gated_fwd failed with %d" % rc)
+    if shape is not None:
+        o = o.reshape(shape + (H, dv))
+    return o, ST
+
+
+def gated_bwd(q, k, v, beta, g, d_o, initial_state=None, dfinal_state=None, cu_seqlens=None, nthreads: int = 0):
+    """(dq, dk, dv, dbeta, dg, dinitial_state) of the gated recurrence."""
+    lib = _load()
+    q, k, v, beta, cu, shape, (T, H, dk, dv) = _pack(q, k, v, beta, cu_seqlens)
+    g = _gate(g, shape, T, H)
+    N = len(cu) - 1
+    d_o = _f64(d_o).reshape(T, H, dv)
+    S0, dST = _f64(initial_state), _f64(dfinal_state)
+    for s in (S0, dST):
+        if s is not None:
+            assert s.shape == (N, H, dk, dv)
+    dq = np.empty((T, H, dk)); dkk = np.empty((T, H, dk)); dvv = np.empty((T, H, dv))
+    db = np.empty((T, H)); dg = np.empty((T, H)); dS0 = np.empty((N, H, dk, dv))
+    rc = lib.dn_oracle_gated_bwd(N, cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), H, dk, dv,
+                                 _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(g), _ptr(S0), _ptr(d_o), _ptr(dST),
+                                 _ptr(dq), _ptr(dkk), _ptr(dvv), _ptr(db), _ptr(dg), _ptr(dS0), nthreads)
+    if rc != 0:
+        raise RuntimeError("dn_oracle_gated_bwd failed with %d" % rc)
+    if shape is not None:
+        dq = dq.reshape(shape + (H, dk)); dkk = dkk.reshape(shape + (H, dk))
+        dvv = dvv.reshape(shape + (H, dv)); db = db.reshape(shape + (H,)); dg = dg.reshape(shape + (H,))
+    return dq, dkk, dvv, db, dg, dS0

@@ -105,6 +105,34 @@ int deltanet_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, 
                            void *hip_stream);
 
 /*
+ * Gated variant: the last row of the paper's overview table of linear recurrent models (section 6),
+ * which its limitations section names as the way to add the decay DeltaNet lacks.  A scalar decay
+ * alpha_t = exp(g_t) per token and head multiplies the transition,
+ *
+ *     S_t = alpha_t (S_{t-1} - beta_t k_t (S_{t-1}^T k_t)^T) + beta_t k_t v_t^T ,   o_t = S_t^T q_t
+ *
+ * (state orientation as above; g = 0 is the plain delta rule).  g is fp32 [B,L,H] (packed: [L,H]),
+ * g <= 0 expected; inside one chunk of 64 tokens the sum of |g| must stay below about 80, as the
+ * kernels work with exp(-sum g) in fp32.  Evaluated chunkwise like deltanet_fwd / deltanet_bwd: with
+ * gamma_i the running product of alpha inside a chunk, S_i / gamma_i follows the plain delta rule on
+ * the values v_i / gamma_i, so Eq. 8-11 apply unchanged to rescaled rows.  deltanet_gated_bwd also
+ * returns dg (fp32, shape of g).  Workspace sizes come from deltanet_gated_workspace_bytes; everything
+ * else (layouts, nullable states, return codes) is as for the plain calls.
+ * deltanet_gated_recurrent_fwd is the token-serial form (decode steps), as deltanet_recurrent_fwd.
+ */
+int deltanet_gated_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes);
+int deltanet_gated_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                       const float *g, const float *initial_state, void *o, float *final_state, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+int deltanet_gated_bwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                       const float *g, const float *initial_state, const void *d_o, const float *dfinal_state,
+                       void *dq, void *dk, void *dv, float *dbeta, float *dg, float *dinitial_state, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+int deltanet_gated_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v,
+                                 const void *beta, const float *g, const float *initial_state, void *o,
+                                 float *final_state, void *hip_stream);
+
+/*
  * Measurement aid (not part of the method): per-kernel device time.  After
  * deltanet_profile_enable(1), every kernel launch of deltanet_fwd / deltanet_bwd is bracketed by a
  * pair of HIP events recorded on the launch stream.  deltanet_profile_collect waits for those

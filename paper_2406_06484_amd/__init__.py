@@ -8,6 +8,10 @@ from .binding import (  # noqa: F401
     DeltaNetError,
     deltanet_bwd,
     deltanet_fwd,
+    deltanet_gated_bwd,
+    deltanet_gated_fwd,
+    deltanet_gated_recurrent_fwd,
+    deltanet_gated_workspace_bytes,
     deltanet_profile_collect,
     deltanet_recurrent_fwd,
     deltanet_profile_enable,

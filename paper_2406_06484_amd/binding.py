@@ -58,6 +58,14 @@ def load_library():
         lib.deltanet_bwd.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
         lib.deltanet_recurrent_fwd.restype = ctypes.c_int
         lib.deltanet_recurrent_fwd.argtypes = [sp] + [vp] * 7 + [vp]
+        lib.deltanet_gated_workspace_bytes.restype = ctypes.c_int
+        lib.deltanet_gated_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(sz)]
+        lib.deltanet_gated_fwd.restype = ctypes.c_int
+        lib.deltanet_gated_fwd.argtypes = [sp] + [vp] * 8 + [vp, sz, vp]
+        lib.deltanet_gated_bwd.restype = ctypes.c_int
+        lib.deltanet_gated_bwd.argtypes = [sp] + [vp] * 14 + [vp, sz, vp]
+        lib.deltanet_gated_recurrent_fwd.restype = ctypes.c_int
+        lib.deltanet_gated_recurrent_fwd.argtypes = [sp] + [vp] * 8 + [vp]
         lib.deltanet_profile_enable.restype = ctypes.c_int
         lib.deltanet_profile_enable.argtypes = [ctypes.c_int]
         lib.deltanet_profile_collect.restype = ctypes.c_int
@@ -150,9 +158,15 @@ def deltanet_workspace_bytes(shape: dn_shape, want_bwd: bool) -> int:
     return int(out.value)
 
 
-def _workspace(shape, want_bwd, workspace, device):
+def deltanet_gated_workspace_bytes(shape: dn_shape, want_bwd: bool) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().deltanet_gated_workspace_bytes(ctypes.byref(shape), int(bool(want_bwd)), ctypes.byref(out)))
+    return int(out.value)
+
+
+def _workspace(shape, want_bwd, workspace, device, gated=False):
     import torch
-    need = deltanet_workspace_bytes(shape, want_bwd)
+    need = (deltanet_gated_workspace_bytes if gated else deltanet_workspace_bytes)(shape, want_bwd)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
     return workspace, workspace.numel() * workspace.element_size()
@@ -160,11 +174,13 @@ def _workspace(shape, want_bwd, workspace, device):
 
 def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: int = 64,
                  output_final_state: bool = True, o=None, final_state=None, workspace=None,
-                 stream=None) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
+                 stream=None, _g=None) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
     """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None)."""
     import torch
     lib = load_library()
     keep = []
+    if _g is not None:
+        _req(_g, "g", torch.float32, beta.shape)
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta")):
         _req(t, n, q.dtype)
     s = _shape_of(q, v, cu_seqlens, chunk, keep)
@@ -181,14 +197,23 @@ def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: i
         final_state = torch.empty(st_shape, dtype=torch.float32, device=q.device)
     if final_state is not None:
         _req(final_state, "final_state", torch.float32, st_shape)
-    workspace, wbytes = _workspace(s, False, workspace, q.device)
-    _check(lib.deltanet_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
-                            _p(final_state), _p(workspace), wbytes, _stream(stream)))
+    workspace, wbytes = _workspace(s, False, workspace, q.device, _g is not None)
+    if _g is None:
+        _check(lib.deltanet_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
+                                _p(final_state), _p(workspace), wbytes, _stream(stream)))
+    else:
+        _check(lib.deltanet_gated_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(initial_state), _p(o),
+                                      _p(final_state), _p(workspace), wbytes, _stream(stream)))
     return o, final_state
 
 
+def deltanet_gated_fwd(q, k, v, beta, g, initial_state=None, **kw):
+    """Forward pass of the gated variant (decay exp(g) per token and head, g fp32); returns (o, final_state or None)."""
+    return deltanet_fwd(q, k, v, beta, initial_state, _g=g, **kw)
+
+
 def deltanet_recurrent_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, output_final_state: bool = True,
-                           o=None, final_state=None, stream=None):
+                           o=None, final_state=None, stream=None, _g=None):
     """Token-serial forward on the GPU (decode steps, and the baseline of the chunkwise form); returns (o, final_state or None)."""
     import torch
     lib = load_library()
@@ -209,17 +234,29 @@ def deltanet_recurrent_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None
         final_state = torch.empty(st_shape, dtype=torch.float32, device=q.device)
     if final_state is not None:
         _req(final_state, "final_state", torch.float32, st_shape)
-    _check(lib.deltanet_recurrent_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
-                                      _p(final_state), _stream(stream)))
+    if _g is None:
+        _check(lib.deltanet_recurrent_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
+                                          _p(final_state), _stream(stream)))
+    else:
+        _req(_g, "g", torch.float32, beta.shape)
+        _check(lib.deltanet_gated_recurrent_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(initial_state),
+                                                _p(o), _p(final_state), _stream(stream)))
     return o, final_state
 
 
+def deltanet_gated_recurrent_fwd(q, k, v, beta, g, initial_state=None, **kw):
+    """Token-serial forward of the gated variant; returns (o, final_state or None)."""
+    return deltanet_recurrent_fwd(q, k, v, beta, initial_state, _g=g, **kw)
+
+
 def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None,
-                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None):
+                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, _g=None):
     """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None)."""
     import torch
     lib = load_library()
     keep = []
+    if _g is not None:
+        _req(_g, "g", torch.float32, beta.shape)
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta"), (d_o, "d_o")):
         _req(t, n, q.dtype)
     s = _shape_of(q, v, cu_seqlens, chunk, keep)
@@ -233,8 +270,19 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     dbeta = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
     dS0 = torch.empty(st_shape, dtype=torch.float32, device=q.device) if want_dinitial_state else None
-    workspace, wbytes = _workspace(s, True, workspace, q.device)
-    _check(lib.deltanet_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(d_o),
-                            _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace),
-                            wbytes, _stream(stream)))
-    return dq, dk, dv, dbeta, dS0
+    workspace, wbytes = _workspace(s, True, workspace, q.device, _g is not None)
+    if _g is None:
+        _check(lib.deltanet_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(d_o),
+                                _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace),
+                                wbytes, _stream(stream)))
+        return dq, dk, dv, dbeta, dS0
+    dg = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
+    _check(lib.deltanet_gated_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(initial_state), _p(d_o),
+                                  _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dg), _p(dS0), _p(workspace),
+                                  wbytes, _stream(stream)))
+    return dq, dk, dv, dbeta, dg, dS0
+
+
+def deltanet_gated_bwd(q, k, v, beta, g, d_o, initial_state=None, dfinal_state=None, **kw):
+    """Backward pass of the gated variant; returns (dq, dk, dv, dbeta, dg, dinitial_state or None), dbeta and dg in fp32."""
+    return deltanet_bwd(q, k, v, beta, d_o, initial_state, dfinal_state, _g=g, **kw)

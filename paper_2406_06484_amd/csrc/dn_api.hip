@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_P, off_X, off_Ut, off_dUt, off_Sc, off_dSc, total;
+    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_zc, total;
     size_t esz;
 };
 
@@ -91,7 +91,7 @@ int validate_shape(const dn_shape *s, const Impl **impl, bool need_impl = true) 
     return *impl ? DN_OK : DN_ERR_UNSUPPORTED;
 }
 
-void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
+void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false) {
     memset(pl, 0, sizeof(*pl));
     Problem &pb = pl->pb;
     const bool packed = s->cu_seqlens != nullptr;
@@ -117,12 +117,16 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl) {
         pl->off_Sc = o; o += tS;
         pl->off_dSc = o; o += tS;
     }
+    if (gated) {
+        pl->off_gam = o; o += up256(tiles * 2 * kChunk * sizeof(float)); // gamma_i and 1 / gamma_i per chunk row
+        if (want_bwd) { pl->off_zc = o; o += up256(tiles * sizeof(float)); } // <dS_C, S_C> per chunk
+    }
     pl->total = o;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
-void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd) {
+void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd, bool gated = false) {
     unsigned char *b = static_cast<unsigned char *>(ws);
     pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
     p->Tm = b + pl.off_T;
@@ -131,6 +135,10 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
         p->Xm = b + pl.off_X;
         p->Ut = b + pl.off_Ut; p->dUt = b + pl.off_dUt; p->Sc = b + pl.off_Sc;
         p->dSc = b + pl.off_dSc;
+    }
+    if (gated) {
+        p->gam = reinterpret_cast<float *>(b + pl.off_gam);
+        if (want_bwd) p->zc = reinterpret_cast<float *>(b + pl.off_zc);
     }
 }
 
@@ -141,6 +149,49 @@ int check_device(const Impl *impl, Problem *pb) {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return DN_ERR_LAUNCH;
     pb->num_cus = cus;
     return (size_t)lds >= impl->lds() ? DN_OK : DN_ERR_UNSUPPORTED;
+}
+
+int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
+             bool gated, const float *initial_state, void *o, float *final_state, void *workspace,
+             size_t workspace_bytes, void *hip_stream) {
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    if (!q || !k || !v || !beta || !o || (gated && !g)) return DN_ERR_NULL;
+    const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, workspace, shape->cu_seqlens};
+    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
+    Plan pl;
+    make_plan(shape, 0, &pl, gated);
+    if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
+    if (int rc = check_device(impl, &pl.pb)) return rc;
+    Ptrs p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.k = k; p.v = v; p.beta = beta; p.g = gated ? g : nullptr; p.S0 = initial_state; p.o = o; p.ST = final_state;
+    pl.pb.stream = static_cast<hipStream_t>(hip_stream);
+    bind_workspace(pl, workspace, &p, &pl.pb, false, gated);
+    return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+}
+
+int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
+             bool gated, const float *initial_state, const void *d_o, const float *dfinal_state, void *dq, void *dk,
+             void *dv, float *dbeta, float *dg, float *dinitial_state, void *workspace, size_t workspace_bytes,
+             void *hip_stream) {
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    if (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta || (gated && (!g || !dg))) return DN_ERR_NULL;
+    const void *al[] = {q, k, v, beta, g, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
+                        workspace, shape->cu_seqlens};
+    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
+    Plan pl;
+    make_plan(shape, 1, &pl, gated);
+    if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
+    if (int rc = check_device(impl, &pl.pb)) return rc;
+    Ptrs p;
+    memset(&p, 0, sizeof(p));
+    p.q = q; p.k = k; p.v = v; p.beta = beta; p.g = gated ? g : nullptr; p.S0 = initial_state; p.d_o = d_o; p.dST = dfinal_state;
+    p.dq = dq; p.dk = dk; p.dv = dv; p.dbeta = dbeta; p.dg = gated ? dg : nullptr; p.dS0 = dinitial_state;
+    pl.pb.stream = static_cast<hipStream_t>(hip_stream);
+    bind_workspace(pl, workspace, &p, &pl.pb, true, gated);
+    return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
 
 } // namespace
@@ -160,62 +211,70 @@ int deltanet_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_by
 int deltanet_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
                  const float *initial_state, void *o, float *final_state, void *workspace,
                  size_t workspace_bytes, void *hip_stream) {
-    const Impl *impl = nullptr;
-    if (int rc = validate_shape(shape, &impl)) return rc;
-    if (!q || !k || !v || !beta || !o) return DN_ERR_NULL;
-    const void *al[] = {q, k, v, beta, initial_state, o, final_state, workspace, shape->cu_seqlens};
-    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
-    Plan pl;
-    make_plan(shape, 0, &pl);
-    if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
-    if (int rc = check_device(impl, &pl.pb)) return rc;
-    Ptrs p;
-    memset(&p, 0, sizeof(p));
-    p.q = q; p.k = k; p.v = v; p.beta = beta; p.S0 = initial_state; p.o = o; p.ST = final_state;
-    pl.pb.stream = static_cast<hipStream_t>(hip_stream);
-    bind_workspace(pl, workspace, &p, &pl.pb, false);
-    return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+    return fwd_impl(shape, q, k, v, beta, nullptr, false, initial_state, o, final_state, workspace, workspace_bytes, hip_stream);
 }
 
 int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
                  const float *initial_state, const void *d_o, const float *dfinal_state, void *dq,
                  void *dk, void *dv, float *dbeta, float *dinitial_state, void *workspace,
                  size_t workspace_bytes, void *hip_stream) {
-    const Impl *impl = nullptr;
-    if (int rc = validate_shape(shape, &impl)) return rc;
-    if (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta) return DN_ERR_NULL;
-    const void *al[] = {q, k, v, beta, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dinitial_state,
-                        workspace, shape->cu_seqlens};
-    for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
-    Plan pl;
-    make_plan(shape, 1, &pl);
-    if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
-    if (int rc = check_device(impl, &pl.pb)) return rc;
-    Ptrs p;
-    memset(&p, 0, sizeof(p));
-    p.q = q; p.k = k; p.v = v; p.beta = beta; p.S0 = initial_state; p.d_o = d_o; p.dST = dfinal_state;
-    p.dq = dq; p.dk = dk; p.dv = dv; p.dbeta = dbeta; p.dS0 = dinitial_state;
-    pl.pb.stream = static_cast<hipStream_t>(hip_stream);
-    bind_workspace(pl, workspace, &p, &pl.pb, true);
-    return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
+    return bwd_impl(shape, q, k, v, beta, nullptr, false, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, nullptr,
+                    dinitial_state, workspace, workspace_bytes, hip_stream);
 }
 
-int deltanet_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
-                           const float *initial_state, void *o, float *final_state, void *hip_stream) {
+int deltanet_gated_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes) {
+    if (!out_bytes) return DN_ERR_NULL;
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    Plan pl;
+    make_plan(shape, want_bwd, &pl, true);
+    *out_bytes = pl.total;
+    return DN_OK;
+}
+
+int deltanet_gated_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                       const float *g, const float *initial_state, void *o, float *final_state, void *workspace,
+                       size_t workspace_bytes, void *hip_stream) {
+    return fwd_impl(shape, q, k, v, beta, g, true, initial_state, o, final_state, workspace, workspace_bytes, hip_stream);
+}
+
+int deltanet_gated_bwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                       const float *g, const float *initial_state, const void *d_o, const float *dfinal_state,
+                       void *dq, void *dk, void *dv, float *dbeta, float *dg, float *dinitial_state, void *workspace,
+                       size_t workspace_bytes, void *hip_stream) {
+    return bwd_impl(shape, q, k, v, beta, g, true, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
+                    workspace, workspace_bytes, hip_stream);
+}
+
+static int recurrent_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                          const float *g, bool gated, const float *initial_state, void *o, float *final_state,
+                          void *hip_stream) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl, false)) return rc;
-    if (!q || !k || !v || !beta || !o) return DN_ERR_NULL;
-    const void *al[] = {q, k, v, beta, initial_state, o, final_state, shape->cu_seqlens};
+    if (!q || !k || !v || !beta || !o || (gated && !g)) return DN_ERR_NULL;
+    const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
     if (shape->d_v % 16 != 0) return DN_ERR_UNSUPPORTED;
     if (shape->d_k != 32 && shape->d_k != 64 && shape->d_k != 128 && shape->d_k != 256) return DN_ERR_UNSUPPORTED;
     RecArgs a;
     a.q = q; a.k = k; a.v = v; a.beta = beta; a.S0 = initial_state; a.o = o; a.ST = final_state;
     a.cu = shape->cu_seqlens;
+    a.g = gated ? g : nullptr;
     a.N = shape->cu_seqlens ? shape->num_seqs : shape->B;
     a.L = shape->L; a.H = shape->H; a.DV = shape->d_v;
     const int rc = run_recurrent_fwd(shape->dtype == DN_BF16 ? 1 : 0, shape->d_k, a, static_cast<hipStream_t>(hip_stream));
     return rc == 0 ? DN_OK : (rc < 0 ? DN_ERR_UNSUPPORTED : DN_ERR_LAUNCH);
+}
+
+int deltanet_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                           const float *initial_state, void *o, float *final_state, void *hip_stream) {
+    return recurrent_impl(shape, q, k, v, beta, nullptr, false, initial_state, o, final_state, hip_stream);
+}
+
+int deltanet_gated_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                                 const float *g, const float *initial_state, void *o, float *final_state,
+                                 void *hip_stream) {
+    return recurrent_impl(shape, q, k, v, beta, g, true, initial_state, o, final_state, hip_stream);
 }
 
 int deltanet_profile_enable(int on) {

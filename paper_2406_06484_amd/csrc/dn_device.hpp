@@ -254,6 +254,36 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
 #pragma unroll
         for (int it = 0; it < NIT; ++it) *reinterpret_cast<uint4 *>(dst + (it * RPI + tr) * ld + tc) = v[it];
     }
+    // sum over the elements this lane holds of (this tile) * (other tile); both tiles share the lane mapping
+    __device__ inline float dot(const TileRegs &o) const {
+        float s = 0.f;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            alignas(16) T a[VEC], b[VEC];
+            *reinterpret_cast<uint4 *>(a) = v[it];
+            *reinterpret_cast<uint4 *>(b) = o.v[it];
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
+        }
+        return s;
+    }
+    // Per-row factors for scale_rows: f[it] = src[row held in step it] (rows of the tile this lane touches).
+    __device__ inline void load_row_factors(float (&f)[NIT], const float *src, int t = threadIdx.x) const {
+        const int tr = t / TPR;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) f[it] = src[it * RPI + tr];
+    }
+    // held tile <- diag(f) * tile, in the storage type
+    __device__ inline void scale_rows(const float (&f)[NIT]) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            alignas(16) T e[VEC];
+            *reinterpret_cast<uint4 *>(e) = v[it];
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) e[u] = from_f32<T>(to_f32(e[u]) * f[it]);
+            v[it] = *reinterpret_cast<const uint4 *>(e);
+        }
+    }
 };
 // ---------------------------------------------------------------------------------------------
 // Global -> LDS: ROWS x COLS tile, 16-byte loads, rows >= nvalid become zero.

@@ -24,6 +24,11 @@ struct Ptrs {
     // workspace tiles, indexed by (global chunk * H + head)
     void *Tm, *Xm, *Ut, *dUt, *Sc, *dSc;
     int want_x; // backward: k_wy_prep also stores the inverse X for the chunk kernel
+    // gated variant (all null for the plain delta rule): g = log decay per token and head (fp32, user
+    // tensor), dg its gradient; workspace: gam = per chunk the running decay gamma_i and 1/gamma_i
+    // ([tile][2][C] fp32), zc = per chunk <dS_C, S_C>, state after the chunk against its gradient ([tile] fp32)
+    const float *g;
+    float *dg, *gam, *zc;
 };
 
 // Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is
@@ -45,6 +50,7 @@ struct RecArgs {
     void *o;
     float *ST;
     const int32_t *cu; // device cu_seqlens or nullptr
+    const float *g;    // gated variant: log decay per token and head, or nullptr
     int N, L, H, DV;
 };
 int run_recurrent_fwd(int dtype, int d_k, const RecArgs &a, hipStream_t stream);

@@ -79,6 +79,19 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
 
     load_tile<T, C, DK>(sK, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
     if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
+    if (p.g && tid < C) {
+        // Gated variant: gamma_i = exp(g_1 + ... + g_i) within the chunk (rows past the end keep the last
+        // value).  S_i / gamma_i follows the plain delta rule on the values v_i / gamma_i, so the other
+        // kernels only rescale rows with gamma_i and 1 / gamma_i; T and X do not depend on the gate.
+        float cs = tid < nvalid ? p.g[(row0 + tid) * H + h] : 0.f;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float up = __shfl_up(cs, d);
+            if (tid >= d) cs += up;
+        }
+        p.gam[tile * 2 * C + tid] = __expf(cs);
+        p.gam[tile * 2 * C + C + tid] = __expf(-cs);
+    }
     lds_barrier();
     f32x16 g = zero16();
     if (!upper) mma<DK, false, false, T>(g, sK + 32 * mi * SM::LD, SM::LD, sK + 32 * ni * SM::LD, SM::LD); // K K^T
@@ -163,10 +176,11 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oP = oT + align16(sizeof(T) * C * LT);
     static constexpr size_t oStage = oP + align16(sizeof(T) * C * LT); // per-wave output staging tiles
     static constexpr int NSTG = 4; // only the four output waves stage tiles
-    static constexpr size_t bytes = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS;
+    static constexpr size_t oGam = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS; // gated: gamma_i, 1 / gamma_i of the chunk
+    static constexpr size_t bytes = oGam + sizeof(float) * 2 * C;
 };
 
-template <typename T, int DK, int DV, bool STORE>
+template <typename T, int DK, int DV, bool STORE, bool GATED>
 __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanFwdSmem<T, DK, DV>;
     constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
@@ -182,6 +196,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     T *sUT0 = reinterpret_cast<T *>(smem + SM::oUT), *sUT1 = reinterpret_cast<T *>(smem + SM::oUT + SM::szUT);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sP = reinterpret_cast<T *>(smem + SM::oP);
+    float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
+    constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -209,6 +225,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         TileRegs<T, C, DK, NTL> q, k;
         TileRegs<T, C, BV, NTL> v;
         TileRegs<T, C, C, NTL> t;
+        float vs[TileRegs<T, C, BV, NTL>::NIT], gm; // gated: 1 / gamma of this lane's V rows; one entry of the gamma table
     } r;
     auto fetch_a = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
@@ -217,6 +234,10 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+        if (gated) {
+            r.v.load_row_factors(r.vs, p.gam + tile * 2 * C + C, lt);
+            if (lt < 2 * C) r.gm = p.gam[tile * 2 * C + lt];
+        }
     };
     auto fetch_b = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
@@ -238,13 +259,23 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
         if (!STORE) r.q.store(sQ, SM::LQ, lt);
         r.k.store(sK, SM::LK, lt);
+        if (gated) { // the chunk runs the plain rule on v_i / gamma_i
+            r.v.scale_rows(r.vs);
+            if (lt < 2 * C) sGam[lt] = r.gm;
+        }
         r.v.store(sV, SM::LV, lt);
         r.t.store(sT, SM::LT, lt);
     };
     if (loader && nchunks > 0) { fetch_a(0); fetch_b(0); stash(); }
+    // gated: gamma at the end of the chunk, which rescales the state when the chunk is done; every wave
+    // requests the next chunk's value one step ahead
+    float gC = 1.f, gCn = 1.f;
+    if (gated && nchunks > 0) gCn = p.gam[((long)cb * H + h) * 2 * C + C - 1];
     for (int ic = 0; ic < nchunks; ++ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sUT = (ic & 1) ? sUT1 : sUT0;
+        gC = gCn;
+        if (gated && ic + 1 < nchunks) gCn = p.gam[(tile + H) * 2 * C + C - 1];
         if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         lds_barrier();
         if (loader && ic + 1 < nchunks) fetch_a(ic + 1);
@@ -296,9 +327,11 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
+            if (gated) acc_each(acc, [&](int rr, int, float &val) { val *= sGam[32 * m.ua + rr]; }); // o_i = gamma_i o~_i
             acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc);
         }
         if (m.has_s) mma<C, true, false, T>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
+        if (gated) S *= gC; // back from S / gamma to the state itself at the chunk boundary
         lds_barrier();
         // The next chunk's tiles move to LDS here, in the iteration that requested them: the wait the
         // compiler puts in front counts the stores issued after the loads and lets those stay in flight.
@@ -310,9 +343,9 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
 }
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool GATED>
 __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
-    scan_fwd_body<T, DK, DV, false>(sm, H, p, blockIdx.x);
+    scan_fwd_body<T, DK, DV, false, GATED>(sm, H, p, blockIdx.x);
 }
 
 // scan_bwd_body: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
@@ -333,7 +366,7 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t bytes = oPT + align16(sizeof(T) * C * LT);
 };
 
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool GATED>
 __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanBwdSmem<T, DK, DV>;
     constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
@@ -348,6 +381,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     T *sDUT0 = reinterpret_cast<T *>(smem + SM::oDUT), *sDUT1 = reinterpret_cast<T *>(smem + SM::oDUT + SM::szDUT);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
+    constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -373,6 +407,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         TileRegs<T, C, DK, NTL> q, k;
         TileRegs<T, C, BV, NTL> d_o;
         TileRegs<T, C, C, NTL> t;
+        float dos[TileRegs<T, C, BV, NTL>::NIT]; // gated: gamma of this lane's dO rows
     } r;
     auto fetch_a = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
@@ -386,6 +421,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         const long tile = ((long)(cb + ic) * H + h);
         r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+        if (gated) r.d_o.load_row_factors(r.dos, p.gam + tile * 2 * C, lt);
     };
     auto flush_dut = [&](int icp) __attribute__((always_inline)) { // dUt^T of chunk icp, still in LDS
         copy_out<T, BV, C, NTL>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, lt);
@@ -393,13 +429,23 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
-        r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt); r.d_o.store(sDO, SM::LD, lt);
+        r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt);
+        if (gated) r.d_o.scale_rows(r.dos); // o_i = gamma_i o~_i, so the plain rule's output gradient is gamma_i dO_i
+        r.d_o.store(sDO, SM::LD, lt);
         r.t.store(sT, SM::LT, lt);
     };
     if (loader && nchunks > 0) { fetch_a(nchunks - 1); fetch_b(nchunks - 1); stash(); }
+    // gated: the state after the chunk is gamma_C times the plain rule's, so its gradient is scaled by
+    // gamma_C on entry; every wave requests the value for the next step one step ahead
+    float gCn = 1.f;
+    if (gated && nchunks > 0) gCn = p.gam[((long)(cb + nchunks - 1) * H + h) * 2 * C + C - 1];
     for (int ic = nchunks - 1; ic >= 0; --ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sDUT = (ic & 1) ? sDUT1 : sDUT0;
+        if (gated) {
+            dS *= gCn;
+            if (ic > 0) gCn = p.gam[(tile - H) * 2 * C + C - 1];
+        }
         if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' (gradient w.r.t. the state after this chunk)
         lds_barrier();
         if (loader && ic > 0) fetch_a(ic - 1);
@@ -457,10 +503,10 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
 // scan needs T; the reverse scan needs T and P^T), so the first half of the grid runs the reverse
 // scan and the second half the recompute scan: a CU picks up one of each with no kernel boundary
 // in between.  `half` = workgroups per scan.
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool GATED>
 __global__ __launch_bounds__(NTS) void k_scan_pair(SeqMap sm, int H, Ptrs p, int half) {
-    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV>(sm, H, p, blockIdx.x);
-    else scan_fwd_body<T, DK, DV, true>(sm, H, p, blockIdx.x - half);
+    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV, GATED>(sm, H, p, blockIdx.x);
+    else scan_fwd_body<T, DK, DV, true, GATED>(sm, H, p, blockIdx.x - half);
 }
 
 // =============================================================================================
@@ -516,12 +562,14 @@ template <typename T, int DK, int DV> struct ChunkSmem {
     static constexpr size_t oB7 = oB6 + align16(szCC);                 // S^T; dS'^T; X
     static constexpr size_t szB7 = cmax(sizeof(T) * DV * LSK, szCC);
     static constexpr size_t oBeta = oB7 + align16(szB7);
-    static constexpr size_t oDb = oBeta + sizeof(float) * C;
-    static constexpr size_t oStage = align16(oDb + sizeof(float) * 4 * C);
+    static constexpr size_t oGi = oBeta + sizeof(float) * C;            // gated: 1 / gamma_i
+    static constexpr size_t oDb = oGi + sizeof(float) * C;
+    static constexpr size_t oZ = oDb + sizeof(float) * 4 * C;          // gated: per-wave shares of <dS_C, S_C>
+    static constexpr size_t oStage = align16(oZ + sizeof(float) * NWC);
     static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
 };
 
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool GATED>
 __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int chunks_total) {
     using SM = ChunkSmem<T, DK, DV>;
     constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);        // 32 x 32 tiles of a C x DK / C x DV matrix
@@ -538,7 +586,10 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     T *sS = reinterpret_cast<T *>(smem + SM::oB7);
     T *sXn = reinterpret_cast<T *>(smem + SM::oB7); // X = (I + A)^-1 as computed by k_wy_prep
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
+    float *sGi = reinterpret_cast<float *>(smem + SM::oGi);
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
+    float *sZ = reinterpret_cast<float *>(smem + SM::oZ);
+    constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
     const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
@@ -556,6 +607,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         TileRegs<T, C, DK, NTC> k, q;
         TileRegs<T, C, C, NTC> x;
         T beta; // kept in storage format: converting here would wait for the whole prefetch
+        // gated: gamma of this lane's dO rows, 1 / gamma of its V rows, 1 / gamma of row tid
+        float dos[TileRegs<T, C, DV, NTC>::NIT], vsc[TileRegs<T, C, DV, NTC>::NIT], gi;
     } r;
     auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
         if (!tp.ok) return;
@@ -569,6 +622,11 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV);
         r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
         r.x.load((const T *)p.Xm + tp.tile * C * C, C, C);
+        if (gated) {
+            r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
+            r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
+            if (tid < C) r.gi = p.gam[tp.tile * 2 * C + C + tid];
+        }
     };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
 
@@ -585,9 +643,20 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
         // ---- adjoint of Eq. 8-9
+        // gated: the chunk is the plain rule on v_i / gamma_i with outputs gamma_i o~_i, so dO rows come in
+        // scaled by gamma_i, V rows by 1 / gamma_i, and dV goes out scaled by 1 / gamma_i
+        // gated: this thread's share of <dS_C, S_C> = <dS~', S_0> + <K, Ut dS~'^T>, for the gate gradient
+        float zp = 0.f;
+        if (gated) {
+            zp = r.s.dot(r.ds);
+            r.d_o.scale_rows(r.dos);
+        }
         r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LU); r.s.store(sS, SM::LSK);
         r.dut.store(sDU, SM::LU); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
-        if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
+        if (tid < C) {
+            sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
+            if (gated) sGi[tid] = r.gi;
+        }
         lds_barrier();
         if (cc) { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
@@ -617,7 +686,14 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
             if (ka(sI) == 1) mma<32, true, true, T>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK);
             else mma<C, true, true, T>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK);
-            mma<DV, true, true, T>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
+            if (gated) {
+                f32x16 uds = zero16();
+                mma<DV, true, true, T>(uds, sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
+                acc_each(uds, [&](int rr, int c, float &val) { zp += val * to_f32(sK[(32 * ka(sI) + rr) * SM::LK + 32 * kb(sI) + c]); });
+                dk1[sI] += uds;
+            } else {
+                mma<DV, true, true, T>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
+            }
         }
         lds_barrier(); // dO, Ut, Q, dP, dS' are dead
         // ---- adjoint of Eq. 10-11
@@ -626,6 +702,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             acc_each(dw[sI], [&](int, int, float &val) { val = -val; });
             acc_to_lds<T>(sDW, SM::LK, 32 * ka(sI), 32 * kb(sI), dw[sI]);
         }
+        if (gated) r.v.scale_rows(r.vsc);
         r.v.store(sV, SM::LV);
         lds_barrier();
         f32x16 g = zero16(), dxp = zero16();
@@ -664,7 +741,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             f32x16 acc = zero16();
             if (va(sI) == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * vbk(sI) * SM::LU + 32, SM::LU);
             else mma<C, true, false, T>(acc, sXn, SM::LT, sDU + 32 * vbk(sI) * SM::LU, SM::LU);
-            acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * va(sI) + rr]; });
+            acc_each(acc, [&](int rr, int, float &val) {
+                val *= gated ? sBeta[32 * va(sI) + rr] * sGi[32 * va(sI) + rr] : sBeta[32 * va(sI) + rr];
+            });
             acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
         }
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
@@ -684,6 +763,12 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 sDX[i * SM::LT + j] = from_f32<T>(sBeta[i] * da);
             }
         }
+        if (gated) { // this wave's share of <dS_C, S_C>, summed in a fixed order after the barrier
+            float zw = zp;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) zw += __shfl_xor(zw, d);
+            if (lane == 0) sZ[wave] = zw;
+        }
         lds_barrier();
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK = dK1 + diag(beta) dKb + Ah K + Ah^T K; Ah is strictly lower triangular
@@ -693,6 +778,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             else mma<C, true, true, T>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
             acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
         }
+        if (gated && tid == 0) p.zc[cur.tile] = ((sZ[0] + sZ[1]) + (sZ[2] + sZ[3])) + ((sZ[4] + sZ[5]) + (sZ[6] + sZ[7]));
         if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G
             const int i = tid >> 2, seg = tid & 3;
             float sum = 0.f;
@@ -704,6 +790,61 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 p.dbeta[(row0 + i) * H + h] = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
         }
         lds_barrier(); // every buffer is free for the next tile
+    }
+}
+
+// =============================================================================================
+// Gradient of the gate (gated variant only).  Because o_t is linear in q_t and in the state, the
+// sensitivity of the loss to a rescaling of the state at time t can be read off the other gradients:
+//     dg_j = <dS_C, S_C> + sum_{i = j .. end of the chunk} (q_i . dq_i - v_i . dv_i)
+// with S_C the state after the chunk and dS_C its gradient.  The chunk kernel leaves <dS_C, S_C> in
+// zc[tile] (from fp32 accumulators); this kernel adds the token terms, one workgroup per (chunk,
+// head): four lanes per token for the two dot products, then a suffix sum over the 64 tokens.
+template <typename T, int DK, int DV>
+__global__ __launch_bounds__(NTHR) void k_gate_grad(SeqMap sm, int H, Ptrs p) {
+    constexpr int VEC = El<T>::VEC;
+    __shared__ float sC[C];
+    int n, ic;
+    if (!sm.chunk(blockIdx.x, n, ic)) return;
+    int t0, len, cb;
+    sm.seq(n, t0, len, cb);
+    const int h = blockIdx.y, tid = threadIdx.x, i = tid >> 2, l4 = tid & 3;
+    const int nvalid = min(C, len - ic * C);
+    const long row0 = (long)t0 + (long)ic * C;
+    const long tile = ((long)(cb + ic) * H + h);
+    float s = 0.f;
+    if (i < nvalid) {
+        const long item = (row0 + i) * H + h;
+        const T *q = (const T *)p.q + item * DK, *dq = (const T *)p.dq + item * DK;
+        const T *v = (const T *)p.v + item * DV, *dv = (const T *)p.dv + item * DV;
+        for (int c = l4 * VEC; c < DK; c += 4 * VEC) {
+            alignas(16) T a[VEC], b[VEC];
+            *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(q + c);
+            *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(dq + c);
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
+        }
+        for (int c = l4 * VEC; c < DV; c += 4 * VEC) {
+            alignas(16) T a[VEC], b[VEC];
+            *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(v + c);
+            *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(dv + c);
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) s -= to_f32(a[u]) * to_f32(b[u]);
+        }
+    }
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    if (l4 == 0) sC[i] = s;
+    __syncthreads();
+    if (tid < C) { // suffix sum over the chunk: thread t takes token C - 1 - t, inclusive scan over t
+        float c = sC[C - 1 - tid];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float up = __shfl_up(c, d);
+            if (tid >= d) c += up;
+        }
+        const int tok = C - 1 - tid;
+        if (tok < nvalid) p.dg[(row0 + tok) * H + h] = c + p.zc[tile];
     }
 }
 

@@ -52,7 +52,8 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    DN_LAUNCH_NT((k_scan_fwd<T, DK, DV>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if (p.g) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    else DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;
 }
 
@@ -65,13 +66,16 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     { // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
         const dim3 gpair(2 * gchain.x);
-        DN_LAUNCH_NT((k_scan_pair<T, DK, DV>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
+        if (p.g) DN_LAUNCH_NT((k_scan_pair<T, DK, DV, true>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
+        else DN_LAUNCH_NT((k_scan_pair<T, DK, DV, false>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
     }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
-        DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        if (p.g) DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV, true>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        else DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV, false>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
     }
+    if (p.g && pb.chunks_ub) DN_LAUNCH((k_gate_grad<T, DK, DV>), gchunk, 0, sm, pb.H, p); // from the gradients just written
     return 0;
 }
 

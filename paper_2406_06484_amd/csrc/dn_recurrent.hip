@@ -75,7 +75,8 @@ template <typename T, int DK> struct RecStage {
     static constexpr int VROWW = kRecCols * (int)sizeof(T) / 16;      // 16-byte words of one token's v slice
     static_assert(TB >= 1 && TB * ROWW % 64 == 0 && TB * VROWW <= 64, "staging layout");
     static constexpr int oK = 0, oQ = TB * ROWB, oV = 2 * TB * ROWB, oB = oV + TB * kRecCols * (int)sizeof(T);
-    static constexpr int bytes = (oB + TB * (int)sizeof(T) + 15) & ~15; // one buffer of one wave
+    static constexpr int oG = (oB + TB * (int)sizeof(T) + 3) & ~3;      // gated: alpha_t = exp(g_t), fp32
+    static constexpr int bytes = (oG + TB * 4 + 15) & ~15;              // one buffer of one wave
 };
 
 template <typename T, int DK>
@@ -107,6 +108,7 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
     // one block of tokens in flight: global -> registers (fetch), registers -> LDS (park)
     uint4 gk[ST::NKW], gq[ST::NKW], gv;
     T gb;
+    float ga = 1.f; // gated variant (section 6, the overview table's last row): decay alpha_t = exp(g_t) on the old state
     auto fetch = [&](int tb) __attribute__((always_inline)) { // tokens tb .. tb + TB - 1 of this sequence
 #pragma unroll
         for (int i = 0; i < ST::NKW; ++i) {
@@ -124,7 +126,10 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
             const int tok = lane / ST::VROWW, pos = lane % ST::VROWW;
             if (tok < TB && tb + tok < len)
                 gv = reinterpret_cast<const uint4 *>((const T *)a.v + ((long)(t0 + tb + tok) * H + h) * DV + col0)[pos];
-            if (lane < TB && tb + lane < len) gb = ((const T *)a.beta)[(long)(t0 + tb + lane) * H + h];
+            if (lane < TB && tb + lane < len) {
+                gb = ((const T *)a.beta)[(long)(t0 + tb + lane) * H + h];
+                if (a.g) ga = __expf(a.g[(long)(t0 + tb + lane) * H + h]);
+            }
         }
     };
     auto park = [&](unsigned char *buf) __attribute__((always_inline)) {
@@ -134,7 +139,10 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
             reinterpret_cast<uint4 *>(buf + ST::oQ)[i * 64 + lane] = gq[i];
         }
         if (lane < TB * ST::VROWW) reinterpret_cast<uint4 *>(buf + ST::oV)[lane] = gv;
-        if (lane < TB) reinterpret_cast<T *>(buf + ST::oB)[lane] = gb;
+        if (lane < TB) {
+            reinterpret_cast<T *>(buf + ST::oB)[lane] = gb;
+            reinterpret_cast<float *>(buf + ST::oG)[lane] = ga;
+        }
     };
 
     T *op = (T *)a.o + ((long)t0 * H + h) * DV + col;
@@ -155,6 +163,7 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
             qr.load(reinterpret_cast<const T *>(cur + ST::oQ) + tt * DK + rb * R);
             const float vt = rec_to_f32(reinterpret_cast<const T *>(cur + ST::oV)[tt * kRecCols + j]);
             const float bt = rec_to_f32(reinterpret_cast<const T *>(cur + ST::oB)[tt]);
+            const float at = reinterpret_cast<const float *>(cur + ST::oG)[tt]; // 1 for the plain rule
             float kf[R], qf[R];
             kr.unpack(kf);
             qr.unpack(qf);
@@ -164,14 +173,15 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
                 d0 = fmaf(S[r], kf[r], d0); d1 = fmaf(S[r + 1], kf[r + 1], d1);
                 d2 = fmaf(S[r + 2], kf[r + 2], d2); d3 = fmaf(S[r + 3], kf[r + 3], d3);
             }
-            const float u = live ? bt * (vt - rec_sum4((d0 + d1) + (d2 + d3))) : 0.f;
+            const float u = live ? bt * (vt - at * rec_sum4((d0 + d1) + (d2 + d3))) : 0.f;
+            const float keep = live ? at : 1.f; // S_t = alpha_t S_{t-1} + k_t u_t^T
             float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f; // S_t^T q_t, read-out from the updated state
 #pragma unroll
             for (int r = 0; r < R; r += 4) {
-                S[r] = fmaf(kf[r], u, S[r]); o0 = fmaf(S[r], qf[r], o0);
-                S[r + 1] = fmaf(kf[r + 1], u, S[r + 1]); o1 = fmaf(S[r + 1], qf[r + 1], o1);
-                S[r + 2] = fmaf(kf[r + 2], u, S[r + 2]); o2 = fmaf(S[r + 2], qf[r + 2], o2);
-                S[r + 3] = fmaf(kf[r + 3], u, S[r + 3]); o3 = fmaf(S[r + 3], qf[r + 3], o3);
+                S[r] = fmaf(kf[r], u, keep * S[r]); o0 = fmaf(S[r], qf[r], o0);
+                S[r + 1] = fmaf(kf[r + 1], u, keep * S[r + 1]); o1 = fmaf(S[r + 1], qf[r + 1], o1);
+                S[r + 2] = fmaf(kf[r + 2], u, keep * S[r + 2]); o2 = fmaf(S[r + 2], qf[r + 2], o2);
+                S[r + 3] = fmaf(kf[r + 3], u, keep * S[r + 3]); o3 = fmaf(S[r + 3], qf[r + 3], o3);
             }
             const float out = rec_sum4((o0 + o1) + (o2 + o3));
             if (rb == 0 && live) rec_store(op, out);

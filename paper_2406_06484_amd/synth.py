@@ -104,3 +104,9 @@ CONFIGS = {
 def make_config(idx: int) -> Inputs:
     kw = dict(CONFIGS[idx])
     return make_inputs(kw.pop("seed"), **kw)
+
+
+def make_gate(seed: int, shape, lo: float = 0.85, hi: float = 1.0) -> np.ndarray:
+    """Log-decay g = log(alpha) of the gated variant, alpha ~ U(lo, hi) per token and head, as float32."""
+    rng = np.random.default_rng(seed + 7_000_003)
+    return np.log(rng.uniform(lo, hi, size=shape)).astype(np.float32)

@@ -21,7 +21,8 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(LIB)
     syms = header_symbols()
     assert {"deltanet_fwd", "deltanet_bwd", "deltanet_recurrent_fwd", "deltanet_workspace_bytes",
-            "deltanet_status_string"} <= set(syms)
+            "deltanet_gated_fwd", "deltanet_gated_bwd", "deltanet_gated_recurrent_fwd",
+            "deltanet_gated_workspace_bytes", "deltanet_status_string"} <= set(syms)
     for s in syms:
         assert hasattr(lib, s), s
 

@@ -1,0 +1,79 @@
+"""GPU parity of the gated variant (deltanet_gated_fwd / _bwd / _recurrent_fwd through the C ABI) against
+the fp64 oracle's gated recurrence and its adjoint."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_06484_amd as dn
+from paper_2406_06484_amd.synth import make_gate, make_inputs
+from tests.gpu_util import TOL, dev_inputs, nerr
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gated(inp, g, bwd=True, label=""):
+    d = dev_inputs(inp)
+    gd = torch.from_numpy(g).cuda()
+    o, ST = dn.deltanet_gated_fwd(d["q"], d["k"], d["v"], d["beta"], gd, d["S0"], cu_seqlens=d["cu"])
+    torch.cuda.synchronize()
+    o_ref, ST_ref = oracle.gated_fwd(inp.q, inp.k, inp.v, inp.beta, g, inp.initial_state, inp.cu_seqlens)
+    errs = {"o": nerr(o.float().cpu().numpy(), o_ref), "final_state": nerr(ST.cpu().numpy(), ST_ref)}
+    if bwd:
+        out = dn.deltanet_gated_bwd(d["q"], d["k"], d["v"], d["beta"], gd, d["d_o"], d["S0"], d["dST"], cu_seqlens=d["cu"])
+        torch.cuda.synchronize()
+        ref = oracle.gated_bwd(inp.q, inp.k, inp.v, inp.beta, g, inp.d_o, inp.initial_state, inp.dfinal_state, inp.cu_seqlens)
+        # binding order: dq, dk, dv, dbeta, dg, dS0 -- same as the oracle's
+        for name, a, b in zip(("dq", "dk", "dv", "dbeta", "dg", "dinitial_state"), out, ref):
+            errs[name] = nerr(a.float().cpu().numpy(), b)
+    print(label, " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
+    tol = TOL[inp.dtype]
+    for name, e in errs.items():
+        assert e < tol, (label, name, e)
+
+
+@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128)])
+def test_gated_ragged_multi_chunk_with_states(dtype, dk, dv):
+    inp = make_inputs(300 + dk + dv, B=2, L=200, H=3, dk=dk, dv=dv, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
+    inp.initial_state *= 10.0
+    run_gated(inp, make_gate(1, inp.beta.shape), label="gated %s %dx%d" % (dtype, dk, dv))
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_gated_strong_decay_and_packed(dtype, d):
+    cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)
+    inp = make_inputs(8, H=2, dk=d, dv=d, dtype=dtype, cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)
+    run_gated(inp, make_gate(2, inp.beta.shape, lo=0.4, hi=1.0), label="gated packed strong %s" % dtype)
+
+
+def test_zero_gate_equals_the_plain_path_on_the_gpu():
+    inp = make_inputs(9, B=1, L=150, H=2, dk=128, dv=128, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
+    d = dev_inputs(inp)
+    g0 = torch.zeros(inp.beta.shape, dtype=torch.float32, device="cuda")
+    o_g, S_g = dn.deltanet_gated_fwd(d["q"], d["k"], d["v"], d["beta"], g0, d["S0"])
+    o_p, S_p = dn.deltanet_fwd(d["q"], d["k"], d["v"], d["beta"], d["S0"])
+    out_g = dn.deltanet_gated_bwd(d["q"], d["k"], d["v"], d["beta"], g0, d["d_o"], d["S0"], d["dST"])
+    out_p = dn.deltanet_bwd(d["q"], d["k"], d["v"], d["beta"], d["d_o"], d["S0"], d["dST"])
+    torch.cuda.synchronize()
+    assert torch.equal(o_g, o_p) and torch.equal(S_g, S_p)
+    for a, b in zip((out_g[0], out_g[1], out_g[2], out_g[3], out_g[5]), out_p):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 48), ("bf16", 128, 128), ("bf16", 256, 64)])
+def test_gated_recurrent_matches_oracle(dtype, dk, dv):
+    inp = make_inputs(600 + dk, B=2, L=150, H=3, dk=dk, dv=dv, dtype=dtype, with_initial_state=True)
+    g = make_gate(3, inp.beta.shape, lo=0.5, hi=1.0)
+    d = dev_inputs(inp)
+    o, ST = dn.deltanet_gated_recurrent_fwd(d["q"], d["k"], d["v"], d["beta"], torch.from_numpy(g).cuda(), d["S0"])
+    torch.cuda.synchronize()
+    o_ref, ST_ref = oracle.gated_fwd(inp.q, inp.k, inp.v, inp.beta, g, inp.initial_state)
+    eo, es = nerr(o.float().cpu().numpy(), o_ref), nerr(ST.cpu().numpy(), ST_ref)
+    print("gated recurrent %s %dx%d o=%.2e final_state=%.2e" % (dtype, dk, dv, eo, es), flush=True)
+    assert eo < TOL[dtype] and es < (1e-4 if dtype == "f32" else 2e-3)
+
+
+def test_gated_full_size_benchmark_shape():
+    from paper_2406_06484_amd.synth import make_config
+    inp = make_config(2)
+    run_gated(inp, make_gate(4, inp.beta.shape, lo=0.9, hi=1.0), label="gated cfg2")

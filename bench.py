@@ -214,6 +214,27 @@ def main() -> int:
                                          "unit": "TFLOP/s", "frac": round(rec_tflops / PEAK_FP32_VECTOR_TFLOPS, 4),
                                          "traffic": measured_traffic("k_recurrent_fwd")}}
 
+    # The gated variant (scalar decay exp(g_t) on the transition) on the same workload: same kernels with
+    # rescaled rows, plus the gate gradient.
+    from paper_2406_06484_amd.binding import deltanet_gated_workspace_bytes
+    from paper_2406_06484_amd.synth import make_gate
+    g = torch.from_numpy(make_gate(2, (B, L, H), 0.9, 1.0)).to(dev)
+    wsg = torch.empty(deltanet_gated_workspace_bytes(shp, True), dtype=torch.uint8, device=dev)
+
+    def gated_step():
+        dn.deltanet_gated_fwd(q, k, v, beta, g, o=o, final_state=ST, workspace=wsg)
+        return dn.deltanet_gated_bwd(q, k, v, beta, g, d_o, workspace=wsg)
+    for _ in range(3):
+        gated_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(rec_steps):
+        gated_step()
+    torch.cuda.synchronize()
+    gms = 1e3 * (time.perf_counter() - t0) / rec_steps
+    out["gated_fwd_bwd"] = {"ms": round(gms, 4), "tokens_per_s": round(tokens / (gms * 1e-3), 1), "steps": rec_steps,
+                            "vs_plain": round(gms / ms_per_step, 3)}
+
     if not args.no_cpu_baseline:
         import oracle
         nthr = oracle.max_threads()

@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_zc, total;
+    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, total;
     size_t esz;
 };
 
@@ -119,7 +119,6 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false) {
     }
     if (gated) {
         pl->off_gam = o; o += up256(tiles * 2 * kChunk * sizeof(float)); // gamma_i and 1 / gamma_i per chunk row
-        if (want_bwd) { pl->off_zc = o; o += up256(tiles * sizeof(float)); } // <dS_C, S_C> per chunk
     }
     pl->total = o;
 }
@@ -138,7 +137,6 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     }
     if (gated) {
         p->gam = reinterpret_cast<float *>(b + pl.off_gam);
-        if (want_bwd) p->zc = reinterpret_cast<float *>(b + pl.off_zc);
     }
 }
 

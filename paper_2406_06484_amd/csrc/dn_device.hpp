@@ -226,6 +226,32 @@ __device__ inline void stage_flush(const T *stage, T *dst, long row_stride, int 
     }
     wave_lds_fence(); // the staging tile may be rewritten right away
 }
+// stage_flush that also returns row dot products of the staged tile with the matching 32 x 32 block of
+// an LDS-resident matrix `other` (leading dimension ldo): slot[row0 + r] = sum_c stage(r, c) *
+// other(row0 + r, col0 + c), written by one lane per row.  Used for the per-token terms of the gate gradient.
+template <typename T>
+__device__ inline void stage_flush_dot(const T *stage, T *dst, long row_stride, int row0, int col0, int nvalid,
+                                       const T *other, int ldo, float *slot) {
+    constexpr int SEGS = Stage<T>::SEGS, VEC = El<T>::VEC;
+    const int lane = threadIdx.x & 63;
+    wave_lds_fence();
+#pragma unroll
+    for (int it = 0; it < 32 * SEGS / 64; ++it) {
+        const int idx = it * 64 + lane, r = idx / SEGS, sg = idx % SEGS;
+        alignas(16) T a[VEC], b[VEC];
+        *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(stage + r * Stage<T>::LD + sg * VEC);
+        *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(other + (row0 + r) * ldo + col0 + sg * VEC);
+        if (row0 + r < nvalid)
+            *reinterpret_cast<uint4 *>(dst + (long)(row0 + r) * row_stride + col0 + sg * VEC) = *reinterpret_cast<const uint4 *>(a);
+        float s = 0.f;
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
+#pragma unroll
+        for (int d = 1; d < SEGS; d <<= 1) s += __shfl_xor(s, d); // the SEGS lanes of one row are adjacent
+        if (sg == 0) slot[row0 + r] = s;
+    }
+    wave_lds_fence();
+}
 // dst[row0 + r][col0 + c] = acc(r, c), rows >= nvalid dropped; `stage` is this wave's staging tile
 template <typename T>
 __device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc) {
@@ -254,14 +280,15 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
 #pragma unroll
         for (int it = 0; it < NIT; ++it) *reinterpret_cast<uint4 *>(dst + (it * RPI + tr) * ld + tc) = v[it];
     }
-    // sum over the elements this lane holds of (this tile) * (other tile); both tiles share the lane mapping
-    __device__ inline float dot(const TileRegs &o) const {
+    // sum over the elements this lane holds of (this tile) * (a tile of the same shape parked in LDS by store())
+    __device__ inline float dot_lds(const T *src, int ld, int t = threadIdx.x) const {
+        const int tr = t / TPR, tc = (t % TPR) * VEC;
         float s = 0.f;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             alignas(16) T a[VEC], b[VEC];
             *reinterpret_cast<uint4 *>(a) = v[it];
-            *reinterpret_cast<uint4 *>(b) = o.v[it];
+            *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(src + (it * RPI + tr) * ld + tc);
 #pragma unroll
             for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
         }

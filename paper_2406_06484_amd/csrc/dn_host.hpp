@@ -26,9 +26,9 @@ struct Ptrs {
     int want_x; // backward: k_wy_prep also stores the inverse X for the chunk kernel
     // gated variant (all null for the plain delta rule): g = log decay per token and head (fp32, user
     // tensor), dg its gradient; workspace: gam = per chunk the running decay gamma_i and 1/gamma_i
-    // ([tile][2][C] fp32), zc = per chunk <dS_C, S_C>, state after the chunk against its gradient ([tile] fp32)
+    // ([tile][2][C] fp32)
     const float *g;
-    float *dg, *gam, *zc;
+    float *dg, *gam;
 };
 
 // Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is

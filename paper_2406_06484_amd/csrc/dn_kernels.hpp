@@ -198,6 +198,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     T *sP = reinterpret_cast<T *>(smem + SM::oP);
     float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
+    constexpr int MB = GATED ? 2 : 0; // the gated kernels request operand fragments in smaller batches: they have no registers to spare
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -291,12 +292,12 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
                 const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
                 w[i] = zero16();
                 if (Map::W_TILES % 4 == 0 || t < Map::W_TILES)
-                    mma<C, true, false, T, false>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+                    mma<C, true, false, T, GATED, MB>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
             }
-            if (m.does_u) mma<C, false, true, T, false>(acc, sT + 32 * m.ua * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV); // U = T V
+            if (m.does_u) mma<C, false, true, T, GATED, MB>(acc, sT + 32 * m.ua * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV); // U = T V
             f32x16 pa = zero16();
             if (!STORE) // P = tril(Q K^T), the causal intra-chunk scores of Eq. 9, as the tile (pni, pmi) of P^T
-                mma<DK, false, false, T, false>(pa, sK + 32 * pni * SM::LK, SM::LK, sQ + 32 * pmi * SM::LQ, SM::LQ);
+                mma<DK, false, false, T, GATED, MB>(pa, sK + 32 * pni * SM::LK, SM::LK, sQ + 32 * pmi * SM::LQ, SM::LQ);
 #pragma unroll
             for (int i = 0; i < NWT; ++i) {
                 const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
@@ -316,21 +317,21 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         }
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
             f32x16 ws = zero16();
-            mma<DK, false, false, T>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
+            mma<DK, false, false, T, true, MB>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
             acc -= ws;
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         } else if (does_o) { // Q S
-            mma<DK, false, false, T>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
+            mma<DK, false, false, T, true, MB>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
         if (STORE && loader && ic > 0) flush_prev(ic - 1);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
-            if (m.ua == 0) mma<32, false, false, T>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
-            else mma<C, false, false, T>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
+            if (m.ua == 0) mma<32, false, false, T, true, MB>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
+            else mma<C, false, false, T, true, MB>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             if (gated) acc_each(acc, [&](int rr, int, float &val) { val *= sGam[32 * m.ua + rr]; }); // o_i = gamma_i o~_i
             acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc);
         }
-        if (m.has_s) mma<C, true, false, T>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
+        if (m.has_s) mma<C, true, false, T, true, MB>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         if (gated) S *= gC; // back from S / gamma to the state itself at the chunk boundary
         lds_barrier();
         // The next chunk's tiles move to LDS here, in the iteration that requested them: the wait the
@@ -382,6 +383,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
+    constexpr int MB = GATED ? 2 : 0; // the gated kernels request operand fragments in smaller batches: they have no registers to spare
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -452,16 +454,16 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         f32x16 acc = zero16();
         if (!loader) { // straight-line, as in the forward scan; the loader waves are busy with global memory meanwhile
             f32x16 pa = zero16(); // P^T = triu(K Q^T), the transposed causal scores, computed as the tile (pni, pmi) of P
-            mma<DK, false, false, T, false>(pa, sQ + 32 * pni * SM::LQ, SM::LQ, sK + 32 * pmi * SM::LK, SM::LK);
+            mma<DK, false, false, T, GATED, MB>(pa, sQ + 32 * pni * SM::LQ, SM::LQ, sK + 32 * pmi * SM::LK, SM::LK);
             if (m.does_u) // K dS' part of the dUt tile (ua, ub)
-                mma<DK, false, false, T, false>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+                mma<DK, false, false, T, GATED, MB>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
             f32x16 w[NWT];
 #pragma unroll
             for (int i = 0; i < NWT; ++i) { // W = T K (Eq. 11), computed as W^T = K^T T^T
                 const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
                 w[i] = zero16();
                 if (Map::W_TILES % 4 == 0 || t < Map::W_TILES)
-                    mma<C, true, false, T, false>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+                    mma<C, true, false, T, GATED, MB>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
             }
             acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r < 32 * pmi + c) val = 0.f; });
             acc_to_lds_t<T>(sPT, SM::LT, 32 * pni, 32 * pmi, pa);
@@ -477,16 +479,16 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
             copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
         }
         if (m.does_u) { // + P^T dO; P^T is upper triangular
-            if (m.ua == 0) mma<C, false, true, T>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
-            else mma<32, false, true, T>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LD + 32 * m.ub, SM::LD);
+            if (m.ua == 0) mma<C, false, true, T, true, MB>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
+            else mma<32, false, true, T, true, MB>(acc, sPT + 32 * SM::LT + 32, SM::LT, sDO + 32 * SM::LD + 32 * m.ub, SM::LD);
             acc_to_lds_t<T>(sDUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
-        if (m.has_s) mma<C, true, true, T>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
+        if (m.has_s) mma<C, true, true, T, true, MB>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         lds_barrier();
         if (loader && ic + 1 < nchunks) flush_dut(ic + 1);
         if (m.has_s) { // - W^T dUt
             f32x16 wd = zero16();
-            mma<C, true, false, T>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
+            mma<C, true, false, T, true, MB>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
             dS -= wd;
         }
         lds_barrier();
@@ -562,10 +564,12 @@ template <typename T, int DK, int DV> struct ChunkSmem {
     static constexpr size_t oB7 = oB6 + align16(szCC);                 // S^T; dS'^T; X
     static constexpr size_t szB7 = cmax(sizeof(T) * DV * LSK, szCC);
     static constexpr size_t oBeta = oB7 + align16(szB7);
-    static constexpr size_t oGi = oBeta + sizeof(float) * C;            // gated: 1 / gamma_i
-    static constexpr size_t oDb = oGi + sizeof(float) * C;
+    static constexpr size_t oGam = oBeta + sizeof(float) * C;          // gated: gamma_i, then 1 / gamma_i
+    static constexpr size_t oDb = oGam + sizeof(float) * 2 * C;
     static constexpr size_t oZ = oDb + sizeof(float) * 4 * C;          // gated: per-wave shares of <dS_C, S_C>
-    static constexpr size_t oStage = align16(oZ + sizeof(float) * NWC);
+    static constexpr size_t oCq = oZ + sizeof(float) * NWC;            // gated: q_i . dq_i per column block of d_k
+    static constexpr size_t oCv = oCq + sizeof(float) * (DK / 32) * C; // gated: v_i . dv_i per column block of d_v
+    static constexpr size_t oStage = align16(oCv + sizeof(float) * (DV / 32) * C);
     static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
 };
 
@@ -586,10 +590,12 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     T *sS = reinterpret_cast<T *>(smem + SM::oB7);
     T *sXn = reinterpret_cast<T *>(smem + SM::oB7); // X = (I + A)^-1 as computed by k_wy_prep
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta);
-    float *sGi = reinterpret_cast<float *>(smem + SM::oGi);
+    float *sGam = reinterpret_cast<float *>(smem + SM::oGam), *sGi = sGam + C;
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
     float *sZ = reinterpret_cast<float *>(smem + SM::oZ);
+    float *sCq = reinterpret_cast<float *>(smem + SM::oCq), *sCv = reinterpret_cast<float *>(smem + SM::oCv);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
+    constexpr int MB = GATED ? 2 : 0; // the gated kernels request operand fragments in smaller batches: they have no registers to spare
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
     const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
@@ -607,8 +613,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         TileRegs<T, C, DK, NTC> k, q;
         TileRegs<T, C, C, NTC> x;
         T beta; // kept in storage format: converting here would wait for the whole prefetch
-        // gated: gamma of this lane's dO rows, 1 / gamma of its V rows, 1 / gamma of row tid
-        float dos[TileRegs<T, C, DV, NTC>::NIT], vsc[TileRegs<T, C, DV, NTC>::NIT], gi;
+        // gated: gamma of this lane's dO rows, 1 / gamma of its V rows; entry tid of the chunk's table of gamma_i, 1 / gamma_i
+        float dos[TileRegs<T, C, DV, NTC>::NIT], vsc[TileRegs<T, C, DV, NTC>::NIT], gm;
     } r;
     auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
         if (!tp.ok) return;
@@ -625,7 +631,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (gated) {
             r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
             r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
-            if (tid < C) r.gi = p.gam[tp.tile * 2 * C + C + tid];
+            if (tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
         }
     };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
@@ -644,23 +650,18 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         const long row0 = cur.row0;
         // ---- adjoint of Eq. 8-9
         // gated: the chunk is the plain rule on v_i / gamma_i with outputs gamma_i o~_i, so dO rows come in
-        // scaled by gamma_i, V rows by 1 / gamma_i, and dV goes out scaled by 1 / gamma_i
-        // gated: this thread's share of <dS_C, S_C> = <dS~', S_0> + <K, Ut dS~'^T>, for the gate gradient
+        // scaled by gamma_i, V rows by 1 / gamma_i, and dV goes out scaled by 1 / gamma_i.
+        // zp: this thread's share of <dS_C, S_C> = <dS~', S_0> + <K, Ut dS~'^T>, for the gate gradient
         float zp = 0.f;
-        if (gated) {
-            zp = r.s.dot(r.ds);
-            r.d_o.scale_rows(r.dos);
-        }
+        if (gated) r.d_o.scale_rows(r.dos);
         r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LU); r.s.store(sS, SM::LSK);
         r.dut.store(sDU, SM::LU); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
-        if (tid < C) {
-            sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
-            if (gated) sGi[tid] = r.gi;
-        }
+        if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
+        if (gated && tid < 2 * C) sGam[tid] = r.gm;
         lds_barrier();
         if (cc) { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
-            if (!upper) mma<DV, false, true, T>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni, SM::LU);
+            if (!upper) mma<DV, false, true, T, true, MB>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni, SM::LU);
             acc_each(acc, [&](int rr, int c, float &val) { if (32 * ni + c > 32 * mi + rr) val = 0.f; });
             acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc);
         }
@@ -669,31 +670,35 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         for (int sI = 0; sI < KW; ++sI) {
             dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
             if (kt(sI) < KT) {
-                mma<DV, false, true, T>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI), SM::LSK); // dO S^T
-                mma<DV, true, true, T>(dw[sI], sDU + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);           // dUt S^T
+                mma<DV, false, true, T, true, MB>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI), SM::LSK); // dO S^T
+                mma<DV, true, true, T, true, MB>(dw[sI], sDU + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);           // dUt S^T
             }
         }
         lds_barrier(); // dP visible; S is dead
+        if (gated) zp = r.ds.dot_lds(sS, SM::LSK); // <dS~', S_0>: each thread meets the S values it parked there itself
         r.ds.store(sS, SM::LSK);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dQ += dP K
-            if (ka(sI) == 0) mma<32, false, true, T>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK);
-            else mma<C, false, true, T>(dq[sI], sDP + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
-            acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI]);
+            if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK);
+            else mma<C, false, true, T, true, MB>(dq[sI], sDP + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
+            if (gated) { // also q_i . dq_i over this tile's columns, for the gate gradient
+                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI]);
+                stage_flush_dot<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sQ, SM::LK,
+                                   sCq + kb(sI) * C);
+            } else {
+                acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI]);
+            }
         }
         lds_barrier();
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
-            if (ka(sI) == 1) mma<32, true, true, T>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK);
-            else mma<C, true, true, T>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK);
-            if (gated) {
-                f32x16 uds = zero16();
-                mma<DV, true, true, T>(uds, sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
-                acc_each(uds, [&](int rr, int c, float &val) { zp += val * to_f32(sK[(32 * ka(sI) + rr) * SM::LK + 32 * kb(sI) + c]); });
-                dk1[sI] += uds;
-            } else {
-                mma<DV, true, true, T>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
+            if (gated) { // <K, Ut dS~'^T>, the second half of <dS_C, S_C>, taken while dK1 holds just that product
+                mma<DV, true, true, T, true, MB>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
+                acc_each(dk1[sI], [&](int rr, int c, float &val) { zp += val * to_f32(sK[(32 * ka(sI) + rr) * SM::LK + 32 * kb(sI) + c]); });
             }
+            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK);
+            else mma<C, true, true, T, true, MB>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK);
+            if (!gated) mma<DV, true, true, T, true, MB>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
         }
         lds_barrier(); // dO, Ut, Q, dP, dS' are dead
         // ---- adjoint of Eq. 10-11
@@ -707,9 +712,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         lds_barrier();
         f32x16 g = zero16(), dxp = zero16();
         if (cc && !upper) {
-            mma<DK, false, false, T>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-            mma<DK, false, false, T>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-            mma<DV, true, false, T>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV);
+            mma<DK, false, false, T, true, MB>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
+            mma<DK, false, false, T, true, MB>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
+            mma<DV, true, false, T, true, MB>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV);
         }
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
         lds_barrier(); // V and dS' are dead
@@ -727,32 +732,38 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         lds_barrier();
         f32x16 m1 = zero16(); // M1 = dX X^T
-        if (cc) mma<C, false, false, T>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
+        if (cc) mma<C, false, false, T, true, MB>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dKb = X^T dW (X^T is upper triangular)
             f32x16 dKb = zero16();
-            if (ka(sI) == 1) mma<32, true, true, T>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb(sI), SM::LK);
-            else mma<C, true, true, T>(dKb, sXn, SM::LT, sDW + 32 * kb(sI), SM::LK);
+            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb(sI), SM::LK);
+            else mma<C, true, true, T, true, MB>(dKb, sXn, SM::LT, sDW + 32 * kb(sI), SM::LK);
             acc_each(dKb, [&](int rr, int, float &val) { val *= sBeta[32 * ka(sI) + rr]; });
             dk1[sI] += dKb; // dK1 + diag(beta) dKb
         }
 #pragma unroll
         for (int sI = 0; sI < VW; ++sI) if (kt(sI) < VT) { // dV = diag(beta) X^T dU
             f32x16 acc = zero16();
-            if (va(sI) == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * vbk(sI) * SM::LU + 32, SM::LU);
-            else mma<C, true, false, T>(acc, sXn, SM::LT, sDU + 32 * vbk(sI) * SM::LU, SM::LU);
+            if (va(sI) == 1) mma<32, true, false, T, true, MB>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * vbk(sI) * SM::LU + 32, SM::LU);
+            else mma<C, true, false, T, true, MB>(acc, sXn, SM::LT, sDU + 32 * vbk(sI) * SM::LU, SM::LU);
             acc_each(acc, [&](int rr, int, float &val) {
                 val *= gated ? sBeta[32 * va(sI) + rr] * sGi[32 * va(sI) + rr] : sBeta[32 * va(sI) + rr];
             });
-            acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
+            if (gated) { // also (v_i / gamma_i) . dv_i over this tile's columns
+                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc);
+                stage_flush_dot<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, sV, SM::LV,
+                                   sCv + vbk(sI) * C);
+            } else {
+                acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
+            }
         }
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
         lds_barrier(); // dX is dead
         if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {
-                if (mi == 1) mma<32, true, false, T>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
-                else mma<C, true, false, T>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
+                if (mi == 1) mma<32, true, false, T, true, MB>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
+                else mma<C, true, false, T, true, MB>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
             }
             const int l31 = lane & 31, hh = lane >> 5;
 #pragma unroll
@@ -772,13 +783,33 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         lds_barrier();
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK = dK1 + diag(beta) dKb + Ah K + Ah^T K; Ah is strictly lower triangular
-            if (ka(sI) == 0) mma<32, false, true, T>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
-            else mma<C, false, true, T>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
-            if (ka(sI) == 1) mma<32, true, true, T>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK);
-            else mma<C, true, true, T>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
+            if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
+            else mma<C, false, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
+            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK);
+            else mma<C, true, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
             acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
         }
-        if (gated && tid == 0) p.zc[cur.tile] = ((sZ[0] + sZ[1]) + (sZ[2] + sZ[3])) + ((sZ[4] + sZ[5]) + (sZ[6] + sZ[7]));
+        if (gated && tid < C) {
+            // Gate gradient.  o_t is linear in q_t and in the state, so the sensitivity to a rescaling of the
+            // state at token j can be read off the other gradients:
+            //     dg_j = <dS_C, S_C> + sum_{i = j .. end of the chunk} (q_i . dq_i - v_i . dv_i).
+            // Thread t takes token C - 1 - t; an inclusive scan over t is the suffix sum over tokens.
+            const int tok = C - 1 - tid;
+            float c = 0.f;
+#pragma unroll
+            for (int b = 0; b < DK / 32; ++b) c += sCq[b * C + tok];
+            float cv = 0.f;
+#pragma unroll
+            for (int b = 0; b < DV / 32; ++b) cv += sCv[b * C + tok];
+            c -= cv * sGam[tok]; // v_i . dv_i = gamma_i (v_i / gamma_i) . dv_i
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const float up = __shfl_up(c, d);
+                if (tid >= d) c += up;
+            }
+            const float z = ((sZ[0] + sZ[1]) + (sZ[2] + sZ[3])) + ((sZ[4] + sZ[5]) + (sZ[6] + sZ[7]));
+            if (tok < nvalid) p.dg[(row0 + tok) * H + h] = c + z;
+        }
         if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G
             const int i = tid >> 2, seg = tid & 3;
             float sum = 0.f;
@@ -790,61 +821,6 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 p.dbeta[(row0 + i) * H + h] = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
         }
         lds_barrier(); // every buffer is free for the next tile
-    }
-}
-
-// =============================================================================================
-// Gradient of the gate (gated variant only).  Because o_t is linear in q_t and in the state, the
-// sensitivity of the loss to a rescaling of the state at time t can be read off the other gradients:
-//     dg_j = <dS_C, S_C> + sum_{i = j .. end of the chunk} (q_i . dq_i - v_i . dv_i)
-// with S_C the state after the chunk and dS_C its gradient.  The chunk kernel leaves <dS_C, S_C> in
-// zc[tile] (from fp32 accumulators); this kernel adds the token terms, one workgroup per (chunk,
-// head): four lanes per token for the two dot products, then a suffix sum over the 64 tokens.
-template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTHR) void k_gate_grad(SeqMap sm, int H, Ptrs p) {
-    constexpr int VEC = El<T>::VEC;
-    __shared__ float sC[C];
-    int n, ic;
-    if (!sm.chunk(blockIdx.x, n, ic)) return;
-    int t0, len, cb;
-    sm.seq(n, t0, len, cb);
-    const int h = blockIdx.y, tid = threadIdx.x, i = tid >> 2, l4 = tid & 3;
-    const int nvalid = min(C, len - ic * C);
-    const long row0 = (long)t0 + (long)ic * C;
-    const long tile = ((long)(cb + ic) * H + h);
-    float s = 0.f;
-    if (i < nvalid) {
-        const long item = (row0 + i) * H + h;
-        const T *q = (const T *)p.q + item * DK, *dq = (const T *)p.dq + item * DK;
-        const T *v = (const T *)p.v + item * DV, *dv = (const T *)p.dv + item * DV;
-        for (int c = l4 * VEC; c < DK; c += 4 * VEC) {
-            alignas(16) T a[VEC], b[VEC];
-            *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(q + c);
-            *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(dq + c);
-#pragma unroll
-            for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
-        }
-        for (int c = l4 * VEC; c < DV; c += 4 * VEC) {
-            alignas(16) T a[VEC], b[VEC];
-            *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(v + c);
-            *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(dv + c);
-#pragma unroll
-            for (int u = 0; u < VEC; ++u) s -= to_f32(a[u]) * to_f32(b[u]);
-        }
-    }
-    s += __shfl_xor(s, 1);
-    s += __shfl_xor(s, 2);
-    if (l4 == 0) sC[i] = s;
-    __syncthreads();
-    if (tid < C) { // suffix sum over the chunk: thread t takes token C - 1 - t, inclusive scan over t
-        float c = sC[C - 1 - tid];
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const float up = __shfl_up(c, d);
-            if (tid >= d) c += up;
-        }
-        const int tok = C - 1 - tid;
-        if (tok < nvalid) p.dg[(row0 + tok) * H + h] = c + p.zc[tile];
     }
 }
 

@@ -75,7 +75,6 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
         if (p.g) DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV, true>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
         else DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV, false>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
     }
-    if (p.g && pb.chunks_ub) DN_LAUNCH((k_gate_grad<T, DK, DV>), gchunk, 0, sm, pb.H, p); // from the gradients just written
     return 0;
 }
 

@@ -79,7 +79,7 @@ template <typename T, int DK> struct RecStage {
     static constexpr int bytes = (oG + TB * 4 + 15) & ~15;              // one buffer of one wave
 };
 
-template <typename T, int DK>
+template <typename T, int DK, bool GATED>
 __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
     using ST = RecStage<T, DK>;
     constexpr int R = DK / 4, TB = ST::TB; // rows per lane; tokens per block
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
                 gv = reinterpret_cast<const uint4 *>((const T *)a.v + ((long)(t0 + tb + tok) * H + h) * DV + col0)[pos];
             if (lane < TB && tb + lane < len) {
                 gb = ((const T *)a.beta)[(long)(t0 + tb + lane) * H + h];
-                if (a.g) ga = __expf(a.g[(long)(t0 + tb + lane) * H + h]);
+                if (GATED) ga = __expf(a.g[(long)(t0 + tb + lane) * H + h]);
             }
         }
     };
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
         if (lane < TB * ST::VROWW) reinterpret_cast<uint4 *>(buf + ST::oV)[lane] = gv;
         if (lane < TB) {
             reinterpret_cast<T *>(buf + ST::oB)[lane] = gb;
-            reinterpret_cast<float *>(buf + ST::oG)[lane] = ga;
+            if (GATED) reinterpret_cast<float *>(buf + ST::oG)[lane] = ga;
         }
     };
 
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
             qr.load(reinterpret_cast<const T *>(cur + ST::oQ) + tt * DK + rb * R);
             const float vt = rec_to_f32(reinterpret_cast<const T *>(cur + ST::oV)[tt * kRecCols + j]);
             const float bt = rec_to_f32(reinterpret_cast<const T *>(cur + ST::oB)[tt]);
-            const float at = reinterpret_cast<const float *>(cur + ST::oG)[tt]; // 1 for the plain rule
+            const float at = GATED ? reinterpret_cast<const float *>(cur + ST::oG)[tt] : 1.f;
             float kf[R], qf[R];
             kr.unpack(kf);
             qr.unpack(qf);
@@ -178,10 +178,11 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
             float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f; // S_t^T q_t, read-out from the updated state
 #pragma unroll
             for (int r = 0; r < R; r += 4) {
-                S[r] = fmaf(kf[r], u, keep * S[r]); o0 = fmaf(S[r], qf[r], o0);
-                S[r + 1] = fmaf(kf[r + 1], u, keep * S[r + 1]); o1 = fmaf(S[r + 1], qf[r + 1], o1);
-                S[r + 2] = fmaf(kf[r + 2], u, keep * S[r + 2]); o2 = fmaf(S[r + 2], qf[r + 2], o2);
-                S[r + 3] = fmaf(kf[r + 3], u, keep * S[r + 3]); o3 = fmaf(S[r + 3], qf[r + 3], o3);
+                if (GATED) { S[r] *= keep; S[r + 1] *= keep; S[r + 2] *= keep; S[r + 3] *= keep; }
+                S[r] = fmaf(kf[r], u, S[r]); o0 = fmaf(S[r], qf[r], o0);
+                S[r + 1] = fmaf(kf[r + 1], u, S[r + 1]); o1 = fmaf(S[r + 1], qf[r + 1], o1);
+                S[r + 2] = fmaf(kf[r + 2], u, S[r + 2]); o2 = fmaf(S[r + 2], qf[r + 2], o2);
+                S[r + 3] = fmaf(kf[r + 3], u, S[r + 3]); o3 = fmaf(S[r + 3], qf[r + 3], o3);
             }
             const float out = rec_sum4((o0 + o1) + (o2 + o3));
             if (rb == 0 && live) rec_store(op, out);
@@ -204,7 +205,8 @@ template <typename T, int DK> static int launch_rec(const RecArgs &a, hipStream_
     constexpr int lds = 4 * 2 * RecStage<T, DK>::bytes; // four waves, two buffers each
     static_assert(lds <= 64 * 1024, "staging fits the default LDS limit");
     prof_begin("k_recurrent_fwd", stream);
-    hipLaunchKernelGGL((k_recurrent_fwd<T, DK>), grid, dim3(256), lds, stream, a);
+    if (a.g) hipLaunchKernelGGL((k_recurrent_fwd<T, DK, true>), grid, dim3(256), lds, stream, a);
+    else hipLaunchKernelGGL((k_recurrent_fwd<T, DK, false>), grid, dim3(256), lds, stream, a);
     prof_end(stream);
     return (int)hipGetLastError();
 }

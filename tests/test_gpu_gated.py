@@ -55,9 +55,10 @@ def test_zero_gate_equals_the_plain_path_on_the_gpu():
     out_g = dn.deltanet_gated_bwd(d["q"], d["k"], d["v"], d["beta"], g0, d["d_o"], d["S0"], d["dST"])
     out_p = dn.deltanet_bwd(d["q"], d["k"], d["v"], d["beta"], d["d_o"], d["S0"], d["dST"])
     torch.cuda.synchronize()
-    assert torch.equal(o_g, o_p) and torch.equal(S_g, S_p)
+    assert torch.equal(o_g, o_p) and torch.equal(S_g, S_p)  # the forward kernels do the same arithmetic in the same order
+    # the gated backward sums some products in another order, so its results agree to output rounding
     for a, b in zip((out_g[0], out_g[1], out_g[2], out_g[3], out_g[5]), out_p):
-        assert torch.equal(a, b)
+        assert nerr(a.float().cpu().numpy(), b.float().cpu().numpy()) < 4e-3
 
 
 @pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 48), ("bf16", 128, 128), ("bf16", 256, 64)])

@@ -75,6 +75,18 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     assert lib.deltanet_recurrent_fwd(ctypes.byref(s), odd, fake, fake, fake, None, fake, None, None) == -4
     assert lib.deltanet_recurrent_fwd(ctypes.byref(_shape(d_k=96)), *rargs) == -3
     assert lib.deltanet_recurrent_fwd(ctypes.byref(_shape(d_v=72)), *rargs) == -3
+    # gated entry points: g (and dg in the backward) are required, same checks otherwise
+    gout = ctypes.c_size_t(0)
+    assert lib.deltanet_gated_workspace_bytes(ctypes.byref(s), 1, ctypes.byref(gout)) == 0
+    plain = ctypes.c_size_t(0)
+    assert lib.deltanet_workspace_bytes(ctypes.byref(s), 1, ctypes.byref(plain)) == 0
+    assert gout.value > plain.value  # the per-chunk decay table rides along
+    assert lib.deltanet_gated_fwd(ctypes.byref(s), fake, fake, fake, fake, None, None, fake, None, fake, 1 << 40, None) == -1
+    assert lib.deltanet_gated_fwd(ctypes.byref(s), fake, fake, fake, fake, odd, None, fake, None, fake, 1 << 40, None) == -4
+    assert lib.deltanet_gated_fwd(ctypes.byref(s), fake, fake, fake, fake, fake, None, fake, None, fake, 16, None) == -5
+    gb = [fake] * 5 + [None, fake, None, fake, fake, fake, fake, None, None]  # dg missing
+    assert lib.deltanet_gated_bwd(ctypes.byref(s), *gb, fake, 1 << 40, None) == -1
+    assert lib.deltanet_gated_recurrent_fwd(ctypes.byref(s), fake, fake, fake, fake, None, None, fake, None, None) == -1
     bargs = [fake] * 4 + [None, fake, None, fake, fake, fake, fake, None]
     assert lib.deltanet_bwd(ctypes.byref(s), *bargs, fake, 16, None) == -5
     bargs[10] = None  # dbeta is required

@@ -57,6 +57,8 @@ const Impl kImpls[] = {
     DN_IMPL(DN_F32, float, 64, 64),     DN_IMPL(DN_F32, float, 32, 64),    DN_IMPL(DN_F32, float, 64, 32),
     DN_IMPL(DN_BF16, bf16_t, 128, 128), DN_IMPL(DN_BF16, bf16_t, 64, 64),
     DN_IMPL(DN_BF16, bf16_t, 64, 128),  DN_IMPL(DN_BF16, bf16_t, 128, 64),
+    // forward only: the backward's chunk tiles do not fit the LDS at this head size
+    { DN_BF16, 256, 256, &run_fwd<bf16_t, 256, 256>, nullptr, &max_lds_fwd_bytes<bf16_t, 256, 256> },
 };
 
 const Impl *find_impl(const dn_shape *s) {
@@ -175,6 +177,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
              void *hip_stream) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
+    if (!impl->bwd) return DN_ERR_UNSUPPORTED;
     if (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta || (gated && (!g || !dg))) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
                         workspace, shape->cu_seqlens};
@@ -200,6 +203,7 @@ int deltanet_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_by
     if (!out_bytes) return DN_ERR_NULL;
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
+    if (want_bwd && !impl->bwd) return DN_ERR_UNSUPPORTED;
     Plan pl;
     make_plan(shape, want_bwd, &pl);
     *out_bytes = pl.total;
@@ -224,6 +228,7 @@ int deltanet_gated_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *
     if (!out_bytes) return DN_ERR_NULL;
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
+    if (want_bwd && !impl->bwd) return DN_ERR_UNSUPPORTED;
     Plan pl;
     make_plan(shape, want_bwd, &pl, true);
     *out_bytes = pl.total;

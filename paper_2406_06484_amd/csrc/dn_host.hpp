@@ -41,6 +41,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
 template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p);
 // largest dynamic LDS any kernel of this instantiation needs
 template <typename T, int DK, int DV> size_t max_lds_bytes();
+template <typename T, int DK, int DV> size_t max_lds_fwd_bytes(); // prep and forward scan only
 
 // Token-serial forward (dn_recurrent.hip).  dtype: 0 = fp32, 1 = bf16.  Returns 0, a hipError_t
 // (> 0), or -1 when (dtype, d_k) has no compiled kernel.  d_v must be a multiple of 16.

@@ -129,9 +129,10 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
 // Workgroup ids are laid out so that the v-blocks of one chain land on the same XCD (ids are dealt
 // round-robin over the 8 XCDs) and share its L2 for the Q, K, T tiles they both read.
 constexpr int NTS = 512, NWS = 8, NTL = 256; // threads / waves of a scan workgroup; loader threads
-// bf16 workgroups own 64 state columns; fp32 ones 32, so that the fp32 tiles still fit the 160 KB of LDS
-template <typename T, int DV> struct VBlock {
-    static constexpr int WANT = sizeof(T) == 2 ? 64 : 32;
+// bf16 workgroups own 64 state columns; fp32 ones, and bf16 ones with d_k = 256, own 32, so that the
+// tiles (whose rows are d_k long) still fit the 160 KB of LDS
+template <typename T, int DV, int DK> struct VBlock {
+    static constexpr int WANT = (sizeof(T) == 2 && DK <= 128) ? 64 : 32;
     static constexpr int BV = DV < WANT ? DV : WANT;
     static constexpr int NV = DV / BV;
 };
@@ -149,7 +150,7 @@ __host__ inline int chain_grid(int nchains, int nv) { return ((nchains + 7) / 8)
 // own the tile of O (forward) of the same shape.
 template <int DK, int BV> struct ScanMap {
     static constexpr int NVT = BV / 32, NKT = DK / 32, S_TILES = NKT * NVT, U_TILES = 2 * NVT, W_TILES = 2 * NKT;
-    static_assert(S_TILES <= NWS && U_TILES <= 4 && W_TILES <= NWS, "state tiling");
+    static_assert(S_TILES <= NWS && U_TILES <= 4, "state tiling");
     int sa, sb, ua, ub;
     bool has_s, does_u, does_o;
     __device__ ScanMap(int wave) {
@@ -163,7 +164,7 @@ template <int DK, int BV> struct ScanMap {
 // scan_fwd_body: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
 // writes every chunk-initial state and Ut to the workspace instead of O.
 template <typename T, int DK, int DV> struct ScanFwdSmem {
-    static constexpr int BV = VBlock<T, DV>::BV;
+    static constexpr int BV = VBlock<T, DV, DK>::BV;
     static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LV = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
@@ -175,7 +176,7 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oT = oUT + 2 * szUT;
     static constexpr size_t oP = oT + align16(sizeof(T) * C * LT);
     static constexpr size_t oStage = oP + align16(sizeof(T) * C * LT); // per-wave output staging tiles
-    static constexpr int NSTG = 4; // only the four output waves stage tiles
+    static constexpr int NSTG = ScanMap<DK, BV>::U_TILES; // only the output waves stage tiles
     static constexpr size_t oGam = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS; // gated: gamma_i, 1 / gamma_i of the chunk
     static constexpr size_t bytes = oGam + sizeof(float) * 2 * C;
 };
@@ -183,7 +184,7 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
 template <typename T, int DK, int DV, bool STORE, bool GATED>
 __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanFwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
+    constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
     constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
     extern __shared__ __align__(16) unsigned char smem[];
@@ -198,7 +199,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     T *sP = reinterpret_cast<T *>(smem + SM::oP);
     float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
-    constexpr int MB = GATED ? 2 : 0; // the gated kernels request operand fragments in smaller batches: they have no registers to spare
+    // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
+    constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -286,22 +288,29 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             // Straight-line on purpose (full contraction length even where T's zero block makes half
             // of it idle, a masked all-zero P tile on wave 3): independent products in one basic
             // block are what lets the scheduler overlap one product's LDS and MFMA latency with the next.
+            // (with more than two W tiles per wave, d_k = 256, the tiles are finished one at a time instead:
+            // there are not enough registers to keep them all in flight)
+            constexpr bool SEQ = GATED || NWT > 2;
             f32x16 w[NWT];
 #pragma unroll
             for (int i = 0; i < NWT; ++i) { // W = T K (Eq. 11) as W^T = K^T T^T
                 const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
                 w[i] = zero16();
-                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES)
-                    mma<C, true, false, T, GATED, MB>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) {
+                    mma<C, true, false, T, SEQ, MB>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+                    if (NWT > 2) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
+                }
             }
-            if (m.does_u) mma<C, false, true, T, GATED, MB>(acc, sT + 32 * m.ua * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV); // U = T V
+            if (m.does_u) mma<C, false, true, T, SEQ, MB>(acc, sT + 32 * m.ua * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV); // U = T V
             f32x16 pa = zero16();
             if (!STORE) // P = tril(Q K^T), the causal intra-chunk scores of Eq. 9, as the tile (pni, pmi) of P^T
-                mma<DK, false, false, T, GATED, MB>(pa, sK + 32 * pni * SM::LK, SM::LK, sQ + 32 * pmi * SM::LQ, SM::LQ);
+                mma<DK, false, false, T, SEQ, MB>(pa, sK + 32 * pni * SM::LK, SM::LK, sQ + 32 * pmi * SM::LQ, SM::LQ);
+            if (NWT <= 2) {
 #pragma unroll
-            for (int i = 0; i < NWT; ++i) {
-                const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
-                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
+                for (int i = 0; i < NWT; ++i) {
+                    const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
+                    if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
+                }
             }
             if (!STORE) {
                 acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r > 32 * pmi + c) val = 0.f; });
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
 //   dUt = P^T dO + K dS';  dS = dS' + Q^T dO - W^T dUt
 // Per chunk it leaves dS'^T and dUt^T in the workspace (the transposed LDS copies, written out by the loader waves).
 template <typename T, int DK, int DV> struct ScanBwdSmem {
-    static constexpr int BV = VBlock<T, DV>::BV;
+    static constexpr int BV = VBlock<T, DV, DK>::BV;
     static constexpr int LQ = ldn<T>(DK), LK = ldn<T>(DK), LD = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
     static constexpr size_t oQ = 0;
     static constexpr size_t oK = oQ + align16(sizeof(T) * C * LQ);
@@ -370,7 +379,7 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
 template <typename T, int DK, int DV, bool GATED>
 __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanBwdSmem<T, DK, DV>;
-    constexpr int BV = SM::BV, NV = VBlock<T, DV>::NV;
+    constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
     constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
     extern __shared__ __align__(16) unsigned char smem[];
@@ -383,7 +392,8 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
-    constexpr int MB = GATED ? 2 : 0; // the gated kernels request operand fragments in smaller batches: they have no registers to spare
+    // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
+    constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -595,7 +605,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     float *sZ = reinterpret_cast<float *>(smem + SM::oZ);
     float *sCq = reinterpret_cast<float *>(smem + SM::oCq), *sCv = reinterpret_cast<float *>(smem + SM::oCv);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
-    constexpr int MB = GATED ? 2 : 0; // the gated kernels request operand fragments in smaller batches: they have no registers to spare
+    // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
+    constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
     const bool cc = wave < 4, upper = (mi == 0 && ni == 1);

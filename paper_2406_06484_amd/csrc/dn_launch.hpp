@@ -46,11 +46,18 @@ template <typename T, int DK, int DV> size_t max_lds_bytes() {
     return m;
 }
 
+// forward-only instantiations (head sizes whose backward tiles do not fit)
+template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
+    static_assert(PrepSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_wy_prep LDS");
+    static_assert(ScanFwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_fwd LDS");
+    return PrepSmem<T, DK, DV>::bytes > ScanFwdSmem<T, DK, DV>::bytes ? PrepSmem<T, DK, DV>::bytes : ScanFwdSmem<T, DK, DV>::bytes;
+}
+
 template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0 || pb.chunks_ub == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
     if (p.g) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     else DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
@@ -61,7 +68,7 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (pb.N == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV>::NV));
+    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
     { // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
@@ -78,6 +85,9 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     return 0;
 }
 
+#define DN_INSTANTIATE_FWD(T, DK, DV)                                    \
+    template int run_fwd<T, DK, DV>(const Problem &, const Ptrs &);      \
+    template size_t max_lds_fwd_bytes<T, DK, DV>();
 #define DN_INSTANTIATE(T, DK, DV)                                        \
     template int run_fwd<T, DK, DV>(const Problem &, const Ptrs &);      \
     template int run_bwd<T, DK, DV>(const Problem &, const Ptrs &);      \

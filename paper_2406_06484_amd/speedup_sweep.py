@@ -4,8 +4,8 @@
 The workload is the one of the paper's speed-up figure (section 3.3): model width 2048 split into
 heads of size d (H = 2048 / d), batch times length fixed at 16384 tokens, bf16, random unit-norm
 q, k.  For each (d, L) it times the forward pass of both forms through the C ABI (and the chunkwise
-forward + backward) and prints one table row; the chunkwise path is compiled for d = 64 and 128,
-the recurrent form also for d = 256.
+forward + backward) and prints one table row; the chunkwise backward is compiled for d = 64 and
+128, the forward passes also for d = 256.
 
     python -m paper_2406_06484_amd.speedup_sweep [--steps 20]
 """
@@ -57,9 +57,9 @@ def main() -> int:
             o = torch.empty_like(v)
             ST = torch.empty(B, H, d, d, dtype=torch.float32, device=dev)
             t_rec = timeit(lambda: dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST))
+            ws = torch.empty(deltanet_workspace_bytes(_shape_of(q, v, None, 64, []), d <= 128), dtype=torch.uint8, device=dev)
+            t_chk = timeit(lambda: dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws))
             if d <= 128:
-                ws = torch.empty(deltanet_workspace_bytes(_shape_of(q, v, None, 64, []), True), dtype=torch.uint8, device=dev)
-                t_chk = timeit(lambda: dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws))
 
                 def both():
                     dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
@@ -67,7 +67,7 @@ def main() -> int:
                 t_fb = timeit(both)
                 print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %14.3f" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, t_fb), flush=True)
             else:
-                print("%5d %6d %4d %4d | %12.3f %12s %9s | %14s" % (d, L, B, H, t_rec, "-", "-", "-"), flush=True)
+                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %14s" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, "-"), flush=True)
     return 0
 
 

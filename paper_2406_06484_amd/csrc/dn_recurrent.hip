@@ -18,7 +18,8 @@
 // Global latency (longer than a token takes) is hidden by staging: the wave fetches q, k, v, beta
 // for a block of TB tokens with coalesced 16-byte loads, parks them in its private slice of LDS
 // (two buffers), and works through the previous block meanwhile; all 16 lanes of a row quarter read
-// the same k and q words from LDS (a broadcast, no bank conflict).
+// the same k and q words from LDS (a broadcast, no bank conflict).  k and q are expanded to fp32 once,
+// when the wave parks them, not by every one of the 16 column lanes that read them.
 #include "dn_host.hpp"
 
 namespace dn {
@@ -74,7 +75,8 @@ template <typename T, int DK> struct RecStage {
     static constexpr int NKW = TB * ROWW / 64;                        // k (or q) words per lane and block
     static constexpr int VROWW = kRecCols * (int)sizeof(T) / 16;      // 16-byte words of one token's v slice
     static_assert(TB >= 1 && TB * ROWW % 64 == 0 && TB * VROWW <= 64, "staging layout");
-    static constexpr int oK = 0, oQ = TB * ROWB, oV = 2 * TB * ROWB, oB = oV + TB * kRecCols * (int)sizeof(T);
+    static constexpr int ROWF = DK * 4;                               // k and q rows are parked as fp32
+    static constexpr int oK = 0, oQ = TB * ROWF, oV = 2 * TB * ROWF, oB = oV + TB * kRecCols * (int)sizeof(T);
     static constexpr int oG = (oB + TB * (int)sizeof(T) + 3) & ~3;      // gated: alpha_t = exp(g_t), fp32
     static constexpr int bytes = (oG + TB * 4 + 15) & ~15;              // one buffer of one wave
 };
@@ -135,8 +137,18 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
     auto park = [&](unsigned char *buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < ST::NKW; ++i) {
-            reinterpret_cast<uint4 *>(buf + ST::oK)[i * 64 + lane] = gk[i];
-            reinterpret_cast<uint4 *>(buf + ST::oQ)[i * 64 + lane] = gq[i];
+            constexpr int EPW = 16 / (int)sizeof(T); // elements per 16-byte word
+            float fk[EPW], fq[EPW];
+            RowRegs<T, EPW> wk, wq;
+            wk.w[0] = gk[i]; wq.w[0] = gq[i];
+            wk.unpack(fk); wq.unpack(fq);
+            float *dk_ = reinterpret_cast<float *>(buf + ST::oK) + (i * 64 + lane) * EPW;
+            float *dq_ = reinterpret_cast<float *>(buf + ST::oQ) + (i * 64 + lane) * EPW;
+#pragma unroll
+            for (int e = 0; e < EPW; e += 4) {
+                *reinterpret_cast<float4 *>(dk_ + e) = make_float4(fk[e], fk[e + 1], fk[e + 2], fk[e + 3]);
+                *reinterpret_cast<float4 *>(dq_ + e) = make_float4(fq[e], fq[e + 1], fq[e + 2], fq[e + 3]);
+            }
         }
         if (lane < TB * ST::VROWW) reinterpret_cast<uint4 *>(buf + ST::oV)[lane] = gv;
         if (lane < TB) {
@@ -158,9 +170,9 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
 #pragma unroll
         for (int tt = 0; tt < TB; ++tt) {
             const bool live = tt < nt;
-            RowRegs<T, R> kr, qr;
-            kr.load(reinterpret_cast<const T *>(cur + ST::oK) + tt * DK + rb * R);
-            qr.load(reinterpret_cast<const T *>(cur + ST::oQ) + tt * DK + rb * R);
+            RowRegs<float, R> kr, qr;
+            kr.load(reinterpret_cast<const float *>(cur + ST::oK) + tt * DK + rb * R);
+            qr.load(reinterpret_cast<const float *>(cur + ST::oQ) + tt * DK + rb * R);
             const float vt = rec_to_f32(reinterpret_cast<const T *>(cur + ST::oV)[tt * kRecCols + j]);
             const float bt = rec_to_f32(reinterpret_cast<const T *>(cur + ST::oB)[tt]);
             const float at = GATED ? reinterpret_cast<const float *>(cur + ST::oG)[tt] : 1.f;
@@ -203,7 +215,9 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
 template <typename T, int DK> static int launch_rec(const RecArgs &a, hipStream_t stream) {
     const dim3 grid(a.N * a.H, (a.DV + 4 * kRecCols - 1) / (4 * kRecCols));
     constexpr int lds = 4 * 2 * RecStage<T, DK>::bytes; // four waves, two buffers each
-    static_assert(lds <= 64 * 1024, "staging fits the default LDS limit");
+    static_assert(lds <= 160 * 1024, "staging fits the LDS");
+    if (a.g) (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_recurrent_fwd<T, DK, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    else (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_recurrent_fwd<T, DK, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     prof_begin("k_recurrent_fwd", stream);
     if (a.g) hipLaunchKernelGGL((k_recurrent_fwd<T, DK, true>), grid, dim3(256), lds, stream, a);
     else hipLaunchKernelGGL((k_recurrent_fwd<T, DK, false>), grid, dim3(256), lds, stream, a);

@@ -1,10 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the DeltaNet layer hot path on one MI355X.
 
-A "step" is one forward plus one backward pass of the layer (deltanet_fwd + deltanet_bwd through
-the C ABI) over one batch of synthetic input shaped like the paper's 1.3B-model layers:
-bf16, B=8, L=2048, H=16, d_k=d_v=128, chunk 64.  Inputs are resident in HBM before the timed
-region.  Prints ONE JSON line: tokens/s of the layer (B*L tokens per step), the dominant kernel's
+A "step" is one forward plus one backward pass of the layer over one batch of synthetic input shaped
+like the paper's 1.3B-model layers: bf16, B=8, L=2048, H=16, d_k=d_v=128, chunk 64, through the C ABI
+as a training step calls it: deltanet_fwd_save, which leaves its per-chunk tiles in a buffer, then
+deltanet_bwd_saved, which reads them instead of recomputing them.  The self-contained pair
+(deltanet_fwd + deltanet_bwd, backward recomputes everything from the inputs) is timed beside it and
+reported as "recompute_fwd_bwd".  Inputs are resident in HBM before the timed region.  Prints ONE JSON line: tokens/s of the layer (B*L tokens per step), the dominant kernel's
 roofline position (per-kernel time from HIP events recorded by the library on the launch stream),
 and the fp64 CPU oracle timed on the host cores as a reported baseline.
 """
@@ -36,6 +38,10 @@ def kernel_flops_per_chunk_head(name: str, d: int, c: int = C) -> float:
     """Dense-tile FLOPs one (chunk, head) costs in each kernel (what that kernel contracts)."""
     if "k_wy_prep" in name:      # K K^T, forward substitution
         return 2 * c * c * d + (2.0 / 3.0) * c ** 3
+    if "k_scan_fwd_save" in name:  # as k_scan_fwd
+        return 6 * c * d * d + 8 * c * c * d
+    if "k_scan_bwd" in name:     # T K, K Q^T, P^T dO (3 x 2C^2 d); K dS, Q^T dO, W^T dUt (3 x 2Cd^2)
+        return 6 * c * d * d + 6 * c * c * d
     if "k_scan_pair" in name:    # recompute scan: T K, T V, W S, K^T Ut; reverse scan: T K, K Q^T, P^T dO, K dS, Q^T dO, W^T dUt
         return (4 * c * d * d + 4 * c * c * d) + (6 * c * d * d + 6 * c * c * d)
     if "k_scan_fwd" in name:     # T K, T V, Q K^T, P Ut (4 x 2C^2 d); W S, Q S, K^T Ut (3 x 2Cd^2)
@@ -55,6 +61,10 @@ def kernel_bytes_per_chunk_head(name: str, d: int, c: int = C, es: int = 2) -> f
     tile, cc, st, beta = c * d * es, c * c * es, d * d * es, c * es
     if "k_wy_prep" in name:      # mean of its two launches: K, beta -> T (forward) / T, X (backward)
         return tile + beta + 1.5 * cc
+    if "k_scan_fwd_save" in name:  # Q, K, V, T -> O, Ut, S
+        return 3 * tile + cc + 2 * tile + st
+    if "k_scan_bwd" in name:     # Q, K, dO, T -> dUt, dS'
+        return 3 * tile + cc + tile + st
     if "k_scan_pair" in name:    # K, V, T -> Ut, S   and   Q, K, dO, T -> dUt, dS'
         return (2 * tile + cc + tile + st) + (3 * tile + cc + tile + st)
     if "k_scan_fwd" in name:     # Q, K, V, T -> O
@@ -70,6 +80,8 @@ def kernel_bytes_per_chunk_head(name: str, d: int, c: int = C, es: int = 2) -> f
 # inside this script, so the figures are carried here and refreshed whenever the kernels change.
 MEASURED_HBM_BYTES = {
     "k_wy_prep": 119.8e6,
+    "k_scan_fwd_save": None,
+    "k_scan_bwd": None,
     "k_scan_fwd": 310.5e6,
     "k_scan_pair": 814.6e6,
     "k_bwd_chunk": 919.2e6,
@@ -121,7 +133,11 @@ def main() -> int:
     o = torch.empty_like(v)
     ST = torch.empty((B, H, d, d), dtype=torch.float32, device=dev)
 
-    def step():
+    def step():   # the training step: the forward pass leaves its per-chunk tiles in ws for the backward pass
+        dn.deltanet_fwd_save(q, k, v, beta, o=o, final_state=ST, saved=ws)
+        return dn.deltanet_bwd_saved(q, k, v, beta, d_o, ws)
+
+    def recompute_step():   # the self-contained pair: nothing is kept between the two calls
         dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
         return dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
 
@@ -147,8 +163,8 @@ def main() -> int:
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     fw = bw = 0.0
     for _ in range(args.steps):
-        ev[0].record(); dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
-        ev[1].record(); dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
+        ev[0].record(); dn.deltanet_fwd_save(q, k, v, beta, o=o, final_state=ST, saved=ws)
+        ev[1].record(); dn.deltanet_bwd_saved(q, k, v, beta, d_o, ws)
         ev[2].record(); torch.cuda.synchronize()
         fw += ev[0].elapsed_time(ev[1]); bw += ev[1].elapsed_time(ev[2])
     fw /= args.steps; bw /= args.steps
@@ -186,7 +202,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[2]: bf16 fwd+bwd, B=8, L=2048, H=16, d_k=d_v=128, chunk=64",
+        "config": {"workload": "configs[2]: bf16 fwd+bwd, B=8, L=2048, H=16, d_k=d_v=128, chunk=64; the forward pass keeps its per-chunk tiles for the backward pass",
                    "tokens_per_step": tokens},
         "fwd_ms": round(fw, 4), "bwd_ms": round(bw, 4),
         "model_tflops": round(model_tflops, 2),
@@ -195,6 +211,27 @@ def main() -> int:
         "kernels": kernels,
         "roofline": roofline,
     }
+
+    # The self-contained pair on the same workload (the backward pass recomputes T, X, the chunk states and
+    # Ut from the inputs, as the paper's implementation does), with its own per-kernel times.
+    for _ in range(args.warmup):
+        recompute_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        recompute_step()
+    torch.cuda.synchronize()
+    rms = 1e3 * (time.perf_counter() - t0) / args.steps
+    dn.deltanet_profile_enable(True)
+    for _ in range(args.steps):
+        recompute_step()
+    torch.cuda.synchronize()
+    rprof = dn.deltanet_profile_collect()
+    dn.deltanet_profile_enable(False)
+    out["recompute_fwd_bwd"] = {
+        "ms_per_step": round(rms, 4), "tokens_per_s": round(tokens / (rms * 1e-3), 1), "steps": args.steps,
+        "kernels": {name.strip("()"): {"avg_ms": round(ms / n, 4), "launches_per_step": n // args.steps}
+                    for name, (ms, n) in rprof.items()}}
 
     # The same forward in the recurrent (token-serial) form, the baseline the paper times the chunkwise
     # form against; vector-ALU bound: 3 fused multiply-adds per state element per token.
@@ -207,9 +244,14 @@ def main() -> int:
         dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST)
     torch.cuda.synchronize()
     rec_ms = 1e3 * (time.perf_counter() - t0) / rec_steps
+    t0 = time.perf_counter()
+    for _ in range(rec_steps):
+        dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
+    torch.cuda.synchronize()
+    cfw = 1e3 * (time.perf_counter() - t0) / rec_steps
     rec_tflops = 6.0 * d * d * H * tokens / (rec_ms * 1e-3) / 1e12
     out["recurrent_fwd"] = {"ms": round(rec_ms, 4), "tokens_per_s": round(tokens / (rec_ms * 1e-3), 1), "steps": rec_steps,
-                            "chunkwise_fwd_ms": round(fw, 4), "chunkwise_speedup": round(rec_ms / fw, 2),
+                            "chunkwise_fwd_ms": round(cfw, 4), "chunkwise_speedup": round(rec_ms / cfw, 2),
                             "roofline": {"bound": "alu", "achieved": round(rec_tflops, 2), "peak": PEAK_FP32_VECTOR_TFLOPS,
                                          "unit": "TFLOP/s", "frac": round(rec_tflops / PEAK_FP32_VECTOR_TFLOPS, 4),
                                          "traffic": measured_traffic("k_recurrent_fwd")}}
@@ -222,8 +264,8 @@ def main() -> int:
     wsg = torch.empty(deltanet_gated_workspace_bytes(shp, True), dtype=torch.uint8, device=dev)
 
     def gated_step():
-        dn.deltanet_gated_fwd(q, k, v, beta, g, o=o, final_state=ST, workspace=wsg)
-        return dn.deltanet_gated_bwd(q, k, v, beta, g, d_o, workspace=wsg)
+        dn.deltanet_gated_fwd_save(q, k, v, beta, g, o=o, final_state=ST, saved=wsg)
+        return dn.deltanet_gated_bwd_saved(q, k, v, beta, g, d_o, wsg)
     for _ in range(3):
         gated_step()
     torch.cuda.synchronize()

@@ -93,6 +93,27 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
                  size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same forward and backward pass for a training step that keeps the forward pass's per-chunk
+ * results instead of recomputing them (the other side of the trade section 3.2 describes: with
+ * hundreds of GB of HBM the chunk states of a layer, d_k * d_v * 2 bytes per 64 tokens and head in
+ * bf16, are cheap to keep, and the backward pass then skips the UT transform and the forward scan).
+ * deltanet_fwd_save computes what deltanet_fwd computes and leaves T and (I + A)^-1 of Eq. 10, the
+ * chunk-initial states and U - W S of Eq. 8 in `saved`; deltanet_bwd_saved computes what deltanet_bwd
+ * computes from the same q, k, v, beta and that buffer, which it also uses as scratch (afterwards the
+ * buffer can serve another deltanet_fwd_save, not another deltanet_bwd_saved).  `saved` is
+ * caller-provided device memory of deltanet_workspace_bytes(shape, 1) bytes; its layout is private to
+ * the library, and it must stay untouched between the two calls.  The initial state is not an argument
+ * of deltanet_bwd_saved: it is the first saved chunk state.  Everything else is as for deltanet_fwd /
+ * deltanet_bwd; head sizes without a backward pass return DN_ERR_UNSUPPORTED.
+ */
+int deltanet_fwd_save(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                      const float *initial_state, void *o, float *final_state, void *saved, size_t saved_bytes,
+                      void *hip_stream);
+int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                       const void *d_o, const float *dfinal_state, void *dq, void *dk, void *dv, float *dbeta,
+                       float *dinitial_state, void *saved, size_t saved_bytes, void *hip_stream);
+
+/*
  * Forward pass in the recurrent (token-serial) form: the delta-rule update and read-out of
  * section 2.2 applied one token after the other, state in fp32 registers, no chunking, no matrix
  * cores and no workspace.  It computes the same o and final_state as deltanet_fwd (fp32 arithmetic
@@ -134,6 +155,15 @@ int deltanet_gated_bwd(const dn_shape *shape, const void *q, const void *k, cons
 int deltanet_gated_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, const void *v,
                                  const void *beta, const float *g, const float *initial_state, void *o,
                                  float *final_state, void *hip_stream);
+/* The gated pair that keeps the forward pass's per-chunk results, as deltanet_fwd_save / deltanet_bwd_saved;
+ * `saved` holds deltanet_gated_workspace_bytes(shape, 1) bytes. */
+int deltanet_gated_fwd_save(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                            const float *g, const float *initial_state, void *o, float *final_state, void *saved,
+                            size_t saved_bytes, void *hip_stream);
+int deltanet_gated_bwd_saved(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                             const float *g, const void *d_o, const float *dfinal_state, void *dq, void *dk, void *dv,
+                             float *dbeta, float *dg, float *dinitial_state, void *saved, size_t saved_bytes,
+                             void *hip_stream);
 
 /*
  * Measurement aid (not part of the method): per-kernel device time.  After

@@ -7,9 +7,13 @@ library has not been built, calling them raises.
 from .binding import (  # noqa: F401
     DeltaNetError,
     deltanet_bwd,
+    deltanet_bwd_saved,
     deltanet_fwd,
+    deltanet_fwd_save,
     deltanet_gated_bwd,
+    deltanet_gated_bwd_saved,
     deltanet_gated_fwd,
+    deltanet_gated_fwd_save,
     deltanet_gated_recurrent_fwd,
     deltanet_gated_workspace_bytes,
     deltanet_profile_collect,

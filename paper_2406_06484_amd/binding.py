@@ -56,6 +56,14 @@ def load_library():
         lib.deltanet_fwd.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
         lib.deltanet_bwd.restype = ctypes.c_int
         lib.deltanet_bwd.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
+        lib.deltanet_fwd_save.restype = ctypes.c_int
+        lib.deltanet_fwd_save.argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
+        lib.deltanet_bwd_saved.restype = ctypes.c_int
+        lib.deltanet_bwd_saved.argtypes = [sp] + [vp] * 11 + [vp, sz, vp]
+        lib.deltanet_gated_fwd_save.restype = ctypes.c_int
+        lib.deltanet_gated_fwd_save.argtypes = [sp] + [vp] * 8 + [vp, sz, vp]
+        lib.deltanet_gated_bwd_saved.restype = ctypes.c_int
+        lib.deltanet_gated_bwd_saved.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
         lib.deltanet_recurrent_fwd.restype = ctypes.c_int
         lib.deltanet_recurrent_fwd.argtypes = [sp] + [vp] * 7 + [vp]
         lib.deltanet_gated_workspace_bytes.restype = ctypes.c_int
@@ -174,7 +182,7 @@ def _workspace(shape, want_bwd, workspace, device, gated=False):
 
 def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: int = 64,
                  output_final_state: bool = True, o=None, final_state=None, workspace=None,
-                 stream=None, _g=None) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
+                 stream=None, _g=None, _save=False) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
     """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None)."""
     import torch
     lib = load_library()
@@ -197,14 +205,29 @@ def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: i
         final_state = torch.empty(st_shape, dtype=torch.float32, device=q.device)
     if final_state is not None:
         _req(final_state, "final_state", torch.float32, st_shape)
-    workspace, wbytes = _workspace(s, False, workspace, q.device, _g is not None)
+    workspace, wbytes = _workspace(s, _save, workspace, q.device, _g is not None)
     if _g is None:
-        _check(lib.deltanet_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
-                                _p(final_state), _p(workspace), wbytes, _stream(stream)))
+        fn = lib.deltanet_fwd_save if _save else lib.deltanet_fwd
+        _check(fn(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
+                  _p(final_state), _p(workspace), wbytes, _stream(stream)))
     else:
-        _check(lib.deltanet_gated_fwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(initial_state), _p(o),
-                                      _p(final_state), _p(workspace), wbytes, _stream(stream)))
+        fn = lib.deltanet_gated_fwd_save if _save else lib.deltanet_gated_fwd
+        _check(fn(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(initial_state), _p(o),
+                  _p(final_state), _p(workspace), wbytes, _stream(stream)))
+    if _save:
+        return o, final_state, workspace
     return o, final_state
+
+
+def deltanet_fwd_save(q, k, v, beta, initial_state=None, *, saved=None, **kw):
+    """Forward pass that keeps its per-chunk results for deltanet_bwd_saved; returns (o, final_state or None, saved).
+    ``saved`` (optional) is a uint8 device tensor of deltanet_workspace_bytes(shape, True) bytes to reuse."""
+    return deltanet_fwd(q, k, v, beta, initial_state, workspace=saved, _save=True, **kw)
+
+
+def deltanet_gated_fwd_save(q, k, v, beta, g, initial_state=None, *, saved=None, **kw):
+    """Gated forward pass that keeps its per-chunk results; returns (o, final_state or None, saved)."""
+    return deltanet_fwd(q, k, v, beta, initial_state, workspace=saved, _save=True, _g=g, **kw)
 
 
 def deltanet_gated_fwd(q, k, v, beta, g, initial_state=None, **kw):
@@ -250,7 +273,8 @@ def deltanet_gated_recurrent_fwd(q, k, v, beta, g, initial_state=None, **kw):
 
 
 def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None,
-                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, _g=None):
+                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, _g=None,
+                 _saved=False):
     """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None)."""
     import torch
     lib = load_library()
@@ -270,13 +294,24 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     dbeta = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
     dS0 = torch.empty(st_shape, dtype=torch.float32, device=q.device) if want_dinitial_state else None
+    if _saved and workspace is None:
+        raise ValueError("saved must be the buffer returned by the matching forward call")
     workspace, wbytes = _workspace(s, True, workspace, q.device, _g is not None)
+    if _saved and _g is None:
+        _check(lib.deltanet_bwd_saved(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(d_o), _p(dfinal_state),
+                                      _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace), wbytes, _stream(stream)))
+        return dq, dk, dv, dbeta, dS0
     if _g is None:
         _check(lib.deltanet_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(d_o),
                                 _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace),
                                 wbytes, _stream(stream)))
         return dq, dk, dv, dbeta, dS0
     dg = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
+    if _saved:
+        _check(lib.deltanet_gated_bwd_saved(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(d_o),
+                                            _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dg), _p(dS0),
+                                            _p(workspace), wbytes, _stream(stream)))
+        return dq, dk, dv, dbeta, dg, dS0
     _check(lib.deltanet_gated_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(initial_state), _p(d_o),
                                   _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dg), _p(dS0), _p(workspace),
                                   wbytes, _stream(stream)))
@@ -286,3 +321,13 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
 def deltanet_gated_bwd(q, k, v, beta, g, d_o, initial_state=None, dfinal_state=None, **kw):
     """Backward pass of the gated variant; returns (dq, dk, dv, dbeta, dg, dinitial_state or None), dbeta and dg in fp32."""
     return deltanet_bwd(q, k, v, beta, d_o, initial_state, dfinal_state, _g=g, **kw)
+
+
+def deltanet_bwd_saved(q, k, v, beta, d_o, saved, dfinal_state=None, **kw):
+    """Backward pass from the buffer deltanet_fwd_save left for the same inputs; returns what deltanet_bwd returns."""
+    return deltanet_bwd(q, k, v, beta, d_o, None, dfinal_state, workspace=saved, _saved=True, **kw)
+
+
+def deltanet_gated_bwd_saved(q, k, v, beta, g, d_o, saved, dfinal_state=None, **kw):
+    """Gated backward pass from the buffer deltanet_gated_fwd_save left; returns what deltanet_gated_bwd returns."""
+    return deltanet_bwd(q, k, v, beta, d_o, None, dfinal_state, workspace=saved, _saved=True, _g=g, **kw)

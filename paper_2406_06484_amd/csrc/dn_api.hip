@@ -153,28 +153,30 @@ int check_device(const Impl *impl, Problem *pb) {
 
 int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
              bool gated, const float *initial_state, void *o, float *final_state, void *workspace,
-             size_t workspace_bytes, void *hip_stream) {
+             size_t workspace_bytes, void *hip_stream, bool save = false) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
+    if (save && !impl->bwd) return DN_ERR_UNSUPPORTED;
     if (!q || !k || !v || !beta || !o || (gated && !g)) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, workspace, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
     Plan pl;
-    make_plan(shape, 0, &pl, gated);
+    make_plan(shape, save, &pl, gated);
     if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
     if (int rc = check_device(impl, &pl.pb)) return rc;
     Ptrs p;
     memset(&p, 0, sizeof(p));
     p.q = q; p.k = k; p.v = v; p.beta = beta; p.g = gated ? g : nullptr; p.S0 = initial_state; p.o = o; p.ST = final_state;
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
-    bind_workspace(pl, workspace, &p, &pl.pb, false, gated);
+    pl.pb.save = save;
+    bind_workspace(pl, workspace, &p, &pl.pb, save, gated);
     return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
 
 int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
              bool gated, const float *initial_state, const void *d_o, const float *dfinal_state, void *dq, void *dk,
              void *dv, float *dbeta, float *dg, float *dinitial_state, void *workspace, size_t workspace_bytes,
-             void *hip_stream) {
+             void *hip_stream, bool saved = false) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
     if (!impl->bwd) return DN_ERR_UNSUPPORTED;
@@ -191,6 +193,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     p.q = q; p.k = k; p.v = v; p.beta = beta; p.g = gated ? g : nullptr; p.S0 = initial_state; p.d_o = d_o; p.dST = dfinal_state;
     p.dq = dq; p.dk = dk; p.dv = dv; p.dbeta = dbeta; p.dg = gated ? dg : nullptr; p.dS0 = dinitial_state;
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
+    pl.pb.save = saved;
     bind_workspace(pl, workspace, &p, &pl.pb, true, gated);
     return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
@@ -224,6 +227,19 @@ int deltanet_bwd(const dn_shape *shape, const void *q, const void *k, const void
                     dinitial_state, workspace, workspace_bytes, hip_stream);
 }
 
+int deltanet_fwd_save(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                      const float *initial_state, void *o, float *final_state, void *saved, size_t saved_bytes,
+                      void *hip_stream) {
+    return fwd_impl(shape, q, k, v, beta, nullptr, false, initial_state, o, final_state, saved, saved_bytes, hip_stream, true);
+}
+
+int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                       const void *d_o, const float *dfinal_state, void *dq, void *dk, void *dv, float *dbeta,
+                       float *dinitial_state, void *saved, size_t saved_bytes, void *hip_stream) {
+    return bwd_impl(shape, q, k, v, beta, nullptr, false, nullptr, d_o, dfinal_state, dq, dk, dv, dbeta, nullptr,
+                    dinitial_state, saved, saved_bytes, hip_stream, true);
+}
+
 int deltanet_gated_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes) {
     if (!out_bytes) return DN_ERR_NULL;
     const Impl *impl = nullptr;
@@ -247,6 +263,20 @@ int deltanet_gated_bwd(const dn_shape *shape, const void *q, const void *k, cons
                        size_t workspace_bytes, void *hip_stream) {
     return bwd_impl(shape, q, k, v, beta, g, true, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
                     workspace, workspace_bytes, hip_stream);
+}
+
+int deltanet_gated_fwd_save(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                            const float *g, const float *initial_state, void *o, float *final_state, void *saved,
+                            size_t saved_bytes, void *hip_stream) {
+    return fwd_impl(shape, q, k, v, beta, g, true, initial_state, o, final_state, saved, saved_bytes, hip_stream, true);
+}
+
+int deltanet_gated_bwd_saved(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                             const float *g, const void *d_o, const float *dfinal_state, void *dq, void *dk, void *dv,
+                             float *dbeta, float *dg, float *dinitial_state, void *saved, size_t saved_bytes,
+                             void *hip_stream) {
+    return bwd_impl(shape, q, k, v, beta, g, true, nullptr, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
+                    saved, saved_bytes, hip_stream, true);
 }
 
 static int recurrent_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,

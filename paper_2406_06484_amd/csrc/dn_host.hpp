@@ -13,6 +13,8 @@ struct Problem {
     int32_t *coff;          // device chunk-offset prefix [N+1] inside the workspace (packed only)
     hipStream_t stream;
     int num_cus;            // compute units of the current device
+    int save;               // forward: also leave X, Ut and the chunk-initial states in the workspace;
+                            // backward: find them there instead of recomputing them
 };
 
 struct Ptrs {

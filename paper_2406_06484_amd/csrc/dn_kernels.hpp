@@ -161,8 +161,10 @@ template <int DK, int BV> struct ScanMap {
     }
 };
 
-// scan_fwd_body: STORE = false writes O and the final state; STORE = true (backward's recompute pass)
-// writes every chunk-initial state and Ut to the workspace instead of O.
+// scan_fwd_body: MODE = SCAN_OUT writes O and the final state; SCAN_STORE (the backward's recompute pass)
+// writes every chunk-initial state and Ut to the workspace instead of O; SCAN_BOTH (a forward pass whose
+// backward pass will not recompute) does both.
+enum { SCAN_OUT = 0, SCAN_STORE = 1, SCAN_BOTH = 2 };
 template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr int BV = VBlock<T, DV, DK>::BV;
     static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LV = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
@@ -181,9 +183,10 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t bytes = oGam + sizeof(float) * 2 * C;
 };
 
-template <typename T, int DK, int DV, bool STORE, bool GATED>
+template <typename T, int DK, int DV, int MODE, bool GATED>
 __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanFwdSmem<T, DK, DV>;
+    constexpr bool OUT = MODE != SCAN_STORE, SAVE = MODE != SCAN_OUT;
     constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
     constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
@@ -200,7 +203,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
+    constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (DK > 128 ? 4 : 0); // SCAN_BOTH: the loader waves hold more
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -210,7 +213,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     sm.seq(n, t0, len, cb);
     const int nchunks = (len + C - 1) / C;
     const Map m(wave);
-    const bool loader = wave >= 4, does_o = !STORE && m.does_o;
+    const bool loader = wave >= 4, does_o = OUT && m.does_o;
     const int lt = threadIdx.x - NTL; // index among the loader threads
     // waves 0..3 build the tiles (pmi, pni) = (0,0), (1,0), (1,1), (0,1) of P; the last one is all zero
     const int pmi = (wave == 1) | (wave == 2), pni = wave >> 1;
@@ -245,7 +248,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     auto fetch_b = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
-        if (!STORE) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        if (OUT) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
     };
     // Everything that touches global memory is issued by the loader waves in one burst right after
     // the first barrier of a step: the loads for the next chunk, then the stores of what the previous
@@ -254,13 +257,13 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     // full step old.
     auto flush_prev = [&](int icp) __attribute__((always_inline)) { // results of chunk icp, still in LDS
         const long tile = ((long)(cb + icp) * H + h);
-        if (STORE) copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt); // Ut^T
-        else if (m.does_o)
+        if (SAVE) copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt); // Ut^T
+        if (OUT && m.does_o)
             stage_flush<T>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
                            min(C, len - icp * C));
     };
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
-        if (!STORE) r.q.store(sQ, SM::LQ, lt);
+        if (OUT) r.q.store(sQ, SM::LQ, lt);
         r.k.store(sK, SM::LK, lt);
         if (gated) { // the chunk runs the plain rule on v_i / gamma_i
             r.v.scale_rows(r.vs);
@@ -303,7 +306,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             }
             if (m.does_u) mma<C, false, true, T, SEQ, MB>(acc, sT + 32 * m.ua * SM::LT, SM::LT, sV + 32 * m.ub, SM::LV); // U = T V
             f32x16 pa = zero16();
-            if (!STORE) // P = tril(Q K^T), the causal intra-chunk scores of Eq. 9, as the tile (pni, pmi) of P^T
+            if (OUT) // P = tril(Q K^T), the causal intra-chunk scores of Eq. 9, as the tile (pni, pmi) of P^T
                 mma<DK, false, false, T, SEQ, MB>(pa, sK + 32 * pni * SM::LK, SM::LK, sQ + 32 * pmi * SM::LQ, SM::LQ);
             if (NWT <= 2) {
 #pragma unroll
@@ -312,7 +315,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
                     if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
                 }
             }
-            if (!STORE) {
+            if (OUT) {
                 acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r > 32 * pmi + c) val = 0.f; });
                 acc_to_lds_t<T>(sP, SM::LT, 32 * pni, 32 * pmi, pa);
             }
@@ -321,8 +324,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (loader) {
             if (ic + 1 < nchunks) fetch_b(ic + 1);
             // the chunk-initial state leaves transposed, as it sits in LDS
-            if (STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
-            if (!STORE && ic > 0) flush_prev(ic - 1);
+            if (SAVE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (!SAVE && ic > 0) flush_prev(ic - 1);
         }
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
             f32x16 ws = zero16();
@@ -333,7 +336,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             mma<DK, false, false, T, true, MB>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
-        if (STORE && loader && ic > 0) flush_prev(ic - 1);
+        if (SAVE && loader && ic > 0) flush_prev(ic - 1);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T, true, MB>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T, true, MB>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -348,14 +351,18 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (loader && ic + 1 < nchunks) stash();
     }
     if (loader && nchunks > 0) flush_prev(nchunks - 1);
-    if (!STORE && p.ST && m.has_s) {
+    if (OUT && p.ST && m.has_s) {
         float *dst = p.ST + (long)chain * DK * DV + vb;
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
 }
 template <typename T, int DK, int DV, bool GATED>
 __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
-    scan_fwd_body<T, DK, DV, false, GATED>(sm, H, p, blockIdx.x);
+    scan_fwd_body<T, DK, DV, SCAN_OUT, GATED>(sm, H, p, blockIdx.x);
+}
+template <typename T, int DK, int DV, bool GATED>
+__global__ __launch_bounds__(NTS) void k_scan_fwd_save(SeqMap sm, int H, Ptrs p) {
+    scan_fwd_body<T, DK, DV, SCAN_BOTH, GATED>(sm, H, p, blockIdx.x);
 }
 
 // scan_bwd_body: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
@@ -518,7 +525,12 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
 template <typename T, int DK, int DV, bool GATED>
 __global__ __launch_bounds__(NTS) void k_scan_pair(SeqMap sm, int H, Ptrs p, int half) {
     if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV, GATED>(sm, H, p, blockIdx.x);
-    else scan_fwd_body<T, DK, DV, true, GATED>(sm, H, p, blockIdx.x - half);
+    else scan_fwd_body<T, DK, DV, SCAN_STORE, GATED>(sm, H, p, blockIdx.x - half);
+}
+// the reverse scan alone, for a backward pass that finds the forward scan's tiles already in the workspace
+template <typename T, int DK, int DV, bool GATED>
+__global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
+    scan_bwd_body<T, DK, DV, GATED>(sm, H, p, blockIdx.x);
 }
 
 // =============================================================================================

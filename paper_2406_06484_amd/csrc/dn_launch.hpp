@@ -46,6 +46,9 @@ template <typename T, int DK, int DV> size_t max_lds_bytes() {
     return m;
 }
 
+// whether the backward pass is compiled for this head size (its chunk tiles must fit the LDS)
+template <typename T, int DK, int DV> constexpr bool kHasBwd = ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
+
 // forward-only instantiations (head sizes whose backward tiles do not fit)
 template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
     static_assert(PrepSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_wy_prep LDS");
@@ -59,6 +62,13 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    if constexpr (kHasBwd<T, DK, DV>) {
+        if (pb.save) {
+            if (p.g) DN_LAUNCH_NT((k_scan_fwd_save<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+            else DN_LAUNCH_NT((k_scan_fwd_save<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+            return 0;
+        }
+    }
     if (p.g) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     else DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;
@@ -69,8 +79,12 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
-    if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    { // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
+    if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
+        if (p.g) DN_LAUNCH_NT((k_scan_bwd<T, DK, DV, true>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+        else DN_LAUNCH_NT((k_scan_bwd<T, DK, DV, false>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    } else {
+        if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
+        // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
         const dim3 gpair(2 * gchain.x);
         if (p.g) DN_LAUNCH_NT((k_scan_pair<T, DK, DV, true>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);

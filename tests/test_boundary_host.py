@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     syms = header_symbols()
     assert {"deltanet_fwd", "deltanet_bwd", "deltanet_recurrent_fwd", "deltanet_workspace_bytes",
             "deltanet_gated_fwd", "deltanet_gated_bwd", "deltanet_gated_recurrent_fwd",
-            "deltanet_gated_workspace_bytes", "deltanet_status_string"} <= set(syms)
+            "deltanet_gated_workspace_bytes", "deltanet_status_string", "deltanet_fwd_save", "deltanet_bwd_saved",
+            "deltanet_gated_fwd_save", "deltanet_gated_bwd_saved"} <= set(syms)
     for s in syms:
         assert hasattr(lib, s), s
 
@@ -91,6 +92,24 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     assert lib.deltanet_bwd(ctypes.byref(s), *bargs, fake, 16, None) == -5
     bargs[10] = None  # dbeta is required
     assert lib.deltanet_bwd(ctypes.byref(s), *bargs, fake, 1 << 40, None) == -1
+    # the pair that keeps the forward pass's tiles: the buffer has the backward pass's size
+    assert lib.deltanet_fwd_save(ctypes.byref(s), *args, fake, fwd_only_bytes(lib, s), None) == -5
+    assert lib.deltanet_fwd_save(ctypes.byref(s), None, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -1
+    assert lib.deltanet_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), *args, fake, 1 << 40, None) == -3
+    sargs = [fake] * 4 + [fake, None, fake, fake, fake, fake, None]
+    assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, fake, 16, None) == -5
+    assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, odd, 1 << 40, None) == -4
+    sargs[4] = None  # d_o is required
+    assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, fake, 1 << 40, None) == -1
+    assert lib.deltanet_gated_fwd_save(ctypes.byref(s), fake, fake, fake, fake, None, None, fake, None, fake, 1 << 40, None) == -1
+    gs = [fake] * 5 + [fake, None, fake, fake, fake, fake, None, None]  # dg missing
+    assert lib.deltanet_gated_bwd_saved(ctypes.byref(s), *gs, fake, 1 << 40, None) == -1
+
+
+def fwd_only_bytes(lib, s):
+    out = ctypes.c_size_t(0)
+    assert lib.deltanet_workspace_bytes(ctypes.byref(s), 0, ctypes.byref(out)) == 0
+    return out.value
 
 
 def test_cu_seqlens_host_is_validated():

@@ -173,3 +173,6 @@ def gated_bwd(q, k, v, beta, g, d_o, initial_state=None, dfinal_state=None, cu_s
         dq = dq.reshape(shape + (H, dk)); dkk = dkk.reshape(shape + (H, dk))
         dvv = dvv.reshape(shape + (H, dv)); db = db.reshape(shape + (H,)); dg = dg.reshape(shape + (H,))
     return dq, dkk, dvv, db, dg, dS0
+
+
+from .prologue import feature_map, feature_map_bwd, fused_bwd, fused_fwd, sigmoid, silu  # noqa: E402,F401

@@ -277,6 +277,26 @@ def main() -> int:
     out["gated_fwd_bwd"] = {"ms": round(gms, 4), "tokens_per_s": round(tokens / (gms * 1e-3), 1), "steps": rec_steps,
                             "vs_plain": round(gms / ms_per_step, 3)}
 
+    # The same step with the layer's prologue fused into the load path (SiLU + L2 norm of q and k, sigmoid of the beta
+    # logits, and the gradients through them in the store path), on pre-activations of the same shape.
+    from paper_2406_06484_amd.synth import make_pre_activations
+    pre = make_pre_activations(2, inp)
+    qp, kp, bp = bf(pre.q), bf(pre.k), bf(pre.beta)
+
+    def fused_step():
+        dn.deltanet_fused_fwd_save(qp, kp, v, bp, o=o, final_state=ST, saved=ws)
+        return dn.deltanet_fused_bwd_saved(qp, kp, v, bp, d_o, ws)
+    for _ in range(3):
+        fused_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(rec_steps):
+        fused_step()
+    torch.cuda.synchronize()
+    fms = 1e3 * (time.perf_counter() - t0) / rec_steps
+    out["fused_prologue_fwd_bwd"] = {"ms": round(fms, 4), "tokens_per_s": round(tokens / (fms * 1e-3), 1), "steps": rec_steps,
+                                     "vs_plain": round(fms / ms_per_step, 3)}
+
     if not args.no_cpu_baseline:
         import oracle
         nthr = oracle.max_threads()

@@ -114,6 +114,38 @@ int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, cons
                        float *dinitial_state, void *saved, size_t saved_bytes, void *hip_stream);
 
 /*
+ * The same passes with the layer's prologue fused into the load path (section 3.3, "Feature map and
+ * normalization", and the writing strength of section 2.2): the caller hands over the pre-activations
+ * q_pre, k_pre (layouts and element type of q, k) and the logits beta_logit (layout and element type of
+ * beta), and the kernels form
+ *
+ *     q_t = SiLU(q_pre_t) / ||SiLU(q_pre_t)||_2 ,  k_t likewise,  beta_t = sigmoid(beta_logit_t)
+ *
+ * per token and head on their way to the LDS (fp32 arithmetic, result rounded to the element type as a
+ * stored q, k would be), so q and k never make the round trip through HBM.  A row whose SiLU image is
+ * exactly zero maps to zero (the paper gives no epsilon).  deltanet_fused_bwd returns the gradients with
+ * respect to q_pre, k_pre and beta_logit (through the normalisation, the SiLU and the sigmoid) in
+ * dq_pre, dk_pre (element type dtype) and dbeta_logit (fp32); dv and dinitial_state are as for
+ * deltanet_bwd.  Workspace sizes are those of deltanet_workspace_bytes.  deltanet_fused_fwd_save /
+ * deltanet_fused_bwd_saved are the pair that keeps the forward pass's per-chunk results, as
+ * deltanet_fwd_save / deltanet_bwd_saved.  Everything else is as for the plain calls.
+ */
+int deltanet_fused_fwd(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v, const void *beta_logit,
+                       const float *initial_state, void *o, float *final_state, void *workspace, size_t workspace_bytes,
+                       void *hip_stream);
+int deltanet_fused_bwd(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v, const void *beta_logit,
+                       const float *initial_state, const void *d_o, const float *dfinal_state, void *dq_pre, void *dk_pre,
+                       void *dv, float *dbeta_logit, float *dinitial_state, void *workspace, size_t workspace_bytes,
+                       void *hip_stream);
+int deltanet_fused_fwd_save(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v,
+                            const void *beta_logit, const float *initial_state, void *o, float *final_state, void *saved,
+                            size_t saved_bytes, void *hip_stream);
+int deltanet_fused_bwd_saved(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v,
+                             const void *beta_logit, const void *d_o, const float *dfinal_state, void *dq_pre, void *dk_pre,
+                             void *dv, float *dbeta_logit, float *dinitial_state, void *saved, size_t saved_bytes,
+                             void *hip_stream);
+
+/*
  * Forward pass in the recurrent (token-serial) form: the delta-rule update and read-out of
  * section 2.2 applied one token after the other, state in fp32 registers, no chunking, no matrix
  * cores and no workspace.  It computes the same o and final_state as deltanet_fwd (fp32 arithmetic

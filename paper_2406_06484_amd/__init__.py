@@ -8,6 +8,10 @@ from .binding import (  # noqa: F401
     DeltaNetError,
     deltanet_bwd,
     deltanet_bwd_saved,
+    deltanet_fused_bwd,
+    deltanet_fused_bwd_saved,
+    deltanet_fused_fwd,
+    deltanet_fused_fwd_save,
     deltanet_fwd,
     deltanet_fwd_save,
     deltanet_gated_bwd,

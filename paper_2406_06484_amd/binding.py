@@ -64,6 +64,13 @@ def load_library():
         lib.deltanet_gated_fwd_save.argtypes = [sp] + [vp] * 8 + [vp, sz, vp]
         lib.deltanet_gated_bwd_saved.restype = ctypes.c_int
         lib.deltanet_gated_bwd_saved.argtypes = [sp] + [vp] * 13 + [vp, sz, vp]
+        for name in ("deltanet_fused_fwd", "deltanet_fused_fwd_save"):
+            getattr(lib, name).restype = ctypes.c_int
+            getattr(lib, name).argtypes = [sp] + [vp] * 7 + [vp, sz, vp]
+        lib.deltanet_fused_bwd.restype = ctypes.c_int
+        lib.deltanet_fused_bwd.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
+        lib.deltanet_fused_bwd_saved.restype = ctypes.c_int
+        lib.deltanet_fused_bwd_saved.argtypes = [sp] + [vp] * 11 + [vp, sz, vp]
         lib.deltanet_recurrent_fwd.restype = ctypes.c_int
         lib.deltanet_recurrent_fwd.argtypes = [sp] + [vp] * 7 + [vp]
         lib.deltanet_gated_workspace_bytes.restype = ctypes.c_int
@@ -182,7 +189,7 @@ def _workspace(shape, want_bwd, workspace, device, gated=False):
 
 def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: int = 64,
                  output_final_state: bool = True, o=None, final_state=None, workspace=None,
-                 stream=None, _g=None, _save=False) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
+                 stream=None, _g=None, _save=False, _pro=False) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
     """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None)."""
     import torch
     lib = load_library()
@@ -207,7 +214,10 @@ def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: i
         _req(final_state, "final_state", torch.float32, st_shape)
     workspace, wbytes = _workspace(s, _save, workspace, q.device, _g is not None)
     if _g is None:
-        fn = lib.deltanet_fwd_save if _save else lib.deltanet_fwd
+        if _pro:
+            fn = lib.deltanet_fused_fwd_save if _save else lib.deltanet_fused_fwd
+        else:
+            fn = lib.deltanet_fwd_save if _save else lib.deltanet_fwd
         _check(fn(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o),
                   _p(final_state), _p(workspace), wbytes, _stream(stream)))
     else:
@@ -274,7 +284,7 @@ def deltanet_gated_recurrent_fwd(q, k, v, beta, g, initial_state=None, **kw):
 
 def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None,
                  chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, _g=None,
-                 _saved=False):
+                 _saved=False, _pro=False):
     """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None)."""
     import torch
     lib = load_library()
@@ -298,11 +308,13 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
         raise ValueError("saved must be the buffer returned by the matching forward call")
     workspace, wbytes = _workspace(s, True, workspace, q.device, _g is not None)
     if _saved and _g is None:
-        _check(lib.deltanet_bwd_saved(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(d_o), _p(dfinal_state),
+        fn = lib.deltanet_fused_bwd_saved if _pro else lib.deltanet_bwd_saved
+        _check(fn(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(d_o), _p(dfinal_state),
                                       _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace), wbytes, _stream(stream)))
         return dq, dk, dv, dbeta, dS0
     if _g is None:
-        _check(lib.deltanet_bwd(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(d_o),
+        fn = lib.deltanet_fused_bwd if _pro else lib.deltanet_bwd
+        _check(fn(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(d_o),
                                 _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace),
                                 wbytes, _stream(stream)))
         return dq, dk, dv, dbeta, dS0
@@ -331,3 +343,24 @@ def deltanet_bwd_saved(q, k, v, beta, d_o, saved, dfinal_state=None, **kw):
 def deltanet_gated_bwd_saved(q, k, v, beta, g, d_o, saved, dfinal_state=None, **kw):
     """Gated backward pass from the buffer deltanet_gated_fwd_save left; returns what deltanet_gated_bwd returns."""
     return deltanet_bwd(q, k, v, beta, d_o, None, dfinal_state, workspace=saved, _saved=True, _g=g, **kw)
+
+
+def deltanet_fused_fwd(q_pre, k_pre, v, beta_logit, initial_state=None, **kw):
+    """Forward pass with the layer's prologue in the load path: q, k = SiLU(x) / ||SiLU(x)||_2 of the given
+    pre-activations, beta = sigmoid(beta_logit); returns (o, final_state or None)."""
+    return deltanet_fwd(q_pre, k_pre, v, beta_logit, initial_state, _pro=True, **kw)
+
+
+def deltanet_fused_bwd(q_pre, k_pre, v, beta_logit, d_o, initial_state=None, dfinal_state=None, **kw):
+    """Backward pass of deltanet_fused_fwd; returns (dq_pre, dk_pre, dv, dbeta_logit[fp32], dinitial_state or None)."""
+    return deltanet_bwd(q_pre, k_pre, v, beta_logit, d_o, initial_state, dfinal_state, _pro=True, **kw)
+
+
+def deltanet_fused_fwd_save(q_pre, k_pre, v, beta_logit, initial_state=None, *, saved=None, **kw):
+    """deltanet_fused_fwd that keeps its per-chunk results; returns (o, final_state or None, saved)."""
+    return deltanet_fwd(q_pre, k_pre, v, beta_logit, initial_state, workspace=saved, _save=True, _pro=True, **kw)
+
+
+def deltanet_fused_bwd_saved(q_pre, k_pre, v, beta_logit, d_o, saved, dfinal_state=None, **kw):
+    """Backward pass from the buffer deltanet_fused_fwd_save left; returns what deltanet_fused_bwd returns."""
+    return deltanet_bwd(q_pre, k_pre, v, beta_logit, d_o, None, dfinal_state, workspace=saved, _saved=True, _pro=True, **kw)

@@ -153,7 +153,7 @@ int check_device(const Impl *impl, Problem *pb) {
 
 int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
              bool gated, const float *initial_state, void *o, float *final_state, void *workspace,
-             size_t workspace_bytes, void *hip_stream, bool save = false) {
+             size_t workspace_bytes, void *hip_stream, bool save = false, bool prologue = false) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
     if (save && !impl->bwd) return DN_ERR_UNSUPPORTED;
@@ -169,6 +169,7 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     p.q = q; p.k = k; p.v = v; p.beta = beta; p.g = gated ? g : nullptr; p.S0 = initial_state; p.o = o; p.ST = final_state;
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     pl.pb.save = save;
+    p.pro = prologue;
     bind_workspace(pl, workspace, &p, &pl.pb, save, gated);
     return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
@@ -176,7 +177,7 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
 int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
              bool gated, const float *initial_state, const void *d_o, const float *dfinal_state, void *dq, void *dk,
              void *dv, float *dbeta, float *dg, float *dinitial_state, void *workspace, size_t workspace_bytes,
-             void *hip_stream, bool saved = false) {
+             void *hip_stream, bool saved = false, bool prologue = false) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
     if (!impl->bwd) return DN_ERR_UNSUPPORTED;
@@ -194,6 +195,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     p.dq = dq; p.dk = dk; p.dv = dv; p.dbeta = dbeta; p.dg = gated ? dg : nullptr; p.dS0 = dinitial_state;
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     pl.pb.save = saved;
+    p.pro = prologue;
     bind_workspace(pl, workspace, &p, &pl.pb, true, gated);
     return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
@@ -238,6 +240,36 @@ int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, cons
                        float *dinitial_state, void *saved, size_t saved_bytes, void *hip_stream) {
     return bwd_impl(shape, q, k, v, beta, nullptr, false, nullptr, d_o, dfinal_state, dq, dk, dv, dbeta, nullptr,
                     dinitial_state, saved, saved_bytes, hip_stream, true);
+}
+
+int deltanet_fused_fwd(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v, const void *beta_logit,
+                       const float *initial_state, void *o, float *final_state, void *workspace, size_t workspace_bytes,
+                       void *hip_stream) {
+    return fwd_impl(shape, q_pre, k_pre, v, beta_logit, nullptr, false, initial_state, o, final_state, workspace,
+                    workspace_bytes, hip_stream, false, true);
+}
+
+int deltanet_fused_bwd(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v, const void *beta_logit,
+                       const float *initial_state, const void *d_o, const float *dfinal_state, void *dq_pre, void *dk_pre,
+                       void *dv, float *dbeta_logit, float *dinitial_state, void *workspace, size_t workspace_bytes,
+                       void *hip_stream) {
+    return bwd_impl(shape, q_pre, k_pre, v, beta_logit, nullptr, false, initial_state, d_o, dfinal_state, dq_pre, dk_pre, dv,
+                    dbeta_logit, nullptr, dinitial_state, workspace, workspace_bytes, hip_stream, false, true);
+}
+
+int deltanet_fused_fwd_save(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v,
+                            const void *beta_logit, const float *initial_state, void *o, float *final_state, void *saved,
+                            size_t saved_bytes, void *hip_stream) {
+    return fwd_impl(shape, q_pre, k_pre, v, beta_logit, nullptr, false, initial_state, o, final_state, saved, saved_bytes,
+                    hip_stream, true, true);
+}
+
+int deltanet_fused_bwd_saved(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v,
+                             const void *beta_logit, const void *d_o, const float *dfinal_state, void *dq_pre, void *dk_pre,
+                             void *dv, float *dbeta_logit, float *dinitial_state, void *saved, size_t saved_bytes,
+                             void *hip_stream) {
+    return bwd_impl(shape, q_pre, k_pre, v, beta_logit, nullptr, false, nullptr, d_o, dfinal_state, dq_pre, dk_pre, dv,
+                    dbeta_logit, nullptr, dinitial_state, saved, saved_bytes, hip_stream, true, true);
 }
 
 int deltanet_gated_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes) {

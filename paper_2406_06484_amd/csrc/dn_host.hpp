@@ -31,6 +31,9 @@ struct Ptrs {
     // ([tile][2][C] fp32)
     const float *g;
     float *dg, *gam;
+    // prologue variant: q and k hold the pre-activations of the feature map, beta the logits; dq, dk and
+    // dbeta receive the gradients with respect to those
+    int pro;
 };
 
 // Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is

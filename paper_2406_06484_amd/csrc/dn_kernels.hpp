@@ -15,6 +15,11 @@
 namespace dn {
 
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
+// Kernel variants (a compile-time template argument, so that each carries only its own registers):
+// the plain delta rule; the gated rule; the plain rule with the layer's prologue in the load path
+// (q, k = SiLU(x) / ||SiLU(x)||_2 of section 3.3, beta = sigmoid(b) of section 2.2) and its gradient
+// in the store path.
+enum { VAR_PLAIN = 0, VAR_GATED = 1, VAR_PROLOGUE = 2 };
 constexpr size_t align16(size_t x) { return (x + 15) & ~size_t(15); }
 
 // ---------------------------------------------------------------------------------------------
@@ -77,8 +82,20 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     const int mi = wave >> 1, ni = wave & 1; // this wave's 32 x 32 tile of the C x C matrices
     const bool upper = mi == 0 && ni == 1;
 
-    load_tile<T, C, DK>(sK, SM::LD, (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-    if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
+    {
+        TileRegs<T, C, DK> kr;
+        kr.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        if (p.pro) { // prologue variant: k arrives before the feature map of section 3.3
+            float inv[TileRegs<T, C, DK>::NIT];
+            kr.feature_map(inv);
+        }
+        kr.store(sK, SM::LD);
+    }
+    if (tid < C) {
+        float b = tid < nvalid ? to_f32(((const T *)p.beta)[(row0 + tid) * H + h]) : 0.f;
+        if (p.pro) b = tid < nvalid ? sigmoid_f32(b) : 0.f; // ... and beta before the sigmoid
+        sBeta[tid] = b;
+    }
     if (p.g && tid < C) {
         // Gated variant: gamma_i = exp(g_1 + ... + g_i) within the chunk (rows past the end keep the last
         // value).  S_i / gamma_i follows the plain delta rule on the values v_i / gamma_i, so the other
@@ -183,9 +200,10 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t bytes = oGam + sizeof(float) * 2 * C;
 };
 
-template <typename T, int DK, int DV, int MODE, bool GATED>
+template <typename T, int DK, int DV, int MODE, int VAR>
 __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanFwdSmem<T, DK, DV>;
+    constexpr bool GATED = VAR == VAR_GATED, PRO = VAR == VAR_PROLOGUE;
     constexpr bool OUT = MODE != SCAN_STORE, SAVE = MODE != SCAN_OUT;
     constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
@@ -203,7 +221,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (DK > 128 ? 4 : 0); // SCAN_BOTH: the loader waves hold more
+    constexpr int MB = (GATED || PRO || MODE == SCAN_BOTH) ? 2 : (DK > 128 ? 4 : 0); // SCAN_BOTH: the loader waves hold more
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -263,6 +281,11 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
                            min(C, len - icp * C));
     };
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
+        if (PRO) { // the feature map of section 3.3, applied on the way to LDS
+            float inv[TileRegs<T, C, DK, NTL>::NIT];
+            if (OUT) r.q.feature_map(inv);
+            r.k.feature_map(inv);
+        }
         if (OUT) r.q.store(sQ, SM::LQ, lt);
         r.k.store(sK, SM::LK, lt);
         if (gated) { // the chunk runs the plain rule on v_i / gamma_i
@@ -356,13 +379,13 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
 }
-template <typename T, int DK, int DV, bool GATED>
+template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
-    scan_fwd_body<T, DK, DV, SCAN_OUT, GATED>(sm, H, p, blockIdx.x);
+    scan_fwd_body<T, DK, DV, SCAN_OUT, VAR>(sm, H, p, blockIdx.x);
 }
-template <typename T, int DK, int DV, bool GATED>
+template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_fwd_save(SeqMap sm, int H, Ptrs p) {
-    scan_fwd_body<T, DK, DV, SCAN_BOTH, GATED>(sm, H, p, blockIdx.x);
+    scan_fwd_body<T, DK, DV, SCAN_BOTH, VAR>(sm, H, p, blockIdx.x);
 }
 
 // scan_bwd_body: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):
@@ -383,9 +406,10 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t bytes = oPT + align16(sizeof(T) * C * LT);
 };
 
-template <typename T, int DK, int DV, bool GATED>
+template <typename T, int DK, int DV, int VAR>
 __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanBwdSmem<T, DK, DV>;
+    constexpr bool GATED = VAR == VAR_GATED, PRO = VAR == VAR_PROLOGUE;
     constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
     constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
@@ -448,6 +472,11 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
+        if (PRO) { // the feature map of section 3.3, applied on the way to LDS
+            float inv[TileRegs<T, C, DK, NTL>::NIT];
+            r.q.feature_map(inv);
+            r.k.feature_map(inv);
+        }
         r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt);
         if (gated) r.d_o.scale_rows(r.dos); // o_i = gamma_i o~_i, so the plain rule's output gradient is gamma_i dO_i
         r.d_o.store(sDO, SM::LD, lt);
@@ -522,15 +551,15 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
 // scan needs T; the reverse scan needs T and P^T), so the first half of the grid runs the reverse
 // scan and the second half the recompute scan: a CU picks up one of each with no kernel boundary
 // in between.  `half` = workgroups per scan.
-template <typename T, int DK, int DV, bool GATED>
+template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_pair(SeqMap sm, int H, Ptrs p, int half) {
-    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV, GATED>(sm, H, p, blockIdx.x);
-    else scan_fwd_body<T, DK, DV, SCAN_STORE, GATED>(sm, H, p, blockIdx.x - half);
+    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV, VAR>(sm, H, p, blockIdx.x);
+    else scan_fwd_body<T, DK, DV, SCAN_STORE, VAR>(sm, H, p, blockIdx.x - half);
 }
 // the reverse scan alone, for a backward pass that finds the forward scan's tiles already in the workspace
-template <typename T, int DK, int DV, bool GATED>
+template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
-    scan_bwd_body<T, DK, DV, GATED>(sm, H, p, blockIdx.x);
+    scan_bwd_body<T, DK, DV, VAR>(sm, H, p, blockIdx.x);
 }
 
 // =============================================================================================
@@ -595,9 +624,10 @@ template <typename T, int DK, int DV> struct ChunkSmem {
     static constexpr size_t bytes = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
 };
 
-template <typename T, int DK, int DV, bool GATED>
+template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int chunks_total) {
     using SM = ChunkSmem<T, DK, DV>;
+    constexpr bool GATED = VAR == VAR_GATED, PRO = VAR == VAR_PROLOGUE;
     constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);        // 32 x 32 tiles of a C x DK / C x DV matrix
     constexpr int KW = (KT + NWC - 1) / NWC, VW = (VT + NWC - 1) / NWC; // ... per wave
     extern __shared__ __align__(16) unsigned char smem[];
@@ -616,6 +646,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
     float *sZ = reinterpret_cast<float *>(smem + SM::oZ);
     float *sCq = reinterpret_cast<float *>(smem + SM::oCq), *sCv = reinterpret_cast<float *>(smem + SM::oCv);
+    float *sNq = sGam, *sNk = sGam + C; // prologue variant: 1 / ||SiLU(q_i)||, 1 / ||SiLU(k_i)|| (the gate's table is not in use)
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
     constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
@@ -678,8 +709,18 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         float zp = 0.f;
         if (gated) r.d_o.scale_rows(r.dos);
         r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LU); r.s.store(sS, SM::LSK);
-        r.dut.store(sDU, SM::LU); r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
-        if (tid < C) sBeta[tid] = tid < nvalid ? to_f32(r.beta) : 0.f;
+        r.dut.store(sDU, SM::LU);
+        if (PRO) { // the feature map of section 3.3 on the way to LDS; the norms wait for the store path
+            float inv[TileRegs<T, C, DK, NTC>::NIT];
+            r.k.feature_map(inv); r.k.store_row_values(sNk, inv);
+            r.q.feature_map(inv); r.q.store_row_values(sNq, inv);
+        }
+        r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
+        if (tid < C) {
+            float b = tid < nvalid ? to_f32(r.beta) : 0.f;
+            if (PRO) b = tid < nvalid ? sigmoid_f32(b) : 0.f; // beta = sigmoid(logit), section 2.2
+            sBeta[tid] = b;
+        }
         if (gated && tid < 2 * C) sGam[tid] = r.gm;
         lds_barrier();
         if (cc) { // dP = tril(dO Ut^T)
@@ -689,6 +730,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc);
         }
         f32x16 dq[KW], dw[KW], dk1[KW];
+        FmapRaw<T> raw[KW]; // prologue variant: the pre-activation block behind this wave's dq (later dk) tile
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) {
             dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
@@ -708,11 +750,22 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI]);
                 stage_flush_dot<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sQ, SM::LK,
                                    sCq + kb(sI) * C);
+            } else if (PRO) { // dq waits in the staging tile until every wave's share of q_i . dq_i is in
+                static_assert(!PRO || KW == 1, "one staging tile per wave");
+                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI]);
+                stage_fmap_dots<T>(stg, 32 * ka(sI), 32 * kb(sI), nvalid, sQ, SM::LK, sCq + kb(sI) * C,
+                                   (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, raw[sI]);
             } else {
                 acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI]);
             }
         }
         lds_barrier();
+        if (PRO) { // gradient through the feature map: dq~ = SiLU'(q~) (dq - q (q . dq)) / ||SiLU(q~)||
+#pragma unroll
+            for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT)
+                stage_fmap_flush<T, DK / 32>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sQ,
+                                             SM::LK, sCq, sNq, raw[sI]);
+        }
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
             if (gated) { // <K, Ut dS~'^T>, the second half of <dS_C, S_C>, taken while dK1 holds just that product
@@ -810,7 +863,13 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             else mma<C, false, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
             if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK);
             else mma<C, true, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
-            acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
+            if (PRO) {
+                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dk1[sI]);
+                stage_fmap_dots<T>(stg, 32 * ka(sI), 32 * kb(sI), nvalid, sK, SM::LK, sCq + kb(sI) * C,
+                                   (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, raw[sI]);
+            } else {
+                acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
+            }
         }
         if (gated && tid < C) {
             // Gate gradient.  o_t is linear in q_t and in the state, so the sensitivity to a rescaling of the
@@ -840,8 +899,18 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             for (int j = 0; j < 16; ++j) sum += sProd[i * SM::LF + seg * 16 + j];
             sum += __shfl_xor(sum, 1);
             sum += __shfl_xor(sum, 2);
-            if (seg == 0 && i < nvalid)
-                p.dbeta[(row0 + i) * H + h] = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+            if (seg == 0 && i < nvalid) {
+                float db = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+                if (PRO) db *= sBeta[i] * (1.f - sBeta[i]); // through the sigmoid
+                p.dbeta[(row0 + i) * H + h] = db;
+            }
+        }
+        if (PRO) { // every wave's share of k_i . dk_i is in: gradient through the feature map, as for dq
+            lds_barrier();
+#pragma unroll
+            for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT)
+                stage_fmap_flush<T, DK / 32>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sK,
+                                             SM::LK, sCq, sNk, raw[sI]);
         }
         lds_barrier(); // every buffer is free for the next tile
     }

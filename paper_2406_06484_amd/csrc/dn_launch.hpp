@@ -56,6 +56,14 @@ template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
     return PrepSmem<T, DK, DV>::bytes > ScanFwdSmem<T, DK, DV>::bytes ? PrepSmem<T, DK, DV>::bytes : ScanFwdSmem<T, DK, DV>::bytes;
 }
 
+// launches kernel<T, DK, DV, variant> for the variant the pointers ask for
+#define DN_LAUNCH_VAR(kernel, grid, nthreads, lds, ...)                                                     \
+    do {                                                                                                    \
+        if (p.g) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_GATED>), grid, nthreads, lds, __VA_ARGS__);            \
+        else if (p.pro) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PROLOGUE>), grid, nthreads, lds, __VA_ARGS__);  \
+        else DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__);                \
+    } while (0)
+
 template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0 || pb.chunks_ub == 0) return 0;
     const SeqMap sm = make_map(pb);
@@ -64,13 +72,11 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
     if constexpr (kHasBwd<T, DK, DV>) {
         if (pb.save) {
-            if (p.g) DN_LAUNCH_NT((k_scan_fwd_save<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
-            else DN_LAUNCH_NT((k_scan_fwd_save<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+            DN_LAUNCH_VAR(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
             return 0;
         }
     }
-    if (p.g) DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, true>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    else DN_LAUNCH_NT((k_scan_fwd<T, DK, DV, false>), gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH_VAR(k_scan_fwd, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     return 0;
 }
 
@@ -80,21 +86,18 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
-        if (p.g) DN_LAUNCH_NT((k_scan_bwd<T, DK, DV, true>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
-        else DN_LAUNCH_NT((k_scan_bwd<T, DK, DV, false>), gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+        DN_LAUNCH_VAR(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
     } else {
         if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
         // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
         const dim3 gpair(2 * gchain.x);
-        if (p.g) DN_LAUNCH_NT((k_scan_pair<T, DK, DV, true>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
-        else DN_LAUNCH_NT((k_scan_pair<T, DK, DV, false>), gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
+        DN_LAUNCH_VAR(k_scan_pair, gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
     }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
-        if (p.g) DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV, true>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
-        else DN_LAUNCH_NT((k_bwd_chunk<T, DK, DV, false>), gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        DN_LAUNCH_VAR(k_bwd_chunk, gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
     }
     return 0;
 }

@@ -110,3 +110,15 @@ def make_gate(seed: int, shape, lo: float = 0.85, hi: float = 1.0) -> np.ndarray
     """Log-decay g = log(alpha) of the gated variant, alpha ~ U(lo, hi) per token and head, as float32."""
     rng = np.random.default_rng(seed + 7_000_003)
     return np.log(rng.uniform(lo, hi, size=shape)).astype(np.float32)
+
+
+def make_pre_activations(seed: int, inp: Inputs, scale: float = 1.0) -> Inputs:
+    """The same batch with q, k replaced by pre-activations of the feature map (N(0, scale^2), what a
+    projection followed by a short convolution hands over) and beta by logits (N(0, 1)), rounded to the
+    batch's element type.  The values are drawn, nothing of the method is computed here."""
+    rng = np.random.default_rng(seed + 9_000_011)
+    rnd = round_to_bf16 if inp.dtype == "bf16" else round_to_f32
+    q = rnd(scale * rng.standard_normal(inp.q.shape))
+    k = rnd(scale * rng.standard_normal(inp.k.shape))
+    b = rnd(rng.standard_normal(inp.beta.shape))
+    return Inputs(q, k, inp.v, b, inp.d_o, inp.initial_state, inp.dfinal_state, inp.cu_seqlens, inp.dtype, dict(inp.meta))

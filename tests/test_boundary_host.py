@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     assert {"deltanet_fwd", "deltanet_bwd", "deltanet_recurrent_fwd", "deltanet_workspace_bytes",
             "deltanet_gated_fwd", "deltanet_gated_bwd", "deltanet_gated_recurrent_fwd",
             "deltanet_gated_workspace_bytes", "deltanet_status_string", "deltanet_fwd_save", "deltanet_bwd_saved",
-            "deltanet_gated_fwd_save", "deltanet_gated_bwd_saved"} <= set(syms)
+            "deltanet_gated_fwd_save", "deltanet_gated_bwd_saved", "deltanet_fused_fwd", "deltanet_fused_bwd",
+            "deltanet_fused_fwd_save", "deltanet_fused_bwd_saved"} <= set(syms)
     for s in syms:
         assert hasattr(lib, s), s
 
@@ -104,6 +105,15 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     assert lib.deltanet_gated_fwd_save(ctypes.byref(s), fake, fake, fake, fake, None, None, fake, None, fake, 1 << 40, None) == -1
     gs = [fake] * 5 + [fake, None, fake, fake, fake, fake, None, None]  # dg missing
     assert lib.deltanet_gated_bwd_saved(ctypes.byref(s), *gs, fake, 1 << 40, None) == -1
+    # the entry points with the prologue in the load path validate like the plain ones
+    assert lib.deltanet_fused_fwd(ctypes.byref(s), None, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -1
+    assert lib.deltanet_fused_fwd(ctypes.byref(s), *args, fake, 16, None) == -5
+    fb = [fake] * 4 + [None, fake, None, fake, fake, fake, fake, None]
+    assert lib.deltanet_fused_bwd(ctypes.byref(s), *fb, fake, 16, None) == -5
+    assert lib.deltanet_fused_bwd(ctypes.byref(_shape(d_k=256, d_v=256)), *fb, fake, 1 << 40, None) == -3
+    assert lib.deltanet_fused_fwd_save(ctypes.byref(s), *args, fake, fwd_only_bytes(lib, s), None) == -5
+    fs = [fake] * 4 + [fake, None, fake, fake, fake, None, None]  # dbeta_logit missing
+    assert lib.deltanet_fused_bwd_saved(ctypes.byref(s), *fs, fake, 1 << 40, None) == -1
 
 
 def fwd_only_bytes(lib, s):

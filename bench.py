@@ -266,15 +266,15 @@ def main() -> int:
     def gated_step():
         dn.deltanet_gated_fwd_save(q, k, v, beta, g, o=o, final_state=ST, saved=wsg)
         return dn.deltanet_gated_bwd_saved(q, k, v, beta, g, d_o, wsg)
-    for _ in range(3):
+    for _ in range(args.warmup):
         gated_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(rec_steps):
+    for _ in range(args.steps):
         gated_step()
     torch.cuda.synchronize()
-    gms = 1e3 * (time.perf_counter() - t0) / rec_steps
-    out["gated_fwd_bwd"] = {"ms": round(gms, 4), "tokens_per_s": round(tokens / (gms * 1e-3), 1), "steps": rec_steps,
+    gms = 1e3 * (time.perf_counter() - t0) / args.steps
+    out["gated_fwd_bwd"] = {"ms": round(gms, 4), "tokens_per_s": round(tokens / (gms * 1e-3), 1), "steps": args.steps,
                             "vs_plain": round(gms / ms_per_step, 3)}
 
     # The same step with the layer's prologue fused into the load path (SiLU + L2 norm of q and k, sigmoid of the beta
@@ -283,18 +283,21 @@ def main() -> int:
     pre = make_pre_activations(2, inp)
     qp, kp, bp = bf(pre.q), bf(pre.k), bf(pre.beta)
 
+    from paper_2406_06484_amd.binding import deltanet_fused_workspace_bytes
+    wsf = torch.empty(deltanet_fused_workspace_bytes(shp, True), dtype=torch.uint8, device=dev)
+
     def fused_step():
-        dn.deltanet_fused_fwd_save(qp, kp, v, bp, o=o, final_state=ST, saved=ws)
-        return dn.deltanet_fused_bwd_saved(qp, kp, v, bp, d_o, ws)
-    for _ in range(3):
+        dn.deltanet_fused_fwd_save(qp, kp, v, bp, o=o, final_state=ST, saved=wsf)
+        return dn.deltanet_fused_bwd_saved(qp, kp, v, bp, d_o, wsf)
+    for _ in range(args.warmup):
         fused_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(rec_steps):
+    for _ in range(args.steps):
         fused_step()
     torch.cuda.synchronize()
-    fms = 1e3 * (time.perf_counter() - t0) / rec_steps
-    out["fused_prologue_fwd_bwd"] = {"ms": round(fms, 4), "tokens_per_s": round(tokens / (fms * 1e-3), 1), "steps": rec_steps,
+    fms = 1e3 * (time.perf_counter() - t0) / args.steps
+    out["fused_prologue_fwd_bwd"] = {"ms": round(fms, 4), "tokens_per_s": round(tokens / (fms * 1e-3), 1), "steps": args.steps,
                                      "vs_plain": round(fms / ms_per_step, 3)}
 
     if not args.no_cpu_baseline:

@@ -121,15 +121,19 @@ int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, cons
  *
  *     q_t = SiLU(q_pre_t) / ||SiLU(q_pre_t)||_2 ,  k_t likewise,  beta_t = sigmoid(beta_logit_t)
  *
- * per token and head on their way to the LDS (fp32 arithmetic, result rounded to the element type as a
- * stored q, k would be), so q and k never make the round trip through HBM.  A row whose SiLU image is
- * exactly zero maps to zero (the paper gives no epsilon).  deltanet_fused_bwd returns the gradients with
- * respect to q_pre, k_pre and beta_logit (through the normalisation, the SiLU and the sigmoid) in
- * dq_pre, dk_pre (element type dtype) and dbeta_logit (fp32); dv and dinitial_state are as for
- * deltanet_bwd.  Workspace sizes are those of deltanet_workspace_bytes.  deltanet_fused_fwd_save /
+ * per token and head (fp32 arithmetic, result rounded to the element type).  The kernel that builds T
+ * maps q and k once and leaves them in the workspace for the chain scans; the backward's chunk kernel
+ * maps its tiles on their way to the LDS and sends dq, dk back through the map on their way out, so the
+ * gradients never reach HBM in the mapped coordinates and no separate elementwise pass runs in either
+ * direction.  A row whose SiLU image is exactly zero maps to zero (the paper gives no epsilon).
+ * deltanet_fused_bwd returns the gradients with respect to q_pre, k_pre and beta_logit (through the
+ * normalisation, the SiLU and the sigmoid) in dq_pre, dk_pre (element type dtype) and dbeta_logit
+ * (fp32); dv and dinitial_state are as for deltanet_bwd.  Workspace (and `saved`) sizes come from
+ * deltanet_fused_workspace_bytes: the plain sizes plus the mapped q and k.  deltanet_fused_fwd_save /
  * deltanet_fused_bwd_saved are the pair that keeps the forward pass's per-chunk results, as
  * deltanet_fwd_save / deltanet_bwd_saved.  Everything else is as for the plain calls.
  */
+int deltanet_fused_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes);
 int deltanet_fused_fwd(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v, const void *beta_logit,
                        const float *initial_state, void *o, float *final_state, void *workspace, size_t workspace_bytes,
                        void *hip_stream);

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     deltanet_fused_bwd_saved,
     deltanet_fused_fwd,
     deltanet_fused_fwd_save,
+    deltanet_fused_workspace_bytes,
     deltanet_fwd,
     deltanet_fwd_save,
     deltanet_gated_bwd,

@@ -75,6 +75,8 @@ def load_library():
         lib.deltanet_recurrent_fwd.argtypes = [sp] + [vp] * 7 + [vp]
         lib.deltanet_gated_workspace_bytes.restype = ctypes.c_int
         lib.deltanet_gated_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(sz)]
+        lib.deltanet_fused_workspace_bytes.restype = ctypes.c_int
+        lib.deltanet_fused_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(sz)]
         lib.deltanet_gated_fwd.restype = ctypes.c_int
         lib.deltanet_gated_fwd.argtypes = [sp] + [vp] * 8 + [vp, sz, vp]
         lib.deltanet_gated_bwd.restype = ctypes.c_int
@@ -179,9 +181,16 @@ def deltanet_gated_workspace_bytes(shape: dn_shape, want_bwd: bool) -> int:
     return int(out.value)
 
 
-def _workspace(shape, want_bwd, workspace, device, gated=False):
+def deltanet_fused_workspace_bytes(shape: dn_shape, want_bwd: bool) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().deltanet_fused_workspace_bytes(ctypes.byref(shape), int(bool(want_bwd)), ctypes.byref(out)))
+    return int(out.value)
+
+
+def _workspace(shape, want_bwd, workspace, device, gated=False, pro=False):
     import torch
-    need = (deltanet_gated_workspace_bytes if gated else deltanet_workspace_bytes)(shape, want_bwd)
+    query = deltanet_fused_workspace_bytes if pro else (deltanet_gated_workspace_bytes if gated else deltanet_workspace_bytes)
+    need = query(shape, want_bwd)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
     return workspace, workspace.numel() * workspace.element_size()
@@ -212,7 +221,7 @@ def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: i
         final_state = torch.empty(st_shape, dtype=torch.float32, device=q.device)
     if final_state is not None:
         _req(final_state, "final_state", torch.float32, st_shape)
-    workspace, wbytes = _workspace(s, _save, workspace, q.device, _g is not None)
+    workspace, wbytes = _workspace(s, _save, workspace, q.device, _g is not None, _pro)
     if _g is None:
         if _pro:
             fn = lib.deltanet_fused_fwd_save if _save else lib.deltanet_fused_fwd
@@ -306,7 +315,7 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
     dS0 = torch.empty(st_shape, dtype=torch.float32, device=q.device) if want_dinitial_state else None
     if _saved and workspace is None:
         raise ValueError("saved must be the buffer returned by the matching forward call")
-    workspace, wbytes = _workspace(s, True, workspace, q.device, _g is not None)
+    workspace, wbytes = _workspace(s, True, workspace, q.device, _g is not None, _pro)
     if _saved and _g is None:
         fn = lib.deltanet_fused_bwd_saved if _pro else lib.deltanet_bwd_saved
         _check(fn(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(d_o), _p(dfinal_state),

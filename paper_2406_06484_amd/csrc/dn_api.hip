@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, total;
+    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_Qm, off_Km, total;
     size_t esz;
 };
 
@@ -93,7 +93,7 @@ int validate_shape(const dn_shape *s, const Impl **impl, bool need_impl = true) 
     return *impl ? DN_OK : DN_ERR_UNSUPPORTED;
 }
 
-void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false) {
+void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bool prologue = false) {
     memset(pl, 0, sizeof(*pl));
     Problem &pb = pl->pb;
     const bool packed = s->cu_seqlens != nullptr;
@@ -122,12 +122,17 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false) {
     if (gated) {
         pl->off_gam = o; o += up256(tiles * 2 * kChunk * sizeof(float)); // gamma_i and 1 / gamma_i per chunk row
     }
+    if (prologue) { // q and k after the feature map, in the layout of q and k
+        const size_t tQ = up256((size_t)s->B * s->L * s->H * s->d_k * pl->esz);
+        pl->off_Qm = o; o += tQ;
+        pl->off_Km = o; o += tQ;
+    }
     pl->total = o;
 }
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
-void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd, bool gated = false) {
+void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd, bool gated = false, bool prologue = false) {
     unsigned char *b = static_cast<unsigned char *>(ws);
     pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
     p->Tm = b + pl.off_T;
@@ -139,6 +144,9 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     }
     if (gated) {
         p->gam = reinterpret_cast<float *>(b + pl.off_gam);
+    }
+    if (prologue) {
+        p->Qm = b + pl.off_Qm; p->Km = b + pl.off_Km;
     }
 }
 
@@ -161,7 +169,7 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, workspace, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
     Plan pl;
-    make_plan(shape, save, &pl, gated);
+    make_plan(shape, save, &pl, gated, prologue);
     if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
     if (int rc = check_device(impl, &pl.pb)) return rc;
     Ptrs p;
@@ -170,7 +178,7 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     pl.pb.save = save;
     p.pro = prologue;
-    bind_workspace(pl, workspace, &p, &pl.pb, save, gated);
+    bind_workspace(pl, workspace, &p, &pl.pb, save, gated, prologue);
     return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
 
@@ -186,7 +194,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
                         workspace, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
     Plan pl;
-    make_plan(shape, 1, &pl, gated);
+    make_plan(shape, 1, &pl, gated, prologue);
     if (pl.total && (!workspace || workspace_bytes < pl.total)) return DN_ERR_WORKSPACE;
     if (int rc = check_device(impl, &pl.pb)) return rc;
     Ptrs p;
@@ -196,7 +204,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     pl.pb.save = saved;
     p.pro = prologue;
-    bind_workspace(pl, workspace, &p, &pl.pb, true, gated);
+    bind_workspace(pl, workspace, &p, &pl.pb, true, gated, prologue);
     return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
 
@@ -240,6 +248,17 @@ int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, cons
                        float *dinitial_state, void *saved, size_t saved_bytes, void *hip_stream) {
     return bwd_impl(shape, q, k, v, beta, nullptr, false, nullptr, d_o, dfinal_state, dq, dk, dv, dbeta, nullptr,
                     dinitial_state, saved, saved_bytes, hip_stream, true);
+}
+
+int deltanet_fused_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_bytes) {
+    if (!out_bytes) return DN_ERR_NULL;
+    const Impl *impl = nullptr;
+    if (int rc = validate_shape(shape, &impl)) return rc;
+    if (want_bwd && !impl->bwd) return DN_ERR_UNSUPPORTED;
+    Plan pl;
+    make_plan(shape, want_bwd, &pl, false, true);
+    *out_bytes = pl.total;
+    return DN_OK;
 }
 
 int deltanet_fused_fwd(const dn_shape *shape, const void *q_pre, const void *k_pre, const void *v, const void *beta_logit,

@@ -254,61 +254,6 @@ __device__ inline void stage_flush_dot(const T *stage, T *dst, long row_stride, 
     }
     wave_lds_fence();
 }
-// Backward of the feature map y = SiLU(x) / ||SiLU(x)|| for one staged 32 x 32 tile of dy, in two steps
-// with a workgroup barrier between them (a row's dot product y . dy spans the tiles of several waves).
-// Step 1: this tile's share of the row dot products, slot[row0 + r] = sum_c dy(r, c) * y(row0 + r, col0 + c)
-// with y in LDS, and the matching block of x requested from global memory (`raw`, consumed by step 2).
-template <typename T> struct FmapRaw { uint4 v[32 * Stage<T>::SEGS / 64]; };
-template <typename T>
-__device__ inline void stage_fmap_dots(const T *stage, int row0, int col0, int nvalid, const T *y, int ldy, float *slot,
-                                       const T *x, long row_stride, FmapRaw<T> &raw) {
-    constexpr int SEGS = Stage<T>::SEGS, VEC = El<T>::VEC;
-    const int lane = threadIdx.x & 63;
-    wave_lds_fence();
-#pragma unroll
-    for (int it = 0; it < 32 * SEGS / 64; ++it) {
-        const int idx = it * 64 + lane, r = idx / SEGS, sg = idx % SEGS;
-        alignas(16) T a[VEC], b[VEC];
-        raw.v[it] = make_uint4(0, 0, 0, 0);
-        if (row0 + r < nvalid) raw.v[it] = *reinterpret_cast<const uint4 *>(x + (long)(row0 + r) * row_stride + col0 + sg * VEC);
-        *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(stage + r * Stage<T>::LD + sg * VEC);
-        *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(y + (row0 + r) * ldy + col0 + sg * VEC);
-        float s = 0.f;
-#pragma unroll
-        for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
-#pragma unroll
-        for (int d = 1; d < SEGS; d <<= 1) s += __shfl_xor(s, d); // the SEGS lanes of one row are adjacent
-        if (sg == 0) slot[row0 + r] = s;
-    }
-}
-// Step 2: dx = SiLU'(x) (dy - y (y . dy)) / ||SiLU(x)||, written to global memory.  dots = the NB column
-// blocks' shares of y . dy ([NB][C] floats), inv = 1 / ||SiLU(x)|| per row.
-template <typename T, int NB>
-__device__ inline void stage_fmap_flush(const T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, const T *y,
-                                        int ldy, const float *dots, const float *inv, const FmapRaw<T> &raw) {
-    constexpr int SEGS = Stage<T>::SEGS, VEC = El<T>::VEC;
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int it = 0; it < 32 * SEGS / 64; ++it) {
-        const int idx = it * 64 + lane, r = idx / SEGS, sg = idx % SEGS;
-        alignas(16) T a[VEC], b[VEC], x[VEC];
-        *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(stage + r * Stage<T>::LD + sg * VEC);
-        *reinterpret_cast<uint4 *>(b) = *reinterpret_cast<const uint4 *>(y + (row0 + r) * ldy + col0 + sg * VEC);
-        *reinterpret_cast<uint4 *>(x) = raw.v[it];
-        float dot = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) dot += dots[nb * C + row0 + r];
-        const float rn = inv[row0 + r];
-#pragma unroll
-        for (int u = 0; u < VEC; ++u) {
-            const float xv = to_f32(x[u]), sg_ = sigmoid_f32(xv);
-            a[u] = from_f32<T>((to_f32(a[u]) - to_f32(b[u]) * dot) * rn * sg_ * (1.f + xv * (1.f - sg_)));
-        }
-        if (row0 + r < nvalid)
-            *reinterpret_cast<uint4 *>(dst + (long)(row0 + r) * row_stride + col0 + sg * VEC) = *reinterpret_cast<const uint4 *>(a);
-    }
-    wave_lds_fence(); // the staging tile may be rewritten right away
-}
 // dst[row0 + r][col0 + c] = acc(r, c), rows >= nvalid dropped; `stage` is this wave's staging tile
 template <typename T>
 __device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc) {
@@ -373,15 +318,51 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
 #pragma unroll
             for (int u = 0; u < VEC; ++u) e[u] = from_f32<T>(__fmul_rn(sv[u], inv[it]));
             v[it] = *reinterpret_cast<const uint4 *>(e);
+            __builtin_amdgcn_sched_barrier(0); // one step at a time: interleaved, the steps' temporaries do not fit
         }
     }
-    // parks inv[] of feature_map in dst[row], one lane per row
-    __device__ inline void store_row_values(float *dst, const float (&f)[NIT], int t = threadIdx.x) const {
-        const int tr = t / TPR;
-        if (t % TPR == 0) {
+    // the same map, written to an LDS tile; the held tile keeps the pre-activations for feature_map_bwd_store
+    __device__ inline void feature_map_to(T *dst, int ld, float (&inv)[NIT], int t = threadIdx.x) const {
+        TileRegs y = *this;
+        y.feature_map(inv);
+        y.store(dst, ld, t);
+    }
+    // Gradient through the map, for a tile whose pre-activations x this object still holds: src = dy in LDS
+    // (same shape, leading dimension ld), inv[] from feature_map_to;
+    //     dx = SiLU'(x) (dy - y (y . dy)) / ||SiLU(x)||,  SiLU'(x) = sig (1 + x (1 - sig)),
+    // written to global memory (rows >= nvalid dropped).  A row's dot product is a butterfly over its TPR lanes.
+    __device__ inline void feature_map_bwd_store(const T *src, int ld, const float (&inv)[NIT], T *dst, long row_stride, int nvalid,
+                                                 int t = threadIdx.x) const {
+        const int tr = t / TPR, tc = (t % TPR) * VEC;
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) dst[it * RPI + tr] = f[it];
+        for (int it = 0; it < NIT; ++it) {
+            alignas(16) T x[VEC], a[VEC];
+            *reinterpret_cast<uint4 *>(x) = v[it];
+            *reinterpret_cast<uint4 *>(a) = *reinterpret_cast<const uint4 *>(src + (it * RPI + tr) * ld + tc);
+            float y[VEC], dsl[VEC], dot = 0.f;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) {
+                const float xv = to_f32(x[u]), sg = sigmoid_f32(xv);
+                y[u] = __fmul_rn(__fmul_rn(xv, sg), inv[it]);
+                dsl[u] = sg * (1.f + xv * (1.f - sg)) * inv[it];
+                dot += to_f32(a[u]) * y[u];
+            }
+#pragma unroll
+            for (int d = 1; d < TPR; d <<= 1) dot += __shfl_xor(dot, d);
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) a[u] = from_f32<T>((to_f32(a[u]) - y[u] * dot) * dsl[u]);
+            if (it * RPI + tr < nvalid)
+                *reinterpret_cast<uint4 *>(dst + (long)(it * RPI + tr) * row_stride + tc) = *reinterpret_cast<const uint4 *>(a);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    }
+    // held tile -> global memory (rows >= nvalid dropped)
+    __device__ inline void store_global(T *dst, long row_stride, int nvalid, int t = threadIdx.x) const {
+        const int tr = t / TPR, tc = (t % TPR) * VEC;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+            if (it * RPI + tr < nvalid)
+                *reinterpret_cast<uint4 *>(dst + (long)(it * RPI + tr) * row_stride + tc) = v[it];
     }
     // Per-row factors for scale_rows: f[it] = src[row held in step it] (rows of the tile this lane touches).
     __device__ inline void load_row_factors(float (&f)[NIT], const float *src, int t = threadIdx.x) const {

@@ -32,8 +32,9 @@ struct Ptrs {
     const float *g;
     float *dg, *gam;
     // prologue variant: q and k hold the pre-activations of the feature map, beta the logits; dq, dk and
-    // dbeta receive the gradients with respect to those
+    // dbeta receive the gradients with respect to those; workspace: Qm, Km = q, k after the map (layout of q, k)
     int pro;
+    void *Qm, *Km;
 };
 
 // Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is

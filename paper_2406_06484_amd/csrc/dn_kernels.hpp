@@ -16,9 +16,11 @@ namespace dn {
 
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 // Kernel variants (a compile-time template argument, so that each carries only its own registers):
-// the plain delta rule; the gated rule; the plain rule with the layer's prologue in the load path
-// (q, k = SiLU(x) / ||SiLU(x)||_2 of section 3.3, beta = sigmoid(b) of section 2.2) and its gradient
-// in the store path.
+// the plain delta rule; the gated rule; the plain rule with the layer's prologue (q, k = SiLU(x) /
+// ||SiLU(x)||_2 of section 3.3, beta = sigmoid(b) of section 2.2).  For the prologue k_wy_prep maps q
+// and k once and leaves them in the workspace for the scans, which run the plain variant on them;
+// k_bwd_chunk maps its tiles itself on the way to LDS and sends the gradients back through the map on
+// the way out, so dq, dk never reach HBM in the mapped coordinates.
 enum { VAR_PLAIN = 0, VAR_GATED = 1, VAR_PROLOGUE = 2 };
 constexpr size_t align16(size_t x) { return (x + 15) & ~size_t(15); }
 
@@ -85,9 +87,14 @@ __global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     {
         TileRegs<T, C, DK> kr;
         kr.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        if (p.pro) { // prologue variant: k arrives before the feature map of section 3.3
+        if (p.pro) { // prologue variant: q and k arrive before the feature map of section 3.3
+            TileRegs<T, C, DK> qr;
+            qr.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
             float inv[TileRegs<T, C, DK>::NIT];
             kr.feature_map(inv);
+            kr.store_global((T *)p.Km + (row0 * H + h) * DK, (long)H * DK, nvalid);
+            qr.feature_map(inv);
+            qr.store_global((T *)p.Qm + (row0 * H + h) * DK, (long)H * DK, nvalid);
         }
         kr.store(sK, SM::LD);
     }
@@ -203,7 +210,8 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
 template <typename T, int DK, int DV, int MODE, int VAR>
 __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanFwdSmem<T, DK, DV>;
-    constexpr bool GATED = VAR == VAR_GATED, PRO = VAR == VAR_PROLOGUE;
+    static_assert(VAR != VAR_PROLOGUE, "the scans read q and k already mapped");
+    constexpr bool GATED = VAR == VAR_GATED;
     constexpr bool OUT = MODE != SCAN_STORE, SAVE = MODE != SCAN_OUT;
     constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
@@ -221,7 +229,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = (GATED || PRO || MODE == SCAN_BOTH) ? 2 : (DK > 128 ? 4 : 0); // SCAN_BOTH: the loader waves hold more
+    constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (DK > 128 ? 4 : 0); // SCAN_BOTH: the loader waves hold more
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -281,11 +289,6 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
                            min(C, len - icp * C));
     };
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
-        if (PRO) { // the feature map of section 3.3, applied on the way to LDS
-            float inv[TileRegs<T, C, DK, NTL>::NIT];
-            if (OUT) r.q.feature_map(inv);
-            r.k.feature_map(inv);
-        }
         if (OUT) r.q.store(sQ, SM::LQ, lt);
         r.k.store(sK, SM::LK, lt);
         if (gated) { // the chunk runs the plain rule on v_i / gamma_i
@@ -409,7 +412,8 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
 template <typename T, int DK, int DV, int VAR>
 __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanBwdSmem<T, DK, DV>;
-    constexpr bool GATED = VAR == VAR_GATED, PRO = VAR == VAR_PROLOGUE;
+    static_assert(VAR != VAR_PROLOGUE, "the scans read q and k already mapped");
+    constexpr bool GATED = VAR == VAR_GATED;
     constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
     constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
@@ -472,11 +476,6 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
     auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
-        if (PRO) { // the feature map of section 3.3, applied on the way to LDS
-            float inv[TileRegs<T, C, DK, NTL>::NIT];
-            r.q.feature_map(inv);
-            r.k.feature_map(inv);
-        }
         r.q.store(sQ, SM::LQ, lt); r.k.store(sK, SM::LK, lt);
         if (gated) r.d_o.scale_rows(r.dos); // o_i = gamma_i o~_i, so the plain rule's output gradient is gamma_i dO_i
         r.d_o.store(sDO, SM::LD, lt);
@@ -604,6 +603,7 @@ __device__ inline TilePos tile_pos(const SeqMap &sm, int H, int gid, int h) {
 // registers until their buffer is free.
 template <typename T, int DK, int DV> struct ChunkSmem {
     static constexpr int LK = ldn<T>(DK), LV = ldn<T>(DV), LT = ldn<T>(C), LF = C + 4;
+    static constexpr int LQO = ldc<T>(DK); // rows of the dq / dk matrix of the prologue variant
     static constexpr int LU = ldc<T>(C), LSK = ldn<T>(DK); // rows of Ut^T / dUt^T ([d_v][C]) and of S^T / dS'^T ([d_v][d_k])
     static constexpr size_t szX = sizeof(float) * C * LF, szCC = sizeof(T) * C * LT;
     static constexpr size_t oB1 = 0;                                   // dO; V; dA o G (fp32)
@@ -631,7 +631,6 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     constexpr int KT = 2 * (DK / 32), VT = 2 * (DV / 32);        // 32 x 32 tiles of a C x DK / C x DV matrix
     constexpr int KW = (KT + NWC - 1) / NWC, VW = (VT + NWC - 1) / NWC; // ... per wave
     extern __shared__ __align__(16) unsigned char smem[];
-    T *stg = reinterpret_cast<T *>(smem + SM::oStage) + (threadIdx.x >> 6) * Stage<T>::ELEMS;
     T *sDO = reinterpret_cast<T *>(smem + SM::oB1), *sV = sDO;
     float *sProd = reinterpret_cast<float *>(smem + SM::oB1);
     T *sUt = reinterpret_cast<T *>(smem + SM::oB2), *sDW = sUt;
@@ -646,13 +645,16 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     float *sDb = reinterpret_cast<float *>(smem + SM::oDb);
     float *sZ = reinterpret_cast<float *>(smem + SM::oZ);
     float *sCq = reinterpret_cast<float *>(smem + SM::oCq), *sCv = reinterpret_cast<float *>(smem + SM::oCv);
-    float *sNq = sGam, *sNk = sGam + C; // prologue variant: 1 / ||SiLU(q_i)||, 1 / ||SiLU(k_i)|| (the gate's table is not in use)
+    // prologue variant: dq (dk) as a C x d_k matrix, in bytes that are free when it is complete, for the way back through the map
+    T *sDQ = reinterpret_cast<T *>(smem + SM::oB1), *sDK = reinterpret_cast<T *>(smem + SM::oB2);
+    static_assert(!PRO || (sizeof(T) * C * SM::LQO <= SM::oB2 - SM::oB1 && sizeof(T) * C * SM::LQO <= SM::oB3 - SM::oB2), "dq / dk staging");
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
-    const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
+    constexpr int MB = PRO ? 2 : ((DK > 128 || GATED) ? 4 : 0);
+    const int tid = threadIdx.x, lane = tid & 63;
+    // The wave number, and with it every tile offset derived from it, is recomputed per tile in the variants
+    // that are short of registers: hoisted out of the tile loop, those offsets alone would take some 90 VGPRs.
+    int wave = tid >> 6;
     // tile number sI of this wave in a C x DK (C x DV) matrix: row block ka, column block kb
     auto kt = [&](int sI) __attribute__((always_inline)) { return wave + sI * NWC; };
     auto ka = [&](int sI) __attribute__((always_inline)) { return kt(sI) / (DK / 32); };
@@ -699,6 +701,10 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     for (TileIter it(chunks_total, H); it.valid(); it.next()) {
         const TilePos cur = pos_of(it);
         if (!cur.ok) continue; // packed layout: past the last real chunk
+        asm volatile("" : "+v"(wave)); // opaque: see above
+        const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
+        const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
+        T *stg = reinterpret_cast<T *>(smem + SM::oStage) + wave * Stage<T>::ELEMS;
         fetch(cur);
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
@@ -710,12 +716,15 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (gated) r.d_o.scale_rows(r.dos);
         r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LU); r.s.store(sS, SM::LSK);
         r.dut.store(sDU, SM::LU);
-        if (PRO) { // the feature map of section 3.3 on the way to LDS; the norms wait for the store path
-            float inv[TileRegs<T, C, DK, NTC>::NIT];
-            r.k.feature_map(inv); r.k.store_row_values(sNk, inv);
-            r.q.feature_map(inv); r.q.store_row_values(sNq, inv);
+        // prologue variant: the feature map of section 3.3 on the way to LDS; the pre-activations stay in
+        // r.q / r.k and the norms in qinv / kinv for the way back
+        float qinv[TileRegs<T, C, DK, NTC>::NIT], kinv[TileRegs<T, C, DK, NTC>::NIT];
+        if (PRO) {
+            r.k.feature_map_to(sK, SM::LK, kinv);
+            r.q.feature_map_to(sQ, SM::LK, qinv);
+        } else {
+            r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
         }
-        r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
         if (tid < C) {
             float b = tid < nvalid ? to_f32(r.beta) : 0.f;
             if (PRO) b = tid < nvalid ? sigmoid_f32(b) : 0.f; // beta = sigmoid(logit), section 2.2
@@ -730,7 +739,6 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc);
         }
         f32x16 dq[KW], dw[KW], dk1[KW];
-        FmapRaw<T> raw[KW]; // prologue variant: the pre-activation block behind this wave's dq (later dk) tile
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) {
             dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
@@ -750,22 +758,15 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI]);
                 stage_flush_dot<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sQ, SM::LK,
                                    sCq + kb(sI) * C);
-            } else if (PRO) { // dq waits in the staging tile until every wave's share of q_i . dq_i is in
-                static_assert(!PRO || KW == 1, "one staging tile per wave");
-                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI]);
-                stage_fmap_dots<T>(stg, 32 * ka(sI), 32 * kb(sI), nvalid, sQ, SM::LK, sCq + kb(sI) * C,
-                                   (const T *)p.q + (row0 * H + h) * DK, (long)H * DK, raw[sI]);
+            } else if (PRO) { // dO's bytes are free: dq is assembled there for the way back through the map
+                acc_to_lds<T>(sDQ, SM::LQO, 32 * ka(sI), 32 * kb(sI), dq[sI]);
             } else {
                 acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI]);
             }
         }
         lds_barrier();
-        if (PRO) { // gradient through the feature map: dq~ = SiLU'(q~) (dq - q (q . dq)) / ||SiLU(q~)||
-#pragma unroll
-            for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT)
-                stage_fmap_flush<T, DK / 32>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sQ,
-                                             SM::LK, sCq, sNq, raw[sI]);
-        }
+        if (PRO) // gradient through the feature map: dq~ = SiLU'(q~) (dq - q (q . dq)) / ||SiLU(q~)||
+            r.q.feature_map_bwd_store(sDQ, SM::LQO, qinv, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, nvalid);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
             if (gated) { // <K, Ut dS~'^T>, the second half of <dS_C, S_C>, taken while dK1 holds just that product
@@ -863,10 +864,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             else mma<C, false, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
             if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK);
             else mma<C, true, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
-            if (PRO) {
-                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dk1[sI]);
-                stage_fmap_dots<T>(stg, 32 * ka(sI), 32 * kb(sI), nvalid, sK, SM::LK, sCq + kb(sI) * C,
-                                   (const T *)p.k + (row0 * H + h) * DK, (long)H * DK, raw[sI]);
+            if (PRO) { // dW's bytes are free
+                acc_to_lds<T>(sDK, SM::LQO, 32 * ka(sI), 32 * kb(sI), dk1[sI]);
             } else {
                 acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
             }
@@ -905,12 +904,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 p.dbeta[(row0 + i) * H + h] = db;
             }
         }
-        if (PRO) { // every wave's share of k_i . dk_i is in: gradient through the feature map, as for dq
+        if (PRO) { // dk is assembled: back through the feature map, as for dq
             lds_barrier();
-#pragma unroll
-            for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT)
-                stage_fmap_flush<T, DK / 32>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sK,
-                                             SM::LK, sCq, sNk, raw[sI]);
+            r.k.feature_map_bwd_store(sDK, SM::LQO, kinv, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, nvalid);
         }
         lds_barrier(); // every buffer is free for the next tile
     }

@@ -56,7 +56,13 @@ template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
     return PrepSmem<T, DK, DV>::bytes > ScanFwdSmem<T, DK, DV>::bytes ? PrepSmem<T, DK, DV>::bytes : ScanFwdSmem<T, DK, DV>::bytes;
 }
 
-// launches kernel<T, DK, DV, variant> for the variant the pointers ask for
+// launches kernel<T, DK, DV, variant> for the variant the pointers ask for.  The scans know two variants
+// (for the prologue they run the plain one on the q, k that k_wy_prep mapped), the chunk kernel three.
+#define DN_LAUNCH_SCAN(kernel, grid, nthreads, lds, ...)                                                    \
+    do {                                                                                                    \
+        if (p.g) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_GATED>), grid, nthreads, lds, __VA_ARGS__);            \
+        else DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__);                \
+    } while (0)
 #define DN_LAUNCH_VAR(kernel, grid, nthreads, lds, ...)                                                     \
     do {                                                                                                    \
         if (p.g) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_GATED>), grid, nthreads, lds, __VA_ARGS__);            \
@@ -64,19 +70,27 @@ template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
         else DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__);                \
     } while (0)
 
+// what the scans see: with the prologue, the mapped q and k in the workspace
+static inline Ptrs scan_ptrs(const Ptrs &p) {
+    Ptrs ps = p;
+    if (p.pro) { ps.q = p.Qm; ps.k = p.Km; ps.pro = 0; }
+    return ps;
+}
+
 template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0 || pb.chunks_ub == 0) return 0;
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    const Ptrs ps = scan_ptrs(p);
     if constexpr (kHasBwd<T, DK, DV>) {
         if (pb.save) {
-            DN_LAUNCH_VAR(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+            DN_LAUNCH_SCAN(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
             return 0;
         }
     }
-    DN_LAUNCH_VAR(k_scan_fwd, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+    DN_LAUNCH_SCAN(k_scan_fwd, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
     return 0;
 }
 
@@ -85,14 +99,15 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
+    const Ptrs ps = scan_ptrs(p);
     if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
-        DN_LAUNCH_VAR(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, p);
+        DN_LAUNCH_SCAN(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
     } else {
         if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
         // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
         const dim3 gpair(2 * gchain.x);
-        DN_LAUNCH_VAR(k_scan_pair, gpair, NTS, lds, sm, pb.H, p, (int)gchain.x);
+        DN_LAUNCH_SCAN(k_scan_pair, gpair, NTS, lds, sm, pb.H, ps, (int)gchain.x);
     }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;

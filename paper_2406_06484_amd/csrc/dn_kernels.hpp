@@ -672,12 +672,18 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         // gated: gamma of this lane's dO rows, 1 / gamma of its V rows; entry tid of the chunk's table of gamma_i, 1 / gamma_i
         float dos[TileRegs<T, C, DV, NTC>::NIT], vsc[TileRegs<T, C, DV, NTC>::NIT], gm;
     } r;
-    auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
+    // The first four tiles of a chunk are requested separately: where registers allow (the plain variant),
+    // the next chunk's are already on their way while this chunk's last products run.
+    auto fetch_early = [&](const TilePos &tp) __attribute__((always_inline)) {
         if (!tp.ok) return;
         r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
         r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV);
         r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV);
         r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV);
+        if (gated) r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
+    };
+    auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
+        if (!tp.ok) return;
         r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
         r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
         if (tid < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tid, tp.nvalid - 1)) * H + tp.h];
@@ -685,7 +691,6 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
         r.x.load((const T *)p.Xm + tp.tile * C * C, C, C);
         if (gated) {
-            r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
             r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
             if (tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
         }
@@ -698,13 +703,16 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     // bursts of neighbouring CUs interleave with each other's MFMA phases.
     if ((long)chunks_total * H >= 4l * gridDim.x)
         for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(127);
+    constexpr bool AHEAD = VAR != VAR_PROLOGUE;
+    bool ahead = false; // this chunk's first four tiles were requested during the previous chunk
     for (TileIter it(chunks_total, H); it.valid(); it.next()) {
         const TilePos cur = pos_of(it);
-        if (!cur.ok) continue; // packed layout: past the last real chunk
+        if (!cur.ok) continue; // packed layout: past the last real chunk (so is every later one)
         asm volatile("" : "+v"(wave)); // opaque: see above
         const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
         const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
         T *stg = reinterpret_cast<T *>(smem + SM::oStage) + wave * Stage<T>::ELEMS;
+        if (!ahead) fetch_early(cur);
         fetch(cur);
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
@@ -836,6 +844,13 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
         lds_barrier(); // dX is dead
+        if (AHEAD) { // d_o, Ut^T, S^T, dUt^T of the next chunk: their registers have been free since this chunk's first barrier
+            TileIter nx = it;
+            nx.next();
+            const TilePos np = pos_of(nx);
+            ahead = np.ok;
+            fetch_early(np);
+        }
         if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {

@@ -281,10 +281,12 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     // step left in LDS (its Ut^T, or its staged output tile).  The compiler drains the memory counter
     // when the loaded registers are moved to LDS at the top of the next step; by then all of it is a
     // full step old.
-    auto flush_prev = [&](int icp) __attribute__((always_inline)) { // results of chunk icp, still in LDS
+    auto flush_ut = [&](int icp) __attribute__((always_inline)) { // Ut^T of chunk icp, still in LDS
         const long tile = ((long)(cb + icp) * H + h);
-        if (SAVE) copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt); // Ut^T
-        if (OUT && m.does_o)
+        copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt);
+    };
+    auto flush_out = [&](int icp) __attribute__((always_inline)) { // this wave's staged output tile of chunk icp
+        if (m.does_o)
             stage_flush<T>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
                            min(C, len - icp * C));
     };
@@ -311,6 +313,12 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         lds_barrier();
         if (loader && ic + 1 < nchunks) fetch_a(ic + 1);
+        if (MODE == SCAN_BOTH && loader) {
+            // the tiles kept for the backward pass leave in this interval, in which the loader waves have no product
+            // of their own: the chunk-initial state (transposed, as it sits in LDS) and the previous chunk's Ut^T
+            copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (ic > 0) copy_out<T, BV, C, NTL>((T *)p.Ut + ((tile - H) * DV + vb) * C, ((ic - 1) & 1) ? sUT1 : sUT0, SM::LT, lt);
+        }
         f32x16 acc = zero16();
         if (!loader) {
             // What does not depend on the state, while the loader waves are busy with global memory.
@@ -350,8 +358,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (loader) {
             if (ic + 1 < nchunks) fetch_b(ic + 1);
             // the chunk-initial state leaves transposed, as it sits in LDS
-            if (SAVE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
-            if (!SAVE && ic > 0) flush_prev(ic - 1);
+            if (MODE == SCAN_STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (OUT && ic > 0) flush_out(ic - 1);
         }
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
             f32x16 ws = zero16();
@@ -362,7 +370,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             mma<DK, false, false, T, true, MB>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
-        if (SAVE && loader && ic > 0) flush_prev(ic - 1);
+        if (MODE == SCAN_STORE && loader && ic > 0) flush_ut(ic - 1);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T, true, MB>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T, true, MB>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -376,7 +384,10 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         // compiler puts in front counts the stores issued after the loads and lets those stay in flight.
         if (loader && ic + 1 < nchunks) stash();
     }
-    if (loader && nchunks > 0) flush_prev(nchunks - 1);
+    if (loader && nchunks > 0) {
+        if (SAVE) flush_ut(nchunks - 1);
+        if (OUT) flush_out(nchunks - 1);
+    }
     if (OUT && p.ST && m.has_s) {
         float *dst = p.ST + (long)chain * DK * DV + vb;
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });

@@ -309,7 +309,7 @@ def main() -> int:
             oracle.fwd(inp.q, inp.k, inp.v, inp.beta)
             oracle.bwd(inp.q, inp.k, inp.v, inp.beta, inp.d_o)
             reps += 1
-            if time.perf_counter() - t0 >= 10.0 or reps >= 3:
+            if time.perf_counter() - t0 >= 10.0 or reps >= 12:
                 break
         cdt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(tokens * reps / cdt, 1), "unit": "tokens/s", "cores": nthr, "kind": "oracle",

@@ -710,10 +710,11 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
 
     // Workgroups that start together stay in lockstep: every CU issues its tile's load burst at the same
     // moment and then all of them compute while HBM idles.  When each workgroup has several tiles to
-    // walk, delay it by (blockIdx mod 4) quarter-tiles (one s_sleep(127) is about 8K cycles) so the
-    // bursts of neighbouring CUs interleave with each other's MFMA phases.
+    // walk, delay it by (blockIdx mod 4) steps of s_sleep(64), about 4K cycles each (an eighth of a tile's
+    // time; measured best among none, 2K, 4K and 8K), so the bursts of neighbouring CUs interleave with
+    // each other's MFMA phases.
     if ((long)chunks_total * H >= 4l * gridDim.x)
-        for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(127);
+        for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(64);
     constexpr bool AHEAD = VAR != VAR_PROLOGUE;
     bool ahead = false; // this chunk's first four tiles were requested during the previous chunk
     for (TileIter it(chunks_total, H); it.valid(); it.next()) {

@@ -5,6 +5,8 @@
 //   k_scan_fwd   per chain x v-block  serial over chunks: W = T K, U = T V (Eq. 11); Ut = U - W S; O = Q S + P Ut; S += K^T Ut  (Eq. 8-9)
 //   k_scan_pair  per chain x v-block  backward: the state-recompute scan (stores chunk-initial S and Ut) and the reverse
 //                                     scan (dUt = P^T dO + K dS'; dS = dS' + Q^T dO - W^T dUt) as one grid
+//   k_scan_fwd_save / k_scan_bwd      the forward scan that also stores what the recompute scan would, and the reverse
+//                                     scan alone, for a backward pass that keeps the forward pass's tiles
 //   k_bwd_chunk  per chunk            adjoint of Eq. 8-9 given S, dS', Ut, dUt, then adjoint of Eq. 10-11: dQ, dK, dV, dbeta
 //
 // State S is [d_k][d_v] (orientation of the paper's pseudocode listing), fp32 in registers.

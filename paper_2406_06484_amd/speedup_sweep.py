@@ -3,9 +3,10 @@
 
 The workload is the one of the paper's speed-up figure (section 3.3): model width 2048 split into
 heads of size d (H = 2048 / d), batch times length fixed at 16384 tokens, bf16, random unit-norm
-q, k.  For each (d, L) it times the forward pass of both forms through the C ABI (and the chunkwise
-forward + backward) and prints one table row; the chunkwise backward is compiled for d = 64 and
-128, the forward passes also for d = 256.
+q, k.  For each (d, L) it times the forward pass of both forms through the C ABI, the chunkwise
+forward + backward as the self-contained pair and as the pair that keeps the forward pass's tiles,
+and prints one table row; the chunkwise backward is compiled for d = 64 and 128, the forward passes
+also for d = 256.
 
     python -m paper_2406_06484_amd.speedup_sweep [--steps 20]
 """
@@ -43,7 +44,8 @@ def main() -> int:
         torch.cuda.synchronize()
         return 1e3 * (time.perf_counter() - t0) / args.steps
 
-    print("%5s %6s %4s %4s | %12s %12s %9s | %14s" % ("d", "L", "B", "H", "recurrent ms", "chunkwise ms", "speed-up", "chunk fwd+bwd ms"))
+    print("%5s %6s %4s %4s | %12s %12s %9s | %16s %16s" % ("d", "L", "B", "H", "recurrent ms", "chunkwise ms", "speed-up",
+                                                        "fwd+bwd ms", "fwd+bwd kept ms"))
     for d in (64, 128, 256):
         H = args.width // d
         for L in (512, 1024, 2048, 4096, 8192, 16384):
@@ -64,10 +66,15 @@ def main() -> int:
                 def both():
                     dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
                     dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
-                t_fb = timeit(both)
-                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %14.3f" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, t_fb), flush=True)
+
+                def kept():
+                    dn.deltanet_fwd_save(q, k, v, beta, o=o, final_state=ST, saved=ws)
+                    dn.deltanet_bwd_saved(q, k, v, beta, d_o, ws)
+                t_fb, t_kept = timeit(both), timeit(kept)
+                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %16.3f %16.3f" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, t_fb, t_kept),
+                      flush=True)
             else:
-                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %14s" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, "-"), flush=True)
+                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %16s %16s" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, "-", "-"), flush=True)
     return 0
 
 

@@ -71,6 +71,8 @@ def test_fused_equals_the_plain_path_on_the_mapped_inputs():
     assert nerr(o.cpu().numpy(), o2.cpu().numpy()) < 1e-5 and nerr(ST.cpu().numpy(), ST2.cpu().numpy()) < 1e-5
 
 
-def test_fused_full_size_benchmark_shape():
-    inp = make_pre_activations(5, make_config(2))
-    run_fused(inp, "fused cfg2")
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_fused_full_size(cfg):
+    # the benchmark shape and the packed variable-length batch (65536 tokens, lengths 128..8192)
+    inp = make_pre_activations(5, make_config(cfg))
+    run_fused(inp, "fused cfg%d" % cfg)

@@ -104,6 +104,8 @@ def test_saved_pair_rejects_what_it_cannot_do():
     assert ei.value.status == -5
 
 
-def test_saved_pair_full_size_benchmark_shape():
-    inp = make_config(2)
-    run_saved(inp, "saved cfg2", check_oracle=False)   # the self-contained pair is held to the oracle at this size elsewhere
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_saved_pair_full_size(cfg):
+    # the benchmark shape, the long sequence with states at both ends, and the packed variable-length batch;
+    # the self-contained pair is held to the oracle at these sizes elsewhere
+    run_saved(make_config(cfg), "saved cfg%d" % cfg, check_oracle=False)

@@ -231,7 +231,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (DK > 128 ? 4 : 0); // SCAN_BOTH: the loader waves hold more
+    constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (sizeof(T) == 4 ? 2 : (DK > 128 ? 4 : 0)); // SCAN_BOTH: the loader waves hold more
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -441,7 +441,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     T *sPT = reinterpret_cast<T *>(smem + SM::oPT);
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = GATED ? 2 : (DK > 128 ? 4 : 0);
+    constexpr int MB = GATED ? 2 : (sizeof(T) == 4 ? 2 : (DK > 128 ? 4 : 0));
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -663,7 +663,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     static_assert(!PRO || (sizeof(T) * C * SM::LQO <= SM::oB2 - SM::oB1 && sizeof(T) * C * SM::LQO <= SM::oB3 - SM::oB2), "dq / dk staging");
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = PRO ? 2 : ((DK > 128 || GATED) ? 4 : 0);
+    constexpr int MB = PRO ? 2 : (sizeof(T) == 4 ? 2 : ((DK > 128 || GATED) ? 4 : 0));
     const int tid = threadIdx.x, lane = tid & 63;
     // The wave number, and with it every tile offset derived from it, is recomputed per tile in the variants
     // that are short of registers: hoisted out of the tile loop, those offsets alone would take some 90 VGPRs.

@@ -355,6 +355,10 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
                 acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r > 32 * pmi + c) val = 0.f; });
                 acc_to_lds_t<T>(sP, SM::LT, 32 * pni, 32 * pmi, pa);
             }
+        } else if (does_o) {
+            // Q S, the inter-chunk part of Eq. 9: it needs only the state, so the output waves form it here,
+            // where they would otherwise wait for the chain waves' products
+            mma<DK, false, false, T, true, MB>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
         if (loader) {
@@ -368,8 +372,6 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             mma<DK, false, false, T, true, MB>(ws, sW + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
             acc -= ws;
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
-        } else if (does_o) { // Q S
-            mma<DK, false, false, T, true, MB>(acc, sQ + 32 * m.ua * SM::LQ, SM::LQ, sST + 32 * m.ub * SM::LS, SM::LS);
         }
         lds_barrier();
         if (MODE == SCAN_STORE && loader && ic > 0) flush_ut(ic - 1);

@@ -43,7 +43,7 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_Qm, off_Km, total;
+    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_Qm, off_Km, off_seg, seg_bytes, total;
     size_t esz;
 };
 
@@ -122,6 +122,12 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bo
     if (gated) {
         pl->off_gam = o; o += up256(tiles * 2 * kChunk * sizeof(float)); // gamma_i and 1 / gamma_i per chunk row
     }
+    { // forward pass split over segments of the sequence: N, M and the start state per segment
+        const int nv = s->d_v / scan_vblock_cols((int)pl->esz, s->d_k, s->d_v);
+        const int G = segment_count(pb.N, s->L, s->H, s->d_k, s->d_v, nv, packed, kChunk);
+        pl->seg_bytes = G > 1 ? up256((size_t)pb.N * G * s->H * s->d_k * s->d_v * sizeof(float)) : 0;
+        pl->off_seg = o; o += 3 * pl->seg_bytes;
+    }
     if (prologue) { // q and k after the feature map, in the layout of q and k
         const size_t tQ = up256((size_t)s->B * s->L * s->H * s->d_k * pl->esz);
         pl->off_Qm = o; o += tQ;
@@ -147,6 +153,11 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     }
     if (prologue) {
         p->Qm = b + pl.off_Qm; p->Km = b + pl.off_Km;
+    }
+    if (pl.seg_bytes) {
+        p->Nseg = reinterpret_cast<float *>(b + pl.off_seg);
+        p->Mseg = reinterpret_cast<float *>(b + pl.off_seg + pl.seg_bytes);
+        p->Sin = reinterpret_cast<float *>(b + pl.off_seg + 2 * pl.seg_bytes);
     }
 }
 

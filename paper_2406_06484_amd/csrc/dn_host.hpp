@@ -35,7 +35,27 @@ struct Ptrs {
     // dbeta receive the gradients with respect to those; workspace: Qm, Km = q, k after the map (layout of q, k)
     int pro;
     void *Qm, *Km;
+    // forward pass split over segments of the sequence (workspace): per segment the state written from zero, the
+    // transition matrix, and the state the segment starts from, all fp32 [segment][H][d_k][d_v or d_k]
+    float *Nseg, *Mseg, *Sin;
+    int unit_state; // set inside k_scan_state for its transition-matrix pass
 };
+
+// How many segments a dense forward pass over N sequences of length L is cut into (1 = not at all).  Few chains
+// cannot fill the 256 CUs of the chip; segments are whole chunks, at least four of them, d_v = d_k (the transition
+// matrix is scanned with the state kernels).  nv = workgroups per chain (d_v / columns per workgroup).
+inline int segment_count(int N, int L, int H, int d_k, int d_v, int nv, bool packed, int chunk = 64) {
+    if (packed || d_k != d_v || d_k > 128 || L <= 0) return 1;
+    const long wgs = (long)N * H * nv;
+    int G = 1;
+    while (G < 16 && wgs * (2 * G) <= 256 && L % (2 * G * chunk) == 0 && L / (2 * G * chunk) >= 4) G *= 2;
+    return G;
+}
+// state columns per scan workgroup, as the kernels choose them (VBlock)
+inline int scan_vblock_cols(int elem_bytes, int d_k, int d_v) {
+    const int want = (elem_bytes == 2 && d_k <= 128) ? 64 : 32;
+    return d_v < want ? d_v : want;
+}
 
 // Optional per-kernel timing (see deltanet_profile_* in the C header): when enabled, every launch is
 // bracketed by a pair of HIP events on the launch stream.  No-ops when disabled.

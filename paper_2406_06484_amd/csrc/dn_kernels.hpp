@@ -189,8 +189,9 @@ template <int DK, int BV> struct ScanMap {
 
 // scan_fwd_body: MODE = SCAN_OUT writes O and the final state; SCAN_STORE (the backward's recompute pass)
 // writes every chunk-initial state and Ut to the workspace instead of O; SCAN_BOTH (a forward pass whose
-// backward pass will not recompute) does both.
-enum { SCAN_OUT = 0, SCAN_STORE = 1, SCAN_BOTH = 2 };
+// backward pass will not recompute) does both; SCAN_STATE writes only the final state (the first pass of a
+// forward pass that is split over segments of the sequence, see k_scan_state).
+enum { SCAN_OUT = 0, SCAN_STORE = 1, SCAN_BOTH = 2, SCAN_STATE = 3 };
 template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr int BV = VBlock<T, DV, DK>::BV;
     static constexpr int LQ = ldc<T>(DK), LK = ldn<T>(DK), LV = ldn<T>(BV), LS = ldc<T>(DK), LT = ldc<T>(C);
@@ -214,7 +215,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     using SM = ScanFwdSmem<T, DK, DV>;
     static_assert(VAR != VAR_PROLOGUE, "the scans read q and k already mapped");
     constexpr bool GATED = VAR == VAR_GATED;
-    constexpr bool OUT = MODE != SCAN_STORE, SAVE = MODE != SCAN_OUT;
+    constexpr bool OUT = MODE == SCAN_OUT || MODE == SCAN_BOTH, SAVE = MODE == SCAN_STORE || MODE == SCAN_BOTH;
     constexpr int BV = SM::BV, NV = VBlock<T, DV, DK>::NV;
     using Map = ScanMap<DK, BV>;
     constexpr int NWT = (Map::W_TILES + 3) / 4; // W tiles per chain wave
@@ -251,6 +252,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         const float *src = p.S0 + (long)chain * DK * DV + vb;
         acc_each(S, [&](int r, int c, float &val) { val = src[(long)(32 * m.sa + r) * DV + 32 * m.sb + c]; });
     }
+    if (MODE == SCAN_STATE && p.unit_state && m.has_s) // start from the identity: the final state is then the segment's transition matrix
+        acc_each(S, [&](int r, int c, float &val) { val = (32 * m.sa + r == vb + 32 * m.sb + c) ? 1.f : 0.f; });
     // settle these loads here: otherwise the compiler keeps "state registers may still be in flight"
     // alive around the loop and drains the memory counter (and with it the prefetch) in every step
     __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
@@ -266,7 +269,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
         r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
-        r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
+        // (the transition-matrix pass of k_scan_state runs on v = 0: no row is valid)
+        r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, (MODE == SCAN_STATE && p.unit_state) ? 0 : nvalid, lt);
         r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
         if (gated) {
             r.v.load_row_factors(r.vs, p.gam + tile * 2 * C + C, lt);
@@ -392,7 +396,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (SAVE) flush_ut(nchunks - 1);
         if (OUT) flush_out(nchunks - 1);
     }
-    if (OUT && p.ST && m.has_s) {
+    if ((OUT || MODE == SCAN_STATE) && p.ST && m.has_s) {
         float *dst = p.ST + (long)chain * DK * DV + vb;
         acc_each(S, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
@@ -404,6 +408,70 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd(SeqMap sm, int H, Ptrs p) {
 template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_fwd_save(SeqMap sm, int H, Ptrs p) {
     scan_fwd_body<T, DK, DV, SCAN_BOTH, VAR>(sm, H, p, blockIdx.x);
+}
+
+// A forward pass over few, long chains leaves most CUs idle.  Every stretch of a chain acts on the state as an
+// affine map S_out = M S_in + N (M = the product of the chunks' (I - K^T W), d_k x d_k; N = what the stretch writes
+// starting from zero; Eq. 8), so the sequence is cut into G segments that are scanned side by side:
+//   k_scan_state   per segment, both in one grid: N (the scan from a zero state) and M (the same scan on v = 0
+//                  starting from the identity; needs d_v = d_k), final states only
+//   k_seg_combine  per chain: S_in of every segment by S <- M_g S + N_g, in fp32 on the matrix cores
+//   k_scan_fwd     per segment, from its S_in: the outputs
+// `sm` describes the segments as sequences (dense layout: [B, L] viewed as [B G, L / G]); `half` = workgroups per pass.
+template <typename T, int DK, int DV, int VAR>
+__global__ __launch_bounds__(NTS) void k_scan_state(SeqMap sm, int H, Ptrs p, int half) {
+    Ptrs ps = p;
+    ps.S0 = nullptr;
+    if ((int)blockIdx.x < half) { ps.unit_state = 0; ps.ST = p.Nseg; }
+    else { ps.unit_state = 1; ps.ST = p.Mseg; }
+    scan_fwd_body<T, DK, DV, SCAN_STATE, VAR>(sm, H, ps, (int)blockIdx.x < half ? blockIdx.x : blockIdx.x - half);
+}
+
+// S_in(0) = the caller's initial state (or zero); S_in(g + 1) = M_g S_in(g) + N_g; the state after the last segment is
+// the final state.  One workgroup per (chain, block of 32 state columns): the columns evolve independently.
+template <int DK, int DV> struct CombineSmem {
+    static constexpr int LM = DK + 4, LSB = 32 + 4;
+    static constexpr size_t oM = 0, oS = sizeof(float) * DK * LM, bytes = oS + sizeof(float) * DK * LSB;
+};
+template <int DK, int DV>
+__global__ __launch_bounds__(NTHR) void k_seg_combine(const float *Mseg, const float *Nseg, const float *S0, float *Sin, float *ST,
+                                                      int G, int H) {
+    using SM = CombineSmem<DK, DV>;
+    static_assert(DK % 32 == 0 && DK / 32 <= NTHR / 64, "one 32-row tile per wave");
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *sM = reinterpret_cast<float *>(smem + SM::oM), *sS = reinterpret_cast<float *>(smem + SM::oS);
+    const int chain = blockIdx.x, b = chain / H, h = chain - b * H, c0 = 32 * blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6;
+    for (int e = tid; e < DK * 32; e += NTHR) {
+        const int i = e >> 5, j = e & 31;
+        sS[i * SM::LSB + j] = S0 ? S0[((long)chain * DK + i) * DV + c0 + j] : 0.f;
+    }
+    __syncthreads();
+    for (int g = 0; g < G; ++g) {
+        const long seg = ((long)(b * G + g) * H + h);
+        for (int e = tid; e < DK * 32; e += NTHR) { // this segment starts from the current state
+            const int i = e >> 5, j = e & 31;
+            Sin[(seg * DK + i) * DV + c0 + j] = sS[i * SM::LSB + j];
+        }
+        for (int e = tid; e < DK * DK / 4; e += NTHR) { // M_g, 16 bytes per lane
+            const int i = e / (DK / 4), k4 = (e % (DK / 4)) * 4;
+            *reinterpret_cast<float4 *>(sM + i * SM::LM + k4) = *reinterpret_cast<const float4 *>(Mseg + (seg * DK + i) * DK + k4);
+        }
+        __syncthreads();
+        f32x16 acc = zero16();
+        if (wave < DK / 32) {
+            acc_each(acc, [&](int r, int c, float &val) { val = Nseg[(seg * DK + 32 * wave + r) * DV + c0 + c]; });
+            mma<DK, false, true, float>(acc, sM + 32 * wave * SM::LM, SM::LM, sS, SM::LSB);
+        }
+        __syncthreads(); // every wave has read the old state
+        if (wave < DK / 32) acc_to_lds<float>(sS, SM::LSB, 32 * wave, 0, acc);
+        __syncthreads();
+    }
+    if (ST)
+        for (int e = tid; e < DK * 32; e += NTHR) {
+            const int i = e >> 5, j = e & 31;
+            ST[((long)chain * DK + i) * DV + c0 + j] = sS[i * SM::LSB + j];
+        }
 }
 
 // scan_bwd_body: reverse over chunks, carrying dS (gradient w.r.t. the chunk-initial state):

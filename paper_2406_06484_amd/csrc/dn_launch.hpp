@@ -79,11 +79,27 @@ static inline Ptrs scan_ptrs(const Ptrs &p) {
 
 template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0 || pb.chunks_ub == 0) return 0;
-    const SeqMap sm = make_map(pb);
+    SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
-    const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
+    const dim3 gchunk(pb.chunks_ub, pb.H);
+    dim3 gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    const Ptrs ps = scan_ptrs(p);
+    Ptrs ps = scan_ptrs(p);
+    if constexpr (DK == DV && DK <= 128) {
+        // few long chains: cut the sequences into G segments, get every segment's start state from a first pass
+        // (k_scan_state, k_seg_combine), then run the scan below over the segments side by side
+        const int G = segment_count(pb.N, pb.L, pb.H, DK, DV, VBlock<T, DV, DK>::NV, pb.cu != nullptr);
+        if (G > 1 && p.Sin) {
+            sm.N = pb.N * G; sm.L = pb.L / G; sm.ncd = sm.L / C;
+            const dim3 gseg(chain_grid(sm.N * pb.H, VBlock<T, DV, DK>::NV));
+            const dim3 gstate(2 * gseg.x);
+            DN_LAUNCH_SCAN(k_scan_state, gstate, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps, (int)gseg.x);
+            DN_LAUNCH_NT((k_seg_combine<DK, DV>), dim3(pb.N * pb.H, DV / 32), NTHR, (CombineSmem<DK, DV>::bytes), p.Mseg, p.Nseg, p.S0,
+                         p.Sin, p.ST, G, pb.H);
+            ps.S0 = p.Sin; ps.ST = nullptr;
+            gchain = gseg;
+        }
+    }
     if constexpr (kHasBwd<T, DK, DV>) {
         if (pb.save) {
             DN_LAUNCH_SCAN(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);

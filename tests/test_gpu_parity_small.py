@@ -146,3 +146,21 @@ def test_head_size_256_forward_only():
     with pytest.raises(dn.DeltaNetError) as e:
         dn.deltanet_bwd(d["q"], d["k"], d["v"], d["beta"], d["d_o"])
     assert e.value.status == -3
+
+
+@pytest.mark.parametrize("dtype,d,B,H,L", [("f32", 64, 1, 2, 2048), ("bf16", 128, 1, 3, 4096), ("bf16", 64, 2, 1, 1024)])
+def test_few_long_chains_take_the_segmented_forward(dtype, d, B, H, L):
+    # few chains and a long sequence: the forward pass cuts the sequence into segments, gets each segment's start state
+    # from the segments' affine maps, and scans the segments side by side; with and without states at the ends
+    from paper_2406_06484_amd.binding import _shape_of, deltanet_workspace_bytes
+    inp = make_inputs(900 + d + L, B=B, L=L, H=H, dk=d, dv=d, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
+    inp.initial_state *= 10.0
+    dd = dev_inputs(inp)
+    # the workspace grows by the per-segment states exactly when the segmented path is taken
+    one_chunk_tiles = (L // 64) * B * H * 64 * 64 * (2 if dtype == "bf16" else 4)
+    assert deltanet_workspace_bytes(_shape_of(dd["q"], dd["v"], None, 64, []), False) > one_chunk_tiles
+    check_fwd_bwd(inp, label="segmented %s d=%d B=%d H=%d L=%d" % (dtype, d, B, H, L))
+    o, ST, saved = dn.deltanet_fwd_save(dd["q"], dd["k"], dd["v"], dd["beta"], dd["S0"])
+    o2, ST2 = dn.deltanet_fwd(dd["q"], dd["k"], dd["v"], dd["beta"], dd["S0"])
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(ST, ST2)

@@ -25,7 +25,8 @@
  *    states, state gradients and dbeta are always fp32.
  *  - Every data pointer must be 16-byte aligned.
  *  - `workspace` is caller-provided device scratch of at least deltanet_workspace_bytes();
- *    its contents are undefined afterwards.
+ *    its contents are undefined afterwards.  (For few long sequences the passes cut the sequences into
+ *    segments that are scanned side by side; the per-segment states this needs are part of that size.)
  *  - Return value: DN_OK (0) or a negative dn_status.  All validation happens before the first
  *    launch; on a validation error nothing has been enqueued.  No exceptions, no abort.
  *  - Sequences of length 0 are allowed in the packed layout; lengths need not be multiples of

@@ -126,7 +126,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bo
         const int nv = s->d_v / scan_vblock_cols((int)pl->esz, s->d_k, s->d_v);
         const int G = segment_count(pb.N, s->L, s->H, s->d_k, s->d_v, nv, packed, kChunk);
         pl->seg_bytes = G > 1 ? up256((size_t)pb.N * G * s->H * s->d_k * s->d_v * sizeof(float)) : 0;
-        pl->off_seg = o; o += 3 * pl->seg_bytes;
+        pl->off_seg = o; o += 5 * pl->seg_bytes;
     }
     if (prologue) { // q and k after the feature map, in the layout of q and k
         const size_t tQ = up256((size_t)s->B * s->L * s->H * s->d_k * pl->esz);
@@ -158,6 +158,8 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
         p->Nseg = reinterpret_cast<float *>(b + pl.off_seg);
         p->Mseg = reinterpret_cast<float *>(b + pl.off_seg + pl.seg_bytes);
         p->Sin = reinterpret_cast<float *>(b + pl.off_seg + 2 * pl.seg_bytes);
+        p->Rseg = reinterpret_cast<float *>(b + pl.off_seg + 3 * pl.seg_bytes);
+        p->dSout = reinterpret_cast<float *>(b + pl.off_seg + 4 * pl.seg_bytes);
     }
 }
 

@@ -38,6 +38,9 @@ struct Ptrs {
     // forward pass split over segments of the sequence (workspace): per segment the state written from zero, the
     // transition matrix, and the state the segment starts from, all fp32 [segment][H][d_k][d_v or d_k]
     float *Nseg, *Mseg, *Sin;
+    // ... and of the backward pass: per segment the gradient the reverse scan produces from zero, and the gradient
+    // with respect to the segment's end state
+    float *Rseg, *dSout;
     int unit_state; // set inside k_scan_state for its transition-matrix pass
 };
 
@@ -50,6 +53,12 @@ inline int segment_count(int N, int L, int H, int d_k, int d_v, int nv, bool pac
     int G = 1;
     while (G < 16 && wgs * (2 * G) <= 256 && L % (2 * G * chunk) == 0 && L / (2 * G * chunk) >= 4) G *= 2;
     return G;
+}
+// The backward pass runs five scan passes over the segments where the uncut one runs two, so it is cut (into the
+// same segments as the forward pass, whose transition matrices it may find in the workspace) only when its two
+// scans would occupy a quarter of the chip or less.
+inline int segment_count_bwd(int N, int L, int H, int d_k, int d_v, int nv, bool packed, int chunk = 64) {
+    return (long)N * H * nv <= 32 ? segment_count(N, L, H, d_k, d_v, nv, packed, chunk) : 1;
 }
 // state columns per scan workgroup, as the kernels choose them (VBlock)
 inline int scan_vblock_cols(int elem_bytes, int d_k, int d_v) {

@@ -410,6 +410,9 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd_save(SeqMap sm, int H, Ptrs p)
     scan_fwd_body<T, DK, DV, SCAN_BOTH, VAR>(sm, H, p, blockIdx.x);
 }
 
+template <typename T, int DK, int DV, int VAR, bool STATE>
+__device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid);
+
 // A forward pass over few, long chains leaves most CUs idle.  Every stretch of a chain acts on the state as an
 // affine map S_out = M S_in + N (M = the product of the chunks' (I - K^T W), d_k x d_k; N = what the stretch writes
 // starting from zero; Eq. 8), so the sequence is cut into G segments that are scanned side by side:
@@ -418,59 +421,94 @@ __global__ __launch_bounds__(NTS) void k_scan_fwd_save(SeqMap sm, int H, Ptrs p)
 //   k_seg_combine  per chain: S_in of every segment by S <- M_g S + N_g, in fp32 on the matrix cores
 //   k_scan_fwd     per segment, from its S_in: the outputs
 // `sm` describes the segments as sequences (dense layout: [B, L] viewed as [B G, L / G]); `half` = workgroups per pass.
+// The backward pass is cut the same way: the gradient with respect to a segment's start state is
+// M^T (gradient with respect to its end state) + R, R = the reverse scan of the segment from a zero gradient; a grid of
+// three parts adds that pass (k_scan_state), a grid of one part runs it alone (k_scan_bwd_state).
 template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_state(SeqMap sm, int H, Ptrs p, int half) {
     Ptrs ps = p;
     ps.S0 = nullptr;
-    if ((int)blockIdx.x < half) { ps.unit_state = 0; ps.ST = p.Nseg; }
+    const int part = (int)blockIdx.x / half, bid = (int)blockIdx.x - part * half;
+    if (part == 2) {
+        ps.dST = nullptr; ps.dS0 = p.Rseg;
+        scan_bwd_body<T, DK, DV, VAR, true>(sm, H, ps, bid);
+        return;
+    }
+    if (part == 0) { ps.unit_state = 0; ps.ST = p.Nseg; }
     else { ps.unit_state = 1; ps.ST = p.Mseg; }
-    scan_fwd_body<T, DK, DV, SCAN_STATE, VAR>(sm, H, ps, (int)blockIdx.x < half ? blockIdx.x : blockIdx.x - half);
+    scan_fwd_body<T, DK, DV, SCAN_STATE, VAR>(sm, H, ps, bid);
+}
+template <typename T, int DK, int DV, int VAR>
+__global__ __launch_bounds__(NTS) void k_scan_bwd_state(SeqMap sm, int H, Ptrs p) {
+    Ptrs ps = p;
+    ps.dST = nullptr; ps.dS0 = p.Rseg;
+    scan_bwd_body<T, DK, DV, VAR, true>(sm, H, ps, blockIdx.x);
 }
 
 // S_in(0) = the caller's initial state (or zero); S_in(g + 1) = M_g S_in(g) + N_g; the state after the last segment is
-// the final state.  One workgroup per (chain, block of 32 state columns): the columns evolve independently.
+// the final state.  Backward (blockIdx.z = 1): D(G) = the caller's gradient with respect to the final state (or zero);
+// every segment's end gradient dSout(g) = D(g + 1), D(g) = M_g^T D(g + 1) + R_g; D(0) is the gradient with respect to the
+// initial state.  One workgroup per (chain, block of 32 state columns, direction): the columns evolve independently.
+// fp32 on the matrix cores; the next segment's M and N (R) tile travel from global memory while the current product runs.
 template <int DK, int DV> struct CombineSmem {
     static constexpr int LM = DK + 4, LSB = 32 + 4;
     static constexpr size_t oM = 0, oS = sizeof(float) * DK * LM, bytes = oS + sizeof(float) * DK * LSB;
 };
+struct CombineArgs {
+    const float *Mseg, *Nseg, *S0; // forward: per-segment N, the caller's initial state (may be null)
+    float *Sin, *ST;               // forward outputs: start state per segment, final state (may be null)
+    const float *Rseg, *dST;       // backward: per-segment R, the caller's final-state gradient (may be null)
+    float *dSout, *dS0;            // backward outputs: end gradient per segment, initial-state gradient (may be null)
+    int G, H, first_dir;           // grid.z directions run from first_dir: 0 = forward, 1 = backward
+};
 template <int DK, int DV>
-__global__ __launch_bounds__(NTHR) void k_seg_combine(const float *Mseg, const float *Nseg, const float *S0, float *Sin, float *ST,
-                                                      int G, int H) {
+__global__ __launch_bounds__(NTHR) void k_seg_combine(CombineArgs a) {
     using SM = CombineSmem<DK, DV>;
     static_assert(DK % 32 == 0 && DK / 32 <= NTHR / 64, "one 32-row tile per wave");
     extern __shared__ __align__(16) unsigned char smem[];
     float *sM = reinterpret_cast<float *>(smem + SM::oM), *sS = reinterpret_cast<float *>(smem + SM::oS);
-    const int chain = blockIdx.x, b = chain / H, h = chain - b * H, c0 = 32 * blockIdx.y;
+    const int chain = blockIdx.x, b = chain / a.H, h = chain - b * a.H, c0 = 32 * blockIdx.y;
+    const bool bwd = (int)blockIdx.z + a.first_dir == 1;
     const int tid = threadIdx.x, wave = tid >> 6;
+    const bool act = wave < DK / 32;
+    const float *init = bwd ? a.dST : a.S0, *add = bwd ? a.Rseg : a.Nseg;
+    float *start = bwd ? a.dSout : a.Sin, *last = bwd ? a.dS0 : a.ST;
+    auto seg_of = [&](int i) __attribute__((always_inline)) { return ((long)(b * a.G + (bwd ? a.G - 1 - i : i)) * a.H + h); };
+    TileRegs<float, DK, DK, NTHR> mreg;
+    f32x16 nreg = zero16();
+    auto request = [&](int i) __attribute__((always_inline)) { // M and the additive tile of step i, into registers
+        const long seg = seg_of(i);
+        mreg.load(a.Mseg + seg * DK * DK, DK, DK);
+        if (act) acc_each(nreg, [&](int r, int c, float &val) { val = add[(seg * DK + 32 * wave + r) * DV + c0 + c]; });
+    };
+    request(0);
     for (int e = tid; e < DK * 32; e += NTHR) {
         const int i = e >> 5, j = e & 31;
-        sS[i * SM::LSB + j] = S0 ? S0[((long)chain * DK + i) * DV + c0 + j] : 0.f;
+        sS[i * SM::LSB + j] = init ? init[((long)chain * DK + i) * DV + c0 + j] : 0.f;
     }
-    __syncthreads();
-    for (int g = 0; g < G; ++g) {
-        const long seg = ((long)(b * G + g) * H + h);
-        for (int e = tid; e < DK * 32; e += NTHR) { // this segment starts from the current state
-            const int i = e >> 5, j = e & 31;
-            Sin[(seg * DK + i) * DV + c0 + j] = sS[i * SM::LSB + j];
+    lds_barrier(); // (LDS only: the requests and stores in flight are not waited for)
+    for (int i = 0; i < a.G; ++i) {
+        const long seg = seg_of(i);
+        for (int e = tid; e < DK * 32; e += NTHR) { // this segment starts from (backward: ends with) the current value
+            const int r = e >> 5, j = e & 31;
+            start[(seg * DK + r) * DV + c0 + j] = sS[r * SM::LSB + j];
         }
-        for (int e = tid; e < DK * DK / 4; e += NTHR) { // M_g, 16 bytes per lane
-            const int i = e / (DK / 4), k4 = (e % (DK / 4)) * 4;
-            *reinterpret_cast<float4 *>(sM + i * SM::LM + k4) = *reinterpret_cast<const float4 *>(Mseg + (seg * DK + i) * DK + k4);
+        mreg.store(sM, SM::LM);
+        f32x16 acc = nreg;
+        lds_barrier();
+        if (i + 1 < a.G) request(i + 1);
+        if (act) {
+            if (bwd) mma<DK, true, true, float>(acc, sM + 32 * wave, SM::LM, sS, SM::LSB); // M^T D: down the rows of M
+            else mma<DK, false, true, float>(acc, sM + 32 * wave * SM::LM, SM::LM, sS, SM::LSB);
         }
-        __syncthreads();
-        f32x16 acc = zero16();
-        if (wave < DK / 32) {
-            acc_each(acc, [&](int r, int c, float &val) { val = Nseg[(seg * DK + 32 * wave + r) * DV + c0 + c]; });
-            mma<DK, false, true, float>(acc, sM + 32 * wave * SM::LM, SM::LM, sS, SM::LSB);
-        }
-        __syncthreads(); // every wave has read the old state
-        if (wave < DK / 32) acc_to_lds<float>(sS, SM::LSB, 32 * wave, 0, acc);
-        __syncthreads();
+        lds_barrier(); // every wave has read the old value
+        if (act) acc_to_lds<float>(sS, SM::LSB, 32 * wave, 0, acc);
+        lds_barrier();
     }
-    if (ST)
+    if (last)
         for (int e = tid; e < DK * 32; e += NTHR) {
-            const int i = e >> 5, j = e & 31;
-            ST[((long)chain * DK + i) * DV + c0 + j] = sS[i * SM::LSB + j];
+            const int r = e >> 5, j = e & 31;
+            last[((long)chain * DK + r) * DV + c0 + j] = sS[r * SM::LSB + j];
         }
 }
 
@@ -492,7 +530,9 @@ template <typename T, int DK, int DV> struct ScanBwdSmem {
     static constexpr size_t bytes = oPT + align16(sizeof(T) * C * LT);
 };
 
-template <typename T, int DK, int DV, int VAR>
+// STATE = true: only the gradient with respect to the initial state leaves the kernel (the first pass of a backward
+// pass that is split over segments of the sequence).
+template <typename T, int DK, int DV, int VAR, bool STATE>
 __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptrs &p, int bid) {
     using SM = ScanBwdSmem<T, DK, DV>;
     static_assert(VAR != VAR_PROLOGUE, "the scans read q and k already mapped");
@@ -604,7 +644,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader) {
             if (ic > 0) fetch_b(ic - 1);
-            copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
+            if (!STATE) copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
         }
         if (m.does_u) { // + P^T dO; P^T is upper triangular
             if (m.ua == 0) mma<C, false, true, T, true, MB>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
@@ -613,7 +653,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         }
         if (m.has_s) mma<C, true, true, T, true, MB>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         lds_barrier();
-        if (loader && ic + 1 < nchunks) flush_dut(ic + 1);
+        if (!STATE && loader && ic + 1 < nchunks) flush_dut(ic + 1);
         if (m.has_s) { // - W^T dUt
             f32x16 wd = zero16();
             mma<C, true, false, T, true, MB>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
@@ -622,7 +662,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader && ic > 0) stash(); // see k_scan_fwd
     }
-    if (loader && nchunks > 0) flush_dut(0);
+    if (!STATE && loader && nchunks > 0) flush_dut(0);
     if (p.dS0 && m.has_s) {
         float *dst = p.dS0 + (long)chain * DK * DV + vb;
         acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
@@ -635,13 +675,13 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
 // in between.  `half` = workgroups per scan.
 template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_pair(SeqMap sm, int H, Ptrs p, int half) {
-    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV, VAR>(sm, H, p, blockIdx.x);
+    if ((int)blockIdx.x < half) scan_bwd_body<T, DK, DV, VAR, false>(sm, H, p, blockIdx.x);
     else scan_fwd_body<T, DK, DV, SCAN_STORE, VAR>(sm, H, p, blockIdx.x - half);
 }
 // the reverse scan alone, for a backward pass that finds the forward scan's tiles already in the workspace
 template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTS) void k_scan_bwd(SeqMap sm, int H, Ptrs p) {
-    scan_bwd_body<T, DK, DV, VAR>(sm, H, p, blockIdx.x);
+    scan_bwd_body<T, DK, DV, VAR, false>(sm, H, p, blockIdx.x);
 }
 
 // =============================================================================================

@@ -94,8 +94,8 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
             const dim3 gseg(chain_grid(sm.N * pb.H, VBlock<T, DV, DK>::NV));
             const dim3 gstate(2 * gseg.x);
             DN_LAUNCH_SCAN(k_scan_state, gstate, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps, (int)gseg.x);
-            DN_LAUNCH_NT((k_seg_combine<DK, DV>), dim3(pb.N * pb.H, DV / 32), NTHR, (CombineSmem<DK, DV>::bytes), p.Mseg, p.Nseg, p.S0,
-                         p.Sin, p.ST, G, pb.H);
+            const CombineArgs ca{p.Mseg, p.Nseg, p.S0, p.Sin, p.ST, nullptr, nullptr, nullptr, nullptr, G, pb.H, 0};
+            DN_LAUNCH_NT((k_seg_combine<DK, DV>), dim3(pb.N * pb.H, DV / 32, 1), NTHR, (CombineSmem<DK, DV>::bytes), ca);
             ps.S0 = p.Sin; ps.ST = nullptr;
             gchain = gseg;
         }
@@ -115,15 +115,38 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
-    const Ptrs ps = scan_ptrs(p);
-    if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
+    Ptrs ps = scan_ptrs(p);
+    constexpr size_t lds_pair = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
+    // few long chains: the scans run over G segments of the sequences side by side (see k_scan_state)
+    int G = 1;
+    if constexpr (DK == DV && DK <= 128) G = segment_count_bwd(pb.N, pb.L, pb.H, DK, DV, VBlock<T, DV, DK>::NV, pb.cu != nullptr);
+    if (G > 1 && p.Sin && pb.chunks_ub) {
+        if constexpr (DK == DV && DK <= 128) {
+            SeqMap sg = sm;
+            sg.N = pb.N * G; sg.L = pb.L / G; sg.ncd = sg.L / C;
+            const dim3 gseg(chain_grid(sg.N * pb.H, VBlock<T, DV, DK>::NV));
+            if (pb.save) { // the forward pass left its tiles and the segments' transition matrices
+                DN_LAUNCH_SCAN(k_scan_bwd_state, gseg, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sg, pb.H, ps);
+                const CombineArgs ca{p.Mseg, nullptr, nullptr, nullptr, nullptr, p.Rseg, p.dST, p.dSout, p.dS0, G, pb.H, 1};
+                DN_LAUNCH_NT((k_seg_combine<DK, DV>), dim3(pb.N * pb.H, DV / 32, 1), NTHR, (CombineSmem<DK, DV>::bytes), ca);
+                ps.dST = p.dSout; ps.dS0 = nullptr;
+                DN_LAUNCH_SCAN(k_scan_bwd, gseg, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sg, pb.H, ps);
+            } else {
+                DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
+                DN_LAUNCH_SCAN(k_scan_state, dim3(3 * gseg.x), NTS, lds_pair, sg, pb.H, ps, (int)gseg.x);
+                const CombineArgs ca{p.Mseg, p.Nseg, p.S0, p.Sin, nullptr, p.Rseg, p.dST, p.dSout, p.dS0, G, pb.H, 0};
+                DN_LAUNCH_NT((k_seg_combine<DK, DV>), dim3(pb.N * pb.H, DV / 32, 2), NTHR, (CombineSmem<DK, DV>::bytes), ca);
+                ps.S0 = p.Sin; ps.dST = p.dSout; ps.dS0 = nullptr;
+                DN_LAUNCH_SCAN(k_scan_pair, dim3(2 * gseg.x), NTS, lds_pair, sg, pb.H, ps, (int)gseg.x);
+            }
+        }
+    } else if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
         DN_LAUNCH_SCAN(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
     } else {
         if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
         // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
-        constexpr size_t lds = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
         const dim3 gpair(2 * gchain.x);
-        DN_LAUNCH_SCAN(k_scan_pair, gpair, NTS, lds, sm, pb.H, ps, (int)gchain.x);
+        DN_LAUNCH_SCAN(k_scan_pair, gpair, NTS, lds_pair, sm, pb.H, ps, (int)gchain.x);
     }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;

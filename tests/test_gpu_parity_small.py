@@ -149,9 +149,9 @@ def test_head_size_256_forward_only():
 
 
 @pytest.mark.parametrize("dtype,d,B,H,L", [("f32", 64, 1, 2, 2048), ("bf16", 128, 1, 3, 4096), ("bf16", 64, 2, 1, 1024)])
-def test_few_long_chains_take_the_segmented_forward(dtype, d, B, H, L):
-    # few chains and a long sequence: the forward pass cuts the sequence into segments, gets each segment's start state
-    # from the segments' affine maps, and scans the segments side by side; with and without states at the ends
+def test_few_long_chains_take_the_segmented_scans(dtype, d, B, H, L):
+    # few chains and a long sequence: both passes cut the sequence into segments, get each segment's start state (end
+    # gradient) from the segments' affine maps, and scan the segments side by side
     from paper_2406_06484_amd.binding import _shape_of, deltanet_workspace_bytes
     inp = make_inputs(900 + d + L, B=B, L=L, H=H, dk=d, dv=d, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
     inp.initial_state *= 10.0
@@ -161,6 +161,10 @@ def test_few_long_chains_take_the_segmented_forward(dtype, d, B, H, L):
     assert deltanet_workspace_bytes(_shape_of(dd["q"], dd["v"], None, 64, []), False) > one_chunk_tiles
     check_fwd_bwd(inp, label="segmented %s d=%d B=%d H=%d L=%d" % (dtype, d, B, H, L))
     o, ST, saved = dn.deltanet_fwd_save(dd["q"], dd["k"], dd["v"], dd["beta"], dd["S0"])
+    grads = dn.deltanet_bwd_saved(dd["q"], dd["k"], dd["v"], dd["beta"], dd["d_o"], saved, dd["dST"])
     o2, ST2 = dn.deltanet_fwd(dd["q"], dd["k"], dd["v"], dd["beta"], dd["S0"])
+    grads2 = dn.deltanet_bwd(dd["q"], dd["k"], dd["v"], dd["beta"], dd["d_o"], dd["S0"], dd["dST"])
     torch.cuda.synchronize()
     assert torch.equal(o, o2) and torch.equal(ST, ST2)
+    for a, b in zip(grads, grads2):   # the pair that keeps the forward's tiles runs the same segmented arithmetic
+        assert torch.equal(a, b)

@@ -76,3 +76,8 @@ def test_fused_full_size(cfg):
     # the benchmark shape and the packed variable-length batch (65536 tokens, lengths 128..8192)
     inp = make_pre_activations(5, make_config(cfg))
     run_fused(inp, "fused cfg%d" % cfg)
+
+
+def test_fused_few_long_chains_take_the_segmented_scans():
+    base = make_inputs(42, B=1, L=2048, H=2, dk=128, dv=128, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
+    run_fused(make_pre_activations(6, base), "fused segmented")

@@ -78,3 +78,11 @@ def test_gated_full_size_benchmark_shape():
     from paper_2406_06484_amd.synth import make_config
     inp = make_config(2)
     run_gated(inp, make_gate(4, inp.beta.shape, lo=0.9, hi=1.0), label="gated cfg2")
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_gated_few_long_chains_take_the_segmented_scans(dtype, d):
+    # the segments' affine maps carry the decay: M = prod gamma_C (I - K^T W), and the reverse scan sees its transpose
+    inp = make_inputs(41, B=1, L=2048, H=2, dk=d, dv=d, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
+    inp.initial_state *= 10.0
+    run_gated(inp, make_gate(6, inp.beta.shape, lo=0.9, hi=1.0), label="gated segmented %s" % dtype)

@@ -50,6 +50,7 @@ struct Ptrs {
 inline int segment_count(int N, int L, int H, int d_k, int d_v, int nv, bool packed, int chunk = 64) {
     if (packed || d_k != d_v || d_k > 128 || L <= 0) return 1;
     const long wgs = (long)N * H * nv;
+    if (wgs > 64) return 1; // three scan passes over the segments instead of one: pays from a quarter of the chip down
     int G = 1;
     while (G < 16 && wgs * (2 * G) <= 256 && L % (2 * G * chunk) == 0 && L / (2 * G * chunk) >= 4) G *= 2;
     return G;

@@ -207,7 +207,13 @@ def main() -> int:
         "fwd_ms": round(fw, 4), "bwd_ms": round(bw, 4),
         "model_tflops": round(model_tflops, 2),
         "pct_bf16_mfma_peak": round(100 * model_tflops / PEAK_BF16_TFLOPS, 3),
+        # the same with the masked halves of the C x C tiles not counted (forward 6d^2 + 5Cd + 2/3 C^2), and with the FLOPs a
+        # backward pass that recomputes the chunk states adds (4d^2 + 8Cd + 2/3 C^2; this step keeps them, so nothing is added)
+        "pct_bf16_mfma_peak_triangle_aware": round(100 * (model_tflops - 5 * C * d * H * value / 1e12) / PEAK_BF16_TFLOPS, 3),
+        "recompute_extra_flops_per_token_head": 4 * d * d + 8 * C * d + (2.0 / 3.0) * C * C,
         "algorithmic_hbm_gbs": round((1026 + 1798) * H * value / 1e9, 1),
+        "measured_hbm_gbs": round(sum((measured_traffic(n) or 0.0) * k_["launches_per_step"] for n, k_ in kernels.items())
+                                  / (ms_per_step * 1e-3) / 1e9, 1),
         "kernels": kernels,
         "roofline": roofline,
     }
@@ -315,6 +321,13 @@ def main() -> int:
         out["cpu_baseline"] = {"value": round(tokens * reps / cdt, 1), "unit": "tokens/s", "cores": nthr, "kind": "oracle",
                                "sample": "the full workload (all %d chains x %d tokens), fwd+bwd, %d repetition(s), fp64, "
                                          "OpenMP over chains" % (B * H, L, reps)}
+        # the same oracle on one core, on the first sequence of the batch (all heads)
+        t0 = time.perf_counter()
+        oracle.fwd(inp.q[:1], inp.k[:1], inp.v[:1], inp.beta[:1], nthreads=1)
+        oracle.bwd(inp.q[:1], inp.k[:1], inp.v[:1], inp.beta[:1], inp.d_o[:1], nthreads=1)
+        c1 = time.perf_counter() - t0
+        out["cpu_baseline_one_core"] = {"value": round(L / c1, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                        "sample": "the first sequence of the batch (%d chains x %d tokens), fwd+bwd, once" % (H, L)}
     print(json.dumps(out))
     return 0
 

@@ -148,7 +148,8 @@ def test_head_size_256_forward_only():
     assert e.value.status == -3
 
 
-@pytest.mark.parametrize("dtype,d,B,H,L", [("f32", 64, 1, 2, 2048), ("bf16", 128, 1, 3, 4096), ("bf16", 64, 2, 1, 1024)])
+# (the last case cuts the forward pass only: 48 scan workgroups are too many for the backward rule)
+@pytest.mark.parametrize("dtype,d,B,H,L", [("f32", 64, 1, 2, 2048), ("bf16", 128, 1, 3, 4096), ("bf16", 64, 2, 1, 1024), ("bf16", 128, 1, 24, 2048)])
 def test_few_long_chains_take_the_segmented_scans(dtype, d, B, H, L):
     # few chains and a long sequence: both passes cut the sequence into segments, get each segment's start state (end
     # gradient) from the segments' affine maps, and scan the segments side by side
@@ -166,5 +167,9 @@ def test_few_long_chains_take_the_segmented_scans(dtype, d, B, H, L):
     grads2 = dn.deltanet_bwd(dd["q"], dd["k"], dd["v"], dd["beta"], dd["d_o"], dd["S0"], dd["dST"])
     torch.cuda.synchronize()
     assert torch.equal(o, o2) and torch.equal(ST, ST2)
-    for a, b in zip(grads, grads2):   # the pair that keeps the forward's tiles runs the same segmented arithmetic
-        assert torch.equal(a, b)
+    fwd_only_cut = B * H * (2 if (dtype == "bf16" and d == 128) else 1) > 32
+    for a, b in zip(grads, grads2):
+        if fwd_only_cut:   # kept tiles come from the cut forward pass, the self-contained backward recomputes them uncut
+            assert nerr(a.float().cpu().numpy(), b.float().cpu().numpy()) < 1e-2   # two bf16 results, each within 5e-3 of the oracle
+        else:              # the pair that keeps the forward's tiles runs the same segmented arithmetic
+            assert torch.equal(a, b)

@@ -411,7 +411,8 @@ __device__ inline void copy_out(T *dst, const T *src, int ld, int t) {
 // Blocked forward substitution: the eight 8x8 diagonal blocks are solved column by column (16
 // lanes of every wavefront), then 2x2 block merges X21 = -X22 (A21 X11) double the block size
 // 8 -> 16 -> 32 on the vector ALU in fp32 and 32 -> 64 on the matrix cores with operands of type T.
-// sM: 512 floats of scratch.  sOp: 4 x 32 x LO elements of type T, LO >= 32 + 8.  Ends with a barrier.
+// sM: 512 floats of scratch (may share its bytes with sOp: it is dead before sOp is written).  sOp: 3 x 32 x LO elements of
+// type T, LO >= 32 + 8.  Ends with a barrier.
 template <typename T, int NT = NTHR>
 __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *sOp, int LO) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -475,7 +476,7 @@ __device__ inline void tri_inverse_64_inplace(float *sX, int ld, float *sM, T *s
         lds_barrier();
     }
     // 32 -> 64 on the matrix cores: operands A21, X11^T, X22 and (later) M^T, each 32 x LO
-    T *oA = sOp, *oX11T = sOp + 32 * LO, *oX22 = sOp + 64 * LO, *oMT = sOp + 96 * LO;
+    T *oA = sOp, *oX11T = sOp + 32 * LO, *oX22 = sOp + 64 * LO, *oMT = oA; // M^T takes A21's place: one wave reads the one, then writes the other
     for (int e = tid; e < 32 * 32; e += NT) {
         const int i = e >> 5, k = e & 31;
         oA[i * LO + k] = from_f32<T>(sX[(32 + i) * ld + k]);

@@ -59,9 +59,9 @@ template <typename T, int DK, int DV> struct PrepSmem {
     static constexpr size_t sz1 = cmax(sizeof(T) * C * LD, sizeof(float) * C * LF);
     // region 2: the operands of the inverse's MFMA stage
     static constexpr size_t oOp = oX + align16(sz1);
-    static constexpr size_t sz2 = sizeof(T) * 4 * 32 * LO;
-    static constexpr size_t oM = oOp + align16(sz2);
-    static constexpr size_t oBeta = oM + sizeof(float) * 512;
+    static constexpr size_t sz2 = cmax(sizeof(T) * 3 * 32 * LO, sizeof(float) * 512); // ... and, before that, the merges' scratch
+    static constexpr size_t oM = oOp;
+    static constexpr size_t oBeta = oOp + align16(sz2);
     static constexpr size_t bytes = oBeta + sizeof(float) * C;
 };
 

@@ -173,3 +173,18 @@ def test_few_long_chains_take_the_segmented_scans(dtype, d, B, H, L):
             assert nerr(a.float().cpu().numpy(), b.float().cpu().numpy()) < 1e-2   # two bf16 results, each within 5e-3 of the oracle
         else:              # the pair that keeps the forward's tiles runs the same segmented arithmetic
             assert torch.equal(a, b)
+
+
+def test_segmented_scans_without_optional_states():
+    # no initial state, no final-state gradient, and outputs for them not requested
+    inp = make_inputs(77, B=1, L=2048, H=2, dk=128, dv=128, dtype="bf16")
+    dd = dev_inputs(inp)
+    o, _ = dn.deltanet_fwd(dd["q"], dd["k"], dd["v"], dd["beta"], output_final_state=False)
+    grads = dn.deltanet_bwd(dd["q"], dd["k"], dd["v"], dd["beta"], dd["d_o"], want_dinitial_state=False)
+    torch.cuda.synchronize()
+    o_ref, _ = oracle.fwd(inp.q, inp.k, inp.v, inp.beta)
+    g_ref = oracle.bwd(inp.q, inp.k, inp.v, inp.beta, inp.d_o)
+    assert nerr(o.float().cpu().numpy(), o_ref) < TOL["bf16"]
+    for a, b in zip(grads[:4], g_ref[:4]):
+        assert nerr(a.float().cpu().numpy(), b) < TOL["bf16"]
+    assert grads[4] is None

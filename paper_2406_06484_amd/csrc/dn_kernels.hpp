@@ -968,6 +968,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
         lds_barrier(); // dX is dead
+        // prologue variant: the pre-activations of k are needed once more at the very end; they are requested again here
+        // rather than kept in registers through the products above
+        if (PRO) r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
         if (AHEAD) { // d_o, Ut^T, S^T, dUt^T of the next chunk: their registers have been free since this chunk's first barrier
             TileIter nx = it;
             nx.next();

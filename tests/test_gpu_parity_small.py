@@ -188,3 +188,23 @@ def test_segmented_scans_without_optional_states():
     for a, b in zip(grads[:4], g_ref[:4]):
         assert nerr(a.float().cpu().numpy(), b) < TOL["bf16"]
     assert grads[4] is None
+
+
+def test_seeded_random_shapes():
+    # a handful of seeded random shapes, dense and packed (with empty and one-token sequences), both element types
+    rng = np.random.default_rng(2024)
+    for case in range(10):
+        dtype, d = [("f32", 64), ("bf16", 128), ("bf16", 64)][case % 3]
+        H = int(rng.integers(1, 4))
+        if case % 2 == 0:
+            B, L = int(rng.integers(1, 4)), int(rng.integers(1, 700))
+            inp = make_inputs(3000 + case, B=B, L=L, H=H, dk=d, dv=d, dtype=dtype,
+                              with_initial_state=bool(case % 4 == 0), with_dfinal_state=bool(case % 4 == 2))
+            label = "random dense %s d=%d B=%d L=%d H=%d" % (dtype, d, B, L, H)
+        else:
+            lens = rng.integers(0, 300, size=int(rng.integers(1, 7)))
+            lens[rng.integers(0, len(lens))] = 1
+            cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+            inp = make_inputs(3000 + case, H=H, dk=d, dv=d, dtype=dtype, cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)
+            label = "random packed %s d=%d lens=%s H=%d" % (dtype, d, lens.tolist(), H)
+        check_fwd_bwd(inp, label=label)

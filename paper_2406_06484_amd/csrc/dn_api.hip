@@ -109,7 +109,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bo
     const size_t tV = up256(tiles * kChunk * s->d_v * pl->esz);
     const size_t tS = up256(tiles * (size_t)s->d_k * s->d_v * pl->esz);
     size_t o = 0;
-    pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * ((size_t)pb.N + 1)) : 0;
+    pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * (2 * (size_t)pb.N + 1)) : 0; // chunk offsets, then the length order
     const size_t tC = up256(tiles * kChunk * kChunk * pl->esz);
     pl->off_T = o; o += tC; // T of Eq. 10
     if (want_bwd) {

@@ -57,6 +57,7 @@ __device__ inline float sigmoid_f32(float x) { return __frcp_rn(__fadd_rn(1.f, _
 struct SeqMap {
     const int32_t *cu;   // device [N+1] or nullptr
     const int32_t *coff; // device [N+1] chunk offsets (packed only)
+    const int32_t *order; // device [N] sequences by decreasing length (packed only), for the chain-serial kernels
     int N, L, ncd;       // ncd = chunks per dense sequence
     __device__ void seq(int n, int &t0, int &len, int &cb) const {
         if (cu) { t0 = cu[n]; len = cu[n + 1] - t0; cb = coff[n]; }

@@ -27,8 +27,25 @@ enum { VAR_PLAIN = 0, VAR_GATED = 1, VAR_PROLOGUE = 2 };
 constexpr size_t align16(size_t x) { return (x + 15) & ~size_t(15); }
 
 // ---------------------------------------------------------------------------------------------
-// per-sequence chunk-count prefix for the packed layout: coff[n] = sum_{m<n} ceil(len_m / C)
+// per-sequence chunk-count prefix for the packed layout: coff[n] = sum_{m<n} ceil(len_m / C); behind it, order[i] = the
+// i-th longest sequence (ties by index): the chain-serial kernels start the long chains first, so that the short
+// ones fill the tail (up to kMaxOrdered sequences; more than that balance by themselves and keep their order)
+constexpr int kMaxOrdered = 512;
 static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) {
+    int32_t *order = coff + N + 1;
+    if (N <= kMaxOrdered) {
+        for (int n = threadIdx.x; n < N; n += NTHR) {
+            const int len = cu[n + 1] - cu[n];
+            int rank = 0;
+            for (int m = 0; m < N; ++m) {
+                const int lm = cu[m + 1] - cu[m];
+                rank += (lm > len) || (lm == len && m < n);
+            }
+            order[rank] = n;
+        }
+    } else {
+        for (int n = threadIdx.x; n < N; n += NTHR) order[n] = n;
+    }
     __shared__ int part[NTHR];
     const int tid = threadIdx.x;
     const int per = (N + NTHR - 1) / NTHR;
@@ -236,7 +253,9 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
-    const int n = chain / H, h = chain - n * H, vb = vbi * BV;
+    int n = chain / H;
+    const int h = chain - n * H, vb = vbi * BV;
+    if (sm.order) { n = sm.order[n]; chain = n * H + h; } // packed: longest sequences first
     const int wave = threadIdx.x >> 6;
     int t0, len, cb;
     sm.seq(n, t0, len, cb);
@@ -555,7 +574,9 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
-    const int n = chain / H, h = chain - n * H, vb = vbi * BV;
+    int n = chain / H;
+    const int h = chain - n * H, vb = vbi * BV;
+    if (sm.order) { n = sm.order[n]; chain = n * H + h; } // packed: longest sequences first
     const int wave = threadIdx.x >> 6;
     int t0, len, cb;
     sm.seq(n, t0, len, cb);

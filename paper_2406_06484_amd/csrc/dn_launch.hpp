@@ -23,6 +23,7 @@ template <typename K> static inline int set_lds(K kernel, size_t bytes) {
 static inline SeqMap make_map(const Problem &pb) {
     SeqMap sm;
     sm.cu = pb.cu; sm.coff = pb.coff; sm.N = pb.N; sm.L = pb.L; sm.ncd = (pb.L + C - 1) / C;
+    sm.order = pb.cu ? pb.coff + pb.N + 1 : nullptr;
     return sm;
 }
 

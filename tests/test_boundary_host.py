@@ -59,6 +59,16 @@ def test_workspace_query_and_validation_errors():
     assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(dtype=0, d_k=64, d_v=64)), 0, ctypes.byref(out)) == 0
     for code in range(0, -9, -1):
         assert lib.deltanet_status_string(code)
+    # few long chains (16 of them, 32768 tokens): the scans are cut into 8 segments per sequence, and the workspace holds
+    # five fp32 [segment, H, d_k, d_v] arrays for them (N, M, start state; R, end gradient)
+    long_shape = _shape(B=1, L=32768, H=16)
+    assert lib.deltanet_workspace_bytes(ctypes.byref(long_shape), 1, ctypes.byref(out)) == 0
+    tiles = (32768 // 64) * 16
+    base = tiles * (2 * 64 * 64 + 2 * 64 * 128 + 2 * 128 * 128) * 2          # T, X; Ut, dUt; S, dS' per chunk and head, bf16
+    assert out.value == base + 5 * (1 * 8 * 16 * 128 * 128 * 4)
+    # many chains: no cut, no such arrays
+    assert lib.deltanet_workspace_bytes(ctypes.byref(_shape(B=8, L=2048, H=16)), 1, ctypes.byref(out)) == 0
+    assert out.value == 8 * (2048 // 64) * 16 * (2 * 64 * 64 + 2 * 64 * 128 + 2 * 128 * 128) * 2
 
 
 def test_fwd_bwd_reject_bad_arguments_before_any_launch():

@@ -5,5 +5,4 @@ DN_INSTANTIATE(bf16, 128, 128)
 DN_INSTANTIATE(bf16, 64, 64)
 DN_INSTANTIATE(bf16, 64, 128)
 DN_INSTANTIATE(bf16, 128, 64)
-DN_INSTANTIATE_FWD(bf16, 256, 256)
 } // namespace dn

@@ -642,24 +642,30 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         if (loader && ic > 0) fetch_a(ic - 1);
         f32x16 acc = zero16();
         if (!loader) { // straight-line, as in the forward scan; the loader waves are busy with global memory meanwhile
+            // (with more than two W tiles per wave, d_k = 256, the tiles are finished one at a time, as in the forward scan)
+            constexpr bool SEQ = GATED || NWT > 2;
             f32x16 pa = zero16(); // P^T = triu(K Q^T), the transposed causal scores, computed as the tile (pni, pmi) of P
-            mma<DK, false, false, T, GATED, MB>(pa, sQ + 32 * pni * SM::LQ, SM::LQ, sK + 32 * pmi * SM::LK, SM::LK);
+            mma<DK, false, false, T, SEQ, MB>(pa, sQ + 32 * pni * SM::LQ, SM::LQ, sK + 32 * pmi * SM::LK, SM::LK);
             if (m.does_u) // K dS' part of the dUt tile (ua, ub)
-                mma<DK, false, false, T, GATED, MB>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
+                mma<DK, false, false, T, SEQ, MB>(acc, sK + 32 * m.ua * SM::LK, SM::LK, sDST + 32 * m.ub * SM::LS, SM::LS);
             f32x16 w[NWT];
 #pragma unroll
             for (int i = 0; i < NWT; ++i) { // W = T K (Eq. 11), computed as W^T = K^T T^T
                 const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
                 w[i] = zero16();
-                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES)
-                    mma<C, true, false, T, GATED, MB>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) {
+                    mma<C, true, false, T, SEQ, MB>(w[i], sK + 32 * wk, SM::LK, sT + 32 * wi * SM::LT, SM::LT);
+                    if (NWT > 2) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
+                }
             }
             acc_each(pa, [&](int r, int c, float &val) { if (32 * pni + r < 32 * pmi + c) val = 0.f; });
             acc_to_lds_t<T>(sPT, SM::LT, 32 * pni, 32 * pmi, pa);
+            if (NWT <= 2) {
 #pragma unroll
-            for (int i = 0; i < NWT; ++i) {
-                const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
-                if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
+                for (int i = 0; i < NWT; ++i) {
+                    const int t = wave + 4 * i, wk = t % Map::NKT, wi = t / Map::NKT;
+                    if (Map::W_TILES % 4 == 0 || t < Map::W_TILES) acc_to_lds_t<T>(sW, SM::LQ, 32 * wk, 32 * wi, w[i]);
+                }
             }
         }
         lds_barrier();

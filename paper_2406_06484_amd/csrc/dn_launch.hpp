@@ -3,6 +3,7 @@
 #pragma once
 #include "dn_host.hpp"
 #include "dn_kernels.hpp"
+#include "dn_chunk_wide.hpp"
 
 namespace dn {
 
@@ -35,20 +36,27 @@ static inline int launch_offsets(const Problem &pb) {
 
 constexpr size_t kLdsPerWorkgroup = 160 * 1024; // gfx950
 
+// Head sizes whose chunk operands do not fit the LDS at once take the streaming chunk kernel (plain delta rule only).
+template <typename T, int DK, int DV> constexpr bool kChunkFits = ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
+template <typename T, int DK, int DV> constexpr bool kWideBwd = !kChunkFits<T, DK, DV> && sizeof(T) == 2 && DK % 128 == 0 && DV % 64 == 0;
+// whether the backward pass is compiled for this head size
+template <typename T, int DK, int DV> constexpr bool kHasBwd = kChunkFits<T, DK, DV> || kWideBwd<T, DK, DV>;
+
 template <typename T, int DK, int DV> size_t max_lds_bytes() {
     static_assert(PrepSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_wy_prep LDS");
     static_assert(ScanFwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_fwd LDS");
     static_assert(ScanBwdSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_scan_bwd LDS");
-    static_assert(ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_chunk LDS");
     size_t m = PrepSmem<T, DK, DV>::bytes;
     if (ScanFwdSmem<T, DK, DV>::bytes > m) m = ScanFwdSmem<T, DK, DV>::bytes;
     if (ScanBwdSmem<T, DK, DV>::bytes > m) m = ScanBwdSmem<T, DK, DV>::bytes;
-    if (ChunkSmem<T, DK, DV>::bytes > m) m = ChunkSmem<T, DK, DV>::bytes;
+    if constexpr (kChunkFits<T, DK, DV>) {
+        if (ChunkSmem<T, DK, DV>::bytes > m) m = ChunkSmem<T, DK, DV>::bytes;
+    } else {
+        static_assert(WideSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup, "k_bwd_chunk_wide LDS");
+        if (WideSmem<T, DK, DV>::bytes > m) m = WideSmem<T, DK, DV>::bytes;
+    }
     return m;
 }
-
-// whether the backward pass is compiled for this head size (its chunk tiles must fit the LDS)
-template <typename T, int DK, int DV> constexpr bool kHasBwd = ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
 
 // forward-only instantiations (head sizes whose backward tiles do not fit)
 template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
@@ -63,6 +71,13 @@ template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
     do {                                                                                                    \
         if (p.g) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_GATED>), grid, nthreads, lds, __VA_ARGS__);            \
         else DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__);                \
+    } while (0)
+// the kernels of the backward pass at head sizes that have only the plain variant
+#define DN_LAUNCH_PLAIN(kernel, grid, nthreads, lds, ...) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__)
+#define DN_LAUNCH_SCAN_BWD(kernel, grid, nthreads, lds, ...)                                                \
+    do {                                                                                                    \
+        if constexpr (kWideBwd<T, DK, DV>) DN_LAUNCH_PLAIN(kernel, grid, nthreads, lds, __VA_ARGS__);       \
+        else DN_LAUNCH_SCAN(kernel, grid, nthreads, lds, __VA_ARGS__);                                      \
     } while (0)
 #define DN_LAUNCH_VAR(kernel, grid, nthreads, lds, ...)                                                     \
     do {                                                                                                    \
@@ -103,7 +118,8 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     }
     if constexpr (kHasBwd<T, DK, DV>) {
         if (pb.save) {
-            DN_LAUNCH_SCAN(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
+            if (kWideBwd<T, DK, DV> && (p.g || p.pro)) return -1; // no backward pass for these variants at this head size
+            DN_LAUNCH_SCAN_BWD(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
             return 0;
         }
     }
@@ -113,6 +129,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
 
 template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0) return 0;
+    if (kWideBwd<T, DK, DV> && (p.g || p.pro)) return -1; // the streaming chunk kernel knows the plain delta rule only
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
@@ -142,17 +159,20 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
             }
         }
     } else if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
-        DN_LAUNCH_SCAN(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
+        DN_LAUNCH_SCAN_BWD(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
     } else {
         if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
         // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         const dim3 gpair(2 * gchain.x);
-        DN_LAUNCH_SCAN(k_scan_pair, gpair, NTS, lds_pair, sm, pb.H, ps, (int)gchain.x);
+        DN_LAUNCH_SCAN_BWD(k_scan_pair, gpair, NTS, lds_pair, sm, pb.H, ps, (int)gchain.x);
     }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
-        DN_LAUNCH_VAR(k_bwd_chunk, gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        if constexpr (kWideBwd<T, DK, DV>)
+            DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        else
+            DN_LAUNCH_VAR(k_bwd_chunk, gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
     }
     return 0;
 }

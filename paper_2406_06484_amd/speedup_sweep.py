@@ -5,8 +5,7 @@ The workload is the one of the paper's speed-up figure (section 3.3): model widt
 heads of size d (H = 2048 / d), batch times length fixed at 16384 tokens, bf16, random unit-norm
 q, k.  For each (d, L) it times the forward pass of both forms through the C ABI, the chunkwise
 forward + backward as the self-contained pair and as the pair that keeps the forward pass's tiles,
-and prints one table row; the chunkwise backward is compiled for d = 64 and 128, the forward passes
-also for d = 256.
+and prints one table row.
 
     python -m paper_2406_06484_amd.speedup_sweep [--steps 20]
 """
@@ -59,22 +58,19 @@ def main() -> int:
             o = torch.empty_like(v)
             ST = torch.empty(B, H, d, d, dtype=torch.float32, device=dev)
             t_rec = timeit(lambda: dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST))
-            ws = torch.empty(deltanet_workspace_bytes(_shape_of(q, v, None, 64, []), d <= 128), dtype=torch.uint8, device=dev)
+            ws = torch.empty(deltanet_workspace_bytes(_shape_of(q, v, None, 64, []), True), dtype=torch.uint8, device=dev)
             t_chk = timeit(lambda: dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws))
-            if d <= 128:
 
-                def both():
-                    dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
-                    dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
+            def both():
+                dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws)
+                dn.deltanet_bwd(q, k, v, beta, d_o, workspace=ws)
 
-                def kept():
-                    dn.deltanet_fwd_save(q, k, v, beta, o=o, final_state=ST, saved=ws)
-                    dn.deltanet_bwd_saved(q, k, v, beta, d_o, ws)
-                t_fb, t_kept = timeit(both), timeit(kept)
-                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %16.3f %16.3f" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, t_fb, t_kept),
-                      flush=True)
-            else:
-                print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %16s %16s" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, "-", "-"), flush=True)
+            def kept():
+                dn.deltanet_fwd_save(q, k, v, beta, o=o, final_state=ST, saved=ws)
+                dn.deltanet_bwd_saved(q, k, v, beta, d_o, ws)
+            t_fb, t_kept = timeit(both), timeit(kept)
+            print("%5d %6d %4d %4d | %12.3f %12.3f %8.2fx | %16.3f %16.3f" % (d, L, B, H, t_rec, t_chk, t_rec / t_chk, t_fb, t_kept),
+                  flush=True)
     return 0
 
 

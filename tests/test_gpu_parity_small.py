@@ -128,15 +128,18 @@ def test_many_heads_and_the_sequence_count_limit():
     assert e.value.status == -2
 
 
-def test_head_size_256_forward_only():
-    # d_k = d_v = 256 is compiled for the forward pass (plain and gated); its backward is not
+def test_head_size_256():
+    # d_k = d_v = 256: the scans own 32 state columns per workgroup, the backward's chunk kernel streams S and dS' in
+    # column blocks; the gated rule and the fused prologue have the forward pass only at this head size
     from paper_2406_06484_amd.synth import make_gate
-    inp = make_inputs(31, B=2, L=200, H=2, dk=256, dv=256, dtype="bf16", with_initial_state=True)
+    inp = make_inputs(31, B=2, L=200, H=2, dk=256, dv=256, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
     inp.initial_state *= 10.0
-    check_fwd_bwd(inp, bwd=False, label="bf16 256x256 fwd")
+    check_fwd_bwd(inp, label="bf16 256x256")
     cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)
     pk = make_inputs(32, H=2, dk=256, dv=256, dtype="bf16", cu_seqlens=cu, with_initial_state=True)
-    check_fwd_bwd(pk, bwd=False, label="bf16 256x256 packed fwd")
+    check_fwd_bwd(pk, label="bf16 256x256 packed")
+    plain = make_inputs(33, B=1, L=448, H=3, dk=256, dv=256, dtype="bf16")   # no optional state, whole chunks
+    check_fwd_bwd(plain, label="bf16 256x256 no states")
     d = dev_inputs(inp)
     g = make_gate(5, inp.beta.shape, lo=0.6, hi=1.0)
     o, ST = dn.deltanet_gated_fwd(d["q"], d["k"], d["v"], d["beta"], torch.from_numpy(g).cuda(), d["S0"])
@@ -144,7 +147,7 @@ def test_head_size_256_forward_only():
     o_ref, ST_ref = oracle.gated_fwd(inp.q, inp.k, inp.v, inp.beta, g, inp.initial_state)
     assert nerr(o.float().cpu().numpy(), o_ref) < TOL["bf16"] and nerr(ST.cpu().numpy(), ST_ref) < TOL["bf16"]
     with pytest.raises(dn.DeltaNetError) as e:
-        dn.deltanet_bwd(d["q"], d["k"], d["v"], d["beta"], d["d_o"])
+        dn.deltanet_gated_bwd(d["q"], d["k"], d["v"], d["beta"], torch.from_numpy(g).cuda(), d["d_o"])
     assert e.value.status == -3
 
 

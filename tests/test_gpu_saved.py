@@ -39,13 +39,14 @@ def run_saved(inp, label, saved=None, check_oracle=True):
     return saved
 
 
-@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 128, 64)])
+@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 128, 64),
+                                         ("bf16", 256, 256)])
 def test_saved_pair_ragged_multi_chunk_with_states(dtype, dk, dv):
     inp = make_inputs(700 + dk + dv, B=2, L=200, H=3, dk=dk, dv=dv, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
     run_saved(inp, "saved %s %dx%d" % (dtype, dk, dv))
 
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 256)])
 def test_saved_pair_packed_with_empty_and_short_sequences(dtype, d):
     cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)
     inp = make_inputs(21, H=2, dk=d, dv=d, dtype=dtype, cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)
@@ -90,8 +91,8 @@ def test_gated_saved_pair(dtype, d):
 def test_saved_pair_rejects_what_it_cannot_do():
     inp = make_inputs(26, B=1, L=64, H=1, dk=256, dv=256, dtype="bf16")
     d = dev_inputs(inp)
-    with pytest.raises(dn.DeltaNetError) as ei:   # no backward pass at this head size, so nothing to save for
-        dn.deltanet_fwd_save(d["q"], d["k"], d["v"], d["beta"])
+    with pytest.raises(dn.DeltaNetError) as ei:   # no backward pass for the fused prologue at this head size, so nothing to save for
+        dn.deltanet_fused_fwd_save(d["q"], d["k"], d["v"], d["beta"])
     assert ei.value.status == -3
     inp = make_inputs(27, B=1, L=128, H=2, dk=128, dv=128, dtype="bf16")
     d = dev_inputs(inp)

@@ -162,25 +162,29 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
             lds_barrier();
         }
 
-        // ---- sweep 2's first blocks are requested before the C x C part
-        struct {
+        // ---- sweep 2's first blocks are requested before the C x C part.  Its blocks are small (28 KB), so two of them
+        // are kept in flight: two register sets, used alternately.
+        struct Blk {
             TileRegs<T, BV2, KB, NTC> s, ds;
             TileRegs<T, C, BV2, 256> a;  // first half of the workgroup: dO_b
             TileRegs<T, BV2, C, 256> b;  // first half: Ut_b^T; second half: dUt_b^T
-            TileRegs<T, C, KB, NTC> q;
-        } r2;
-        auto fetch2 = [&](int kb, int vb) __attribute__((always_inline)) {
-            r2.s.load(gS + (long)vb * BV2 * DK + kb * KB, DK, BV2, tid);
-            r2.ds.load(gDS + (long)vb * BV2 * DK + kb * KB, DK, BV2, tid);
+        } r2a, r2b;
+        TileRegs<T, C, KB, NTC> rq;
+        auto fetch2 = [&](Blk &r, int kb, int vb) __attribute__((always_inline)) {
+            if (vb >= NB2) { vb -= NB2; ++kb; } // blocks are numbered across the d_k blocks
+            if (kb >= NKB) return;
+            r.s.load(gS + (long)vb * BV2 * DK + kb * KB, DK, BV2, tid);
+            r.ds.load(gDS + (long)vb * BV2 * DK + kb * KB, DK, BV2, tid);
             if (grp_a) {
-                r2.a.load(gDO + vb * BV2, sv, nvalid, th);
-                r2.b.load(gUt + (long)vb * BV2 * C, C, BV2, th);
+                r.a.load(gDO + vb * BV2, sv, nvalid, th);
+                r.b.load(gUt + (long)vb * BV2 * C, C, BV2, th);
             } else {
-                r2.b.load(gDU + (long)vb * BV2 * C, C, BV2, th);
+                r.b.load(gDU + (long)vb * BV2 * C, C, BV2, th);
             }
         };
-        r2.q.load((const T *)p.q + (row0 * H + h) * DK, sk, nvalid, tid);
-        fetch2(0, 0);
+        rq.load((const T *)p.q + (row0 * H + h) * DK, sk, nvalid, tid);
+        fetch2(r2a, 0, 0);
+        fetch2(r2b, 0, 1);
 
         // ---- the C x C part (adjoint of Eq. 10-11)
         f32x16 g = zero16();
@@ -239,22 +243,26 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
             const int ka = wave >> 2, kc = wave & 3; // this wave's tile of a C x 128 block
             T *stg2 = reinterpret_cast<T *>(smem + SM::oStage2) + wave * Stage<T>::ELEMS;
             f32x16 dq = zero16(), dw = zero16(), dk1 = zero16();
-#pragma unroll 1
-            for (int vb = 0; vb < NB2; ++vb) {
-                r2.s.store(sS2, SM::LB, tid); r2.ds.store(sDS2, SM::LB, tid);
-                if (grp_a) { r2.a.store(sDO2, SM::LV2, th); r2.b.store(sUt2, SM::LU, th); }
-                else r2.b.store(sDU2, SM::LU, th);
+            auto block = [&](Blk &r, int vb) __attribute__((always_inline)) {
+                r.s.store(sS2, SM::LB, tid); r.ds.store(sDS2, SM::LB, tid);
+                if (grp_a) { r.a.store(sDO2, SM::LV2, th); r.b.store(sUt2, SM::LU, th); }
+                else r.b.store(sDU2, SM::LU, th);
                 if (vb == 0) {
-                    r2.q.store(sQ2, SM::LB, tid);
-                    if (kb + 1 < NKB) r2.q.load((const T *)p.q + (row0 * H + h) * DK + (kb + 1) * KB, sk, nvalid, tid);
+                    rq.store(sQ2, SM::LB, tid);
+                    if (kb + 1 < NKB) rq.load((const T *)p.q + (row0 * H + h) * DK + (kb + 1) * KB, sk, nvalid, tid);
                 }
                 lds_barrier();
-                if (vb + 1 < NB2) fetch2(kb, vb + 1);
-                else if (kb + 1 < NKB) fetch2(kb + 1, 0);
+                fetch2(r, kb, vb + 2); // this set's registers are free again
                 mma<BV2, false, true, T, true, MB>(dq, sDO2 + 32 * ka * SM::LV2, SM::LV2, sS2 + 32 * kc, SM::LB);  // dO S^T
                 mma<BV2, true, true, T, true, MB>(dw, sDU2 + 32 * ka, SM::LU, sS2 + 32 * kc, SM::LB);              // dUt S^T
                 mma<BV2, true, true, T, true, MB>(dk1, sUt2 + 32 * ka, SM::LU, sDS2 + 32 * kc, SM::LB);            // Ut dS'^T
                 lds_barrier();
+            };
+            static_assert(NB2 % 2 == 0, "blocks are taken in pairs");
+#pragma unroll 1
+            for (int vb = 0; vb < NB2; vb += 2) {
+                block(r2a, vb);
+                block(r2b, vb + 1);
             }
             const T *sKb = sK + kb * KB + 32 * kc; // this wave's 32 columns of K
             // dQ = dO S^T + dP K

@@ -140,6 +140,9 @@ def test_head_size_256():
     check_fwd_bwd(pk, label="bf16 256x256 packed")
     plain = make_inputs(33, B=1, L=448, H=3, dk=256, dv=256, dtype="bf16")   # no optional state, whole chunks
     check_fwd_bwd(plain, label="bf16 256x256 no states")
+    # more (chunk, head) tiles than compute units: the persistent workgroups of the chunk kernel walk over several tiles
+    many = make_inputs(34, B=2, L=2048 + 37, H=5, dk=256, dv=256, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
+    check_fwd_bwd(many, label="bf16 256x256 330 tiles")
     d = dev_inputs(inp)
     g = make_gate(5, inp.beta.shape, lo=0.6, hi=1.0)
     o, ST = dn.deltanet_gated_fwd(d["q"], d["k"], d["v"], d["beta"], torch.from_numpy(g).cuda(), d["S0"])

@@ -306,6 +306,33 @@ def main() -> int:
     out["fused_prologue_fwd_bwd"] = {"ms": round(fms, 4), "tokens_per_s": round(tokens / (fms * 1e-3), 1), "steps": args.steps,
                                      "vs_plain": round(fms / ms_per_step, 3)}
 
+    # The same number of tokens and the same model width at head size 256 (H / 2 heads): the scans own 32 state columns
+    # per workgroup and the backward's chunk kernel streams S and dS' in column blocks.
+    H2, d2 = max(1, H // 2), 2 * d
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    unit2 = lambda: torch.nn.functional.normalize(torch.randn(B, L, H2, d2, generator=gen), dim=-1).bfloat16().to(dev)
+    q2, k2 = unit2(), unit2()
+    v2 = torch.randn(B, L, H2, d2, generator=gen).bfloat16().to(dev)
+    do2 = torch.randn(B, L, H2, d2, generator=gen).bfloat16().to(dev)
+    b2 = torch.sigmoid(torch.randn(B, L, H2, generator=gen)).bfloat16().to(dev)
+    o2 = torch.empty_like(v2)
+    _, _, ws2 = dn.deltanet_fwd_save(q2, k2, v2, b2, o=o2)
+
+    def wide_step():
+        dn.deltanet_fwd_save(q2, k2, v2, b2, o=o2, saved=ws2)
+        return dn.deltanet_bwd_saved(q2, k2, v2, b2, do2, ws2)
+    for _ in range(args.warmup):
+        wide_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wide_step()
+    torch.cuda.synchronize()
+    wms = 1e3 * (time.perf_counter() - t0) / args.steps
+    out["head_size_256_fwd_bwd"] = {"ms": round(wms, 4), "tokens_per_s": round(tokens / (wms * 1e-3), 1), "steps": args.steps,
+                                    "config": {"B": B, "L": L, "H": H2, "d_head": d2}, "vs_plain": round(wms / ms_per_step, 3)}
+    del q2, k2, v2, do2, b2, o2, ws2
+
     if not args.no_cpu_baseline:
         import oracle
         nthr = oracle.max_threads()

@@ -199,8 +199,9 @@ def test_segmented_scans_without_optional_states():
 def test_seeded_random_shapes():
     # a handful of seeded random shapes, dense and packed (with empty and one-token sequences), both element types
     rng = np.random.default_rng(2024)
-    for case in range(10):
-        dtype, d = [("f32", 64), ("bf16", 128), ("bf16", 64)][case % 3]
+    for case in range(14):
+        # (the first ten cases keep the shapes they always had; the last four add the largest head size)
+        dtype, d = [("f32", 64), ("bf16", 128), ("bf16", 64)][case % 3] if case < 10 else ("bf16", 256)
         H = int(rng.integers(1, 4))
         if case % 2 == 0:
             B, L = int(rng.integers(1, 4)), int(rng.integers(1, 700))

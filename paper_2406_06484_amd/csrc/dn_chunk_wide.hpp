@@ -55,7 +55,10 @@ template <typename T, int DK, int DV> struct WideSmem {
     static constexpr size_t bytes = oDb + sizeof(float) * 4 * C;
 };
 
-template <typename T, int DK, int DV>
+// PRO: beta arrives as a logit (beta = sigmoid(logit), section 2.2) and dbeta leaves as the gradient with respect to it;
+// q and k are the mapped ones that k_wy_prep left in the workspace, and k_feature_map_bwd below takes dq and dk back
+// through the feature map afterwards.
+template <typename T, int DK, int DV, bool PRO>
 __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p, int chunks_total) {
     using SM = WideSmem<T, DK, DV>;
     constexpr int BV1 = SM::BV1, BV2 = SM::BV2, NB1 = DV / BV1, NB2 = DV / BV2;
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         // ---- sweep 1
         rh.k.store(sK, SM::LK, tid);
         rh.x.store(sX, SM::LT, tid);
-        if (tid < C) sBeta[tid] = tid < nvalid ? rh.beta : 0.f;
+        if (tid < C) sBeta[tid] = tid < nvalid ? (PRO ? sigmoid_f32(rh.beta) : rh.beta) : 0.f;
         f32x16 dp = zero16(), dxp = zero16();
         f32x16 dq0 = zero16(), dq1 = zero16(), dw0 = zero16(), dw1 = zero16(); // rows 0..31 and 32..63 of this wave's columns
         auto block1 = [&](Blk1 &r, int vb) __attribute__((always_inline)) {
@@ -249,7 +252,11 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
             for (int j = 0; j < 16; ++j) sum += sProd[i * SM::LF + seg * 16 + j];
             sum += __shfl_xor(sum, 1);
             sum += __shfl_xor(sum, 2);
-            if (seg == 0 && i < nvalid) p.dbeta[(row0 + i) * H + h] = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+            if (seg == 0 && i < nvalid) {
+                float db = sum + ((sDb[i] + sDb[C + i]) + (sDb[2 * C + i] + sDb[3 * C + i]));
+                if (PRO) db *= sBeta[i] * (1.f - sBeta[i]); // through the sigmoid
+                p.dbeta[(row0 + i) * H + h] = db;
+            }
         }
         lds_barrier(); // dX, M1^T and dA o G are dead: their bytes take the blocks of sweep 2
 
@@ -299,6 +306,29 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         it = nx;
         tp = np;
     }
+}
+
+// Gradient through the query/key feature map of section 3.3, row by row, in place: x = the pre-activations ([rows, DK],
+// contiguous), dy = on entry the gradient with respect to the mapped rows, on exit the gradient with respect to x.
+// One workgroup per 64 rows; a thread reads back from LDS only what it put there itself.
+template <typename T, int DK>
+__global__ __launch_bounds__(NTHR) void k_feature_map_bwd(const T *x, T *dy, long rows) {
+    constexpr int LD = ldn<T>(DK);
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *sD = reinterpret_cast<T *>(smem);
+    const long r0 = (long)blockIdx.x * C;
+    const int nvalid = (int)(rows - r0 < C ? rows - r0 : C);
+    TileRegs<T, C, DK, NTHR> rx, rd;
+    rx.load(x + r0 * DK, DK, nvalid);
+    rd.load(dy + r0 * DK, DK, nvalid);
+    float inv[TileRegs<T, C, DK, NTHR>::NIT];
+    {
+        TileRegs<T, C, DK, NTHR> y = rx;
+        y.feature_map(inv); // only the norms are needed
+    }
+    rd.store(sD, LD);
+    wave_lds_fence();
+    rx.feature_map_bwd_store(sD, LD, inv, dy + r0 * DK, DK, nvalid);
 }
 
 } // namespace dn

@@ -118,7 +118,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     }
     if constexpr (kHasBwd<T, DK, DV>) {
         if (pb.save) {
-            if (kWideBwd<T, DK, DV> && (p.g || p.pro)) return -1; // no backward pass for these variants at this head size
+            if (kWideBwd<T, DK, DV> && p.g) return -1; // no backward pass for the gated rule at this head size
             DN_LAUNCH_SCAN_BWD(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
             return 0;
         }
@@ -129,7 +129,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
 
 template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0) return 0;
-    if (kWideBwd<T, DK, DV> && (p.g || p.pro)) return -1; // the streaming chunk kernel knows the plain delta rule only
+    if (kWideBwd<T, DK, DV> && p.g) return -1; // the streaming chunk kernel does not know the gated rule
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
@@ -169,9 +169,18 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
-        if constexpr (kWideBwd<T, DK, DV>)
-            DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
-        else
+        if constexpr (kWideBwd<T, DK, DV>) {
+            if (p.pro) { // on the mapped q, k; then dq and dk go back through the feature map, in place
+                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, true>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, ps, pb.chunks_ub);
+                const long rows = (long)(pb.cu ? pb.L : (long)pb.N * pb.L) * pb.H;
+                const dim3 grows((unsigned)((rows + C - 1) / C));
+                constexpr size_t lds_map = sizeof(T) * C * ldn<T>(DK);
+                DN_LAUNCH((k_feature_map_bwd<T, DK>), grows, lds_map, (const T *)p.q, (T *)p.dq, rows);
+                DN_LAUNCH((k_feature_map_bwd<T, DK>), grows, lds_map, (const T *)p.k, (T *)p.dk, rows);
+            } else {
+                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, false>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+            }
+        } else
             DN_LAUNCH_VAR(k_bwd_chunk, gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
     }
     return 0;

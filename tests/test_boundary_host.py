@@ -106,11 +106,11 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     # the pair that keeps the forward pass's tiles: the buffer has the backward pass's size
     assert lib.deltanet_fwd_save(ctypes.byref(s), *args, fake, fwd_only_bytes(lib, s), None) == -5
     assert lib.deltanet_fwd_save(ctypes.byref(s), None, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -1
-    # at d = 256 the backward pass exists for the plain rule only, so there is nothing to keep for the other two
+    # at d = 256 the gated rule has no backward pass, so there is nothing to keep for it
     assert lib.deltanet_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), *args, fake, 16, None) == -5
+    assert lib.deltanet_fused_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), *args, fake, 16, None) == -5
     assert lib.deltanet_gated_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), fake, fake, fake, fake, fake, None, fake, None,
                                        fake, 1 << 40, None) == -3
-    assert lib.deltanet_fused_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), *args, fake, 1 << 40, None) == -3
     sargs = [fake] * 4 + [fake, None, fake, fake, fake, fake, None]
     assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, fake, 16, None) == -5
     assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, odd, 1 << 40, None) == -4
@@ -124,7 +124,8 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     assert lib.deltanet_fused_fwd(ctypes.byref(s), *args, fake, 16, None) == -5
     fb = [fake] * 4 + [None, fake, None, fake, fake, fake, fake, None]
     assert lib.deltanet_fused_bwd(ctypes.byref(s), *fb, fake, 16, None) == -5
-    assert lib.deltanet_fused_bwd(ctypes.byref(_shape(d_k=256, d_v=256)), *fb, fake, 1 << 40, None) == -3
+    assert lib.deltanet_fused_bwd(ctypes.byref(_shape(d_k=256, d_v=256)), *fb, fake, 16, None) == -5
+    assert lib.deltanet_gated_bwd(ctypes.byref(_shape(d_k=256, d_v=256)), *gb, fake, 1 << 40, None) == -3
     assert lib.deltanet_fused_fwd_save(ctypes.byref(s), *args, fake, fwd_only_bytes(lib, s), None) == -5
     fs = [fake] * 4 + [fake, None, fake, fake, fake, None, None]  # dbeta_logit missing
     assert lib.deltanet_fused_bwd_saved(ctypes.byref(s), *fs, fake, 1 << 40, None) == -1

@@ -37,13 +37,14 @@ def run_fused(inp, label, check_saved=True):
             assert torch.equal(a, b), (label, name)
 
 
-@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 64, 64)])
+@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 64, 64),
+                                         ("bf16", 256, 256)])
 def test_fused_ragged_multi_chunk_with_states(dtype, dk, dv):
     base = make_inputs(800 + dk + dv, B=2, L=200, H=3, dk=dk, dv=dv, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
     run_fused(make_pre_activations(1, base), "fused %s %dx%d" % (dtype, dk, dv))
 
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 256)])
 def test_fused_packed_with_empty_and_short_sequences(dtype, d):
     cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)
     base = make_inputs(31, H=2, dk=d, dv=d, dtype=dtype, cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)

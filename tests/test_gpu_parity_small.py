@@ -130,7 +130,7 @@ def test_many_heads_and_the_sequence_count_limit():
 
 def test_head_size_256():
     # d_k = d_v = 256: the scans own 32 state columns per workgroup, the backward's chunk kernel streams S and dS' in
-    # column blocks; the gated rule and the fused prologue have the forward pass only at this head size
+    # column blocks; the gated rule has the forward pass only at this head size
     from paper_2406_06484_amd.synth import make_gate
     inp = make_inputs(31, B=2, L=200, H=2, dk=256, dv=256, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
     inp.initial_state *= 10.0

@@ -91,8 +91,8 @@ def test_gated_saved_pair(dtype, d):
 def test_saved_pair_rejects_what_it_cannot_do():
     inp = make_inputs(26, B=1, L=64, H=1, dk=256, dv=256, dtype="bf16")
     d = dev_inputs(inp)
-    with pytest.raises(dn.DeltaNetError) as ei:   # no backward pass for the fused prologue at this head size, so nothing to save for
-        dn.deltanet_fused_fwd_save(d["q"], d["k"], d["v"], d["beta"])
+    with pytest.raises(dn.DeltaNetError) as ei:   # no backward pass for the gated rule at this head size, so nothing to save for
+        dn.deltanet_gated_fwd_save(d["q"], d["k"], d["v"], d["beta"], torch.zeros_like(d["beta"], dtype=torch.float32))
     assert ei.value.status == -3
     inp = make_inputs(27, B=1, L=128, H=2, dk=128, dv=128, dtype="bf16")
     d = dev_inputs(inp)

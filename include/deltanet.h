@@ -74,8 +74,7 @@ int deltanet_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *out_by
  * Forward pass (Eq. 8-11).  initial_state may be NULL (zeros).  final_state may be NULL (not
  * written).  Outputs: o (element type dtype), final_state (fp32).
  * Compiled (d_k, d_v): fp32 (64,64), (32,64), (64,32); bf16 (128,128), (64,64), (64,128), (128,64)
- * and (256,256).  At (256,256) the gated rule has its forward pass only: deltanet_gated_bwd,
- * deltanet_gated_fwd_save / _bwd_saved and the gated backward workspace query return DN_ERR_UNSUPPORTED there.
+ * and (256,256); every entry point below runs at each of them.
  */
 int deltanet_fwd(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
                  const float *initial_state, void *o, float *final_state, void *workspace,

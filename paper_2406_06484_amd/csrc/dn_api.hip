@@ -43,26 +43,22 @@ constexpr int kChunk = 64;
 
 struct Plan {
     Problem pb;
-    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_Qm, off_Km, off_seg, seg_bytes, total;
+    size_t off_coff, off_T, off_X, off_Ut, off_dUt, off_Sc, off_dSc, off_gam, off_zg, off_Qm, off_Km, off_seg, seg_bytes, total;
     size_t esz;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
 typedef int (*run_fn)(const Problem &, const Ptrs &);
-// bwd_gated: the backward pass also exists for the gated rule
-struct Impl { int dtype, dk, dv; run_fn fwd, bwd; size_t (*lds)(); bool bwd_gated; };
+struct Impl { int dtype, dk, dv; run_fn fwd, bwd; size_t (*lds)(); };
 
-#define DN_IMPL(ENUM, T, DK, DV) { ENUM, DK, DV, &run_fwd<T, DK, DV>, &run_bwd<T, DK, DV>, &max_lds_bytes<T, DK, DV>, true }
+#define DN_IMPL(ENUM, T, DK, DV) { ENUM, DK, DV, &run_fwd<T, DK, DV>, &run_bwd<T, DK, DV>, &max_lds_bytes<T, DK, DV> }
 const Impl kImpls[] = {
     DN_IMPL(DN_F32, float, 64, 64),     DN_IMPL(DN_F32, float, 32, 64),    DN_IMPL(DN_F32, float, 64, 32),
     DN_IMPL(DN_BF16, bf16_t, 128, 128), DN_IMPL(DN_BF16, bf16_t, 64, 64),
     DN_IMPL(DN_BF16, bf16_t, 64, 128),  DN_IMPL(DN_BF16, bf16_t, 128, 64),
-    // the chunk tiles of the backward pass do not fit the LDS at this head size: they are streamed, not for the gated rule
-    { DN_BF16, 256, 256, &run_fwd<bf16_t, 256, 256>, &run_bwd<bf16_t, 256, 256>, &max_lds_bytes<bf16_t, 256, 256>, false },
+    DN_IMPL(DN_BF16, bf16_t, 256, 256), // (the chunk tiles of its backward pass are streamed: they do not fit the LDS)
 };
-
-bool has_bwd(const Impl *im, bool gated) { return im->bwd && (im->bwd_gated || !gated); }
 
 const Impl *find_impl(const dn_shape *s) {
     for (const Impl &im : kImpls)
@@ -124,6 +120,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bo
     }
     if (gated) {
         pl->off_gam = o; o += up256(tiles * 2 * kChunk * sizeof(float)); // gamma_i and 1 / gamma_i per chunk row
+        pl->off_zg = o; o += up256(tiles * sizeof(float)); // <dS_C, S_C> per chunk, where the gate gradient takes a second kernel
     }
     { // forward pass split over segments of the sequence: N, M and the start state per segment
         const int nv = s->d_v / scan_vblock_cols((int)pl->esz, s->d_k, s->d_v);
@@ -153,6 +150,7 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     }
     if (gated) {
         p->gam = reinterpret_cast<float *>(b + pl.off_gam);
+        p->zg = reinterpret_cast<float *>(b + pl.off_zg);
     }
     if (prologue) {
         p->Qm = b + pl.off_Qm; p->Km = b + pl.off_Km;
@@ -180,7 +178,7 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
              size_t workspace_bytes, void *hip_stream, bool save = false, bool prologue = false) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
-    if (save && !has_bwd(impl, gated)) return DN_ERR_UNSUPPORTED;
+    if (save && !impl->bwd) return DN_ERR_UNSUPPORTED;
     if (!q || !k || !v || !beta || !o || (gated && !g)) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, workspace, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
@@ -204,7 +202,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
              void *hip_stream, bool saved = false, bool prologue = false) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
-    if (!has_bwd(impl, gated)) return DN_ERR_UNSUPPORTED;
+    if (!impl->bwd) return DN_ERR_UNSUPPORTED;
     if (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta || (gated && (!g || !dg))) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
                         workspace, shape->cu_seqlens};
@@ -270,7 +268,7 @@ int deltanet_fused_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *
     if (!out_bytes) return DN_ERR_NULL;
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
-    if (want_bwd && !has_bwd(impl, false)) return DN_ERR_UNSUPPORTED;
+    if (want_bwd && !impl->bwd) return DN_ERR_UNSUPPORTED;
     Plan pl;
     make_plan(shape, want_bwd, &pl, false, true);
     *out_bytes = pl.total;
@@ -311,7 +309,7 @@ int deltanet_gated_workspace_bytes(const dn_shape *shape, int want_bwd, size_t *
     if (!out_bytes) return DN_ERR_NULL;
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
-    if (want_bwd && !has_bwd(impl, true)) return DN_ERR_UNSUPPORTED;
+    if (want_bwd && !impl->bwd) return DN_ERR_UNSUPPORTED;
     Plan pl;
     make_plan(shape, want_bwd, &pl, true);
     *out_bytes = pl.total;

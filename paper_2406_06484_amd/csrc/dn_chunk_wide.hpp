@@ -17,9 +17,13 @@
 // K, X, dP, Ah (and dW from the end of sweep 1) stay in LDS for the whole chunk.  Every block is requested into
 // registers ahead of its use: two blocks ahead in both sweeps (32 KB and 20 KB per block; two register sets used alternately).
 #pragma once
+#include <type_traits>
+
 #include "dn_kernels.hpp"
 
 namespace dn {
+
+struct NoTile {};
 
 template <typename T, int DK, int DV> struct WideSmem {
     static constexpr int BV1 = 32, BV2 = 32;
@@ -52,14 +56,21 @@ template <typename T, int DK, int DV> struct WideSmem {
     static constexpr size_t oStage = align16(cmax(cmax(endB1, endBc), cmax(endB2, endBq))); // per-wave output staging tiles
     static constexpr size_t oBeta = oStage + NWC * sizeof(T) * Stage<T>::ELEMS;
     static constexpr size_t oDb = oBeta + sizeof(float) * C;
-    static constexpr size_t bytes = oDb + sizeof(float) * 4 * C;
+    static constexpr size_t oGi = oDb + sizeof(float) * 4 * C;  // gated: 1 / gamma_i
+    static constexpr size_t oZ = oGi + sizeof(float) * C;       // gated: per-wave shares of z
+    static constexpr size_t bytes = oZ + sizeof(float) * NWC;
 };
 
-// PRO: beta arrives as a logit (beta = sigmoid(logit), section 2.2) and dbeta leaves as the gradient with respect to it;
-// q and k are the mapped ones that k_wy_prep left in the workspace, and k_feature_map_bwd below takes dq and dk back
+// VAR_PROLOGUE: beta arrives as a logit (beta = sigmoid(logit), section 2.2) and dbeta leaves as the gradient with respect
+// to it; q and k are the mapped ones that k_wy_prep left in the workspace, and k_feature_map_bwd below takes dq and dk back
 // through the feature map afterwards.
-template <typename T, int DK, int DV, bool PRO>
+// VAR_GATED: as in k_bwd_chunk the chunk is the plain rule on v_i / gamma_i with outputs gamma_i o~_i: dO rows come in scaled
+// by gamma_i, V rows by 1 / gamma_i, dV goes out scaled by 1 / gamma_i.  Of the gate gradient this kernel leaves, per chunk,
+// z = <dS_C, S_C> = <dS~', S_0> + <K, Ut dS~'^T> in p.zg (S is read a second time in sweep 2 for the first term, registers
+// only); k_gate_grad below adds the per-token terms.
+template <typename T, int DK, int DV, int VAR>
 __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p, int chunks_total) {
+    constexpr bool PRO = VAR == VAR_PROLOGUE, GATED = VAR == VAR_GATED;
     using SM = WideSmem<T, DK, DV>;
     constexpr int BV1 = SM::BV1, BV2 = SM::BV2, NB1 = DV / BV1, NB2 = DV / BV2;
     static_assert(DK == 32 * NWC && DV % BV1 == 0 && NB1 % 2 == 0 && NB2 % 2 == 0, "one block of 32 columns of d_k per wave");
@@ -77,6 +88,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
     T *sDS2 = reinterpret_cast<T *>(smem + SM::oDS2), *sUt2 = reinterpret_cast<T *>(smem + SM::oUt2);
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
     float *sBeta = reinterpret_cast<float *>(smem + SM::oBeta), *sDb = reinterpret_cast<float *>(smem + SM::oDb);
+    float *sGi = reinterpret_cast<float *>(smem + SM::oGi), *sZ = reinterpret_cast<float *>(smem + SM::oZ);
 
     const int lane = threadIdx.x & 63;
     int tid = threadIdx.x, wave = tid >> 6;
@@ -92,6 +104,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         TileRegs<T, C, DK, NTC> k;
         TileRegs<T, C, C, NTC> x;
         float beta;
+        float rowf[1], gi; // gated: gamma (first half of the workgroup) or 1 / gamma (second half) of this lane's dO / V row; 1 / gamma_tid
     } rh;
     auto pos_of = [&](const TileIter &i) __attribute__((always_inline)) { return i.valid() ? tile_pos(sm, H, i.gid(), i.head()) : TilePos{0, 0, 0, 0, false}; };
     // (no branches in the request code: the compiler then knows how many requests are in flight at every point and waits
@@ -108,6 +121,11 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         rh.k.load((const T *)p.k + (t.row0 * H + t.h) * DK, (long)H * DK, t.nvalid, tid);
         rh.x.load((const T *)p.Xm + t.tile * C * C, C, C, tid);
         rh.beta = to_f32(((const T *)p.beta)[(t.row0 + min(tid, t.nvalid - 1)) * H + t.h]); // (masked where it is used)
+        if (GATED) {
+            const float *gt = p.gam + t.tile * 2 * C;
+            rh.rowf[0] = gt[(first_half ? 0 : C) + (tid & 255) / TileRegs<T, C, BV1, 256>::TPR];
+            rh.gi = gt[C + (tid & (C - 1))];
+        }
         fetch1(r1a, t, 0);
         fetch1(r1b, t, 1);
     };
@@ -140,10 +158,13 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         rh.k.store(sK, SM::LK, tid);
         rh.x.store(sX, SM::LT, tid);
         if (tid < C) sBeta[tid] = tid < nvalid ? (PRO ? sigmoid_f32(rh.beta) : rh.beta) : 0.f;
+        if (GATED && tid < C) sGi[tid] = rh.gi;
+        const float rowf[1] = {rh.rowf[0]}; // (rh is refilled for the next chunk before this chunk's last blocks are stored)
         f32x16 dp = zero16(), dxp = zero16();
         f32x16 dq0 = zero16(), dq1 = zero16(), dw0 = zero16(), dw1 = zero16(); // rows 0..31 and 32..63 of this wave's columns
         auto block1 = [&](Blk1 &r, int vb) __attribute__((always_inline)) {
             r.s.store(sS1, SM::LK, tid);
+            if (GATED) r.a.scale_rows(rowf);
             if (grp_a) { r.a.store(sDO1, SM::LV1, th); r.b.store(sUt1, SM::LU, th); }
             else { r.a.store(sV1, SM::LV1, th); r.b.store(sDU1, SM::LU, th); }
             lds_barrier();
@@ -161,7 +182,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
                 f32x16 acc = zero16();
                 if (mi == 1) mma<32, true, false, T, true, MB>(acc, sX + 32 * SM::LT + 32, SM::LT, sDU1 + 32, SM::LU);
                 else mma<C, true, false, T, true, MB>(acc, sX, SM::LT, sDU1, SM::LU);
-                acc_each(acc, [&](int rr, int, float &val) { val *= sBeta[32 * mi + rr]; });
+                acc_each(acc, [&](int rr, int, float &val) { val *= GATED ? sBeta[32 * mi + rr] * sGi[32 * mi + rr] : sBeta[32 * mi + rr]; });
                 acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, sv, 32 * mi, vb * BV1, nvalid, acc);
             }
             lds_barrier();
@@ -177,12 +198,14 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         struct Blk {
             TileRegs<T, BV2, DK, NTC> ds;
             TileRegs<T, BV2, C, 256> ut; // first half of the workgroup
+            std::conditional_t<GATED, TileRegs<T, BV2, DK, NTC>, NoTile> s; // gated: the S block once more, for <dS~', S_0>
         } r2a, r2b;
         TileRegs<T, C, DK, NTC> rq;
         auto fetch2 = [&](Blk &r, int vb) __attribute__((always_inline)) {
             vb = min(vb, NB2 - 1);
             r.ds.load(gDS + (long)vb * BV2 * DK, DK, BV2, tid);
             r.ut.load(gUt + (long)vb * BV2 * C, C, BV2, th); // (both halves of the workgroup hold a copy)
+            if constexpr (GATED) r.s.load((const T *)p.Sc + (tile * DV + (long)vb * BV2) * DK, DK, BV2, tid);
         };
         fetch2(r2a, 0);
         fetch2(r2b, 1);
@@ -263,7 +286,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         // ---- sweep 2: dK1 = Ut dS'^T
         derive();
         f32x16 dk0 = zero16(), dk1 = zero16();
+        float zp = 0.f; // gated: this thread's share of z
         auto block = [&](Blk &r, int vb) __attribute__((always_inline)) {
+            if constexpr (GATED) zp += r.ds.dot(r.s);
             r.ds.store(sDS2, SM::LK, tid);
             if (grp_a) r.ut.store(sUt2, SM::LU, th);
             lds_barrier();
@@ -278,6 +303,13 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
             block(r2b, vb + 1);
         }
         derive();
+        if (GATED) { // <K, Ut dS~'^T>, while dK1 holds just that product; then this wave's share of z
+            acc_each(dk0, [&](int rr, int c, float &val) { zp += val * to_f32(sK[rr * SM::LK + kc + c]); });
+            acc_each(dk1, [&](int rr, int c, float &val) { zp += val * to_f32(sK[(32 + rr) * SM::LK + kc + c]); });
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) zp += __shfl_xor(zp, d);
+            if (lane == 0) sZ[wave] = zp;
+        }
         // the next chunk's head (this chunk's once more if there is none: no branch around the requests)
         TileIter nx = it;
         nx.next();
@@ -285,6 +317,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
         fetch_head(np.ok ? np : tp);
         rq.store(sQ, SM::LK, tid); // over the blocks of sweep 2
         lds_barrier();
+        if (GATED && tid == 0) p.zg[tile] = ((sZ[0] + sZ[1]) + (sZ[2] + sZ[3])) + ((sZ[4] + sZ[5]) + (sZ[6] + sZ[7]));
         // dK = dK1 + dP^T Q + diag(beta) X^T dW + Ah K + Ah^T K (dP and Ah are lower triangular, X^T upper)
         mma<C, true, true, T, true, MB>(dk0, sDP, SM::LT, sQ + kc, SM::LK);
         mma<32, true, true, T, true, MB>(dk1, sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + kc, SM::LK);
@@ -329,6 +362,59 @@ __global__ __launch_bounds__(NTHR) void k_feature_map_bwd(const T *x, T *dy, lon
     rd.store(sD, LD);
     wave_lds_fence();
     rx.feature_map_bwd_store(sD, LD, inv, dy + r0 * DK, DK, nvalid);
+}
+
+// The gate gradient of the gated variant for head sizes that take k_bwd_chunk_wide: o_t is linear in q_t and in the state, so
+// the sensitivity to a rescaling of the state at token j can be read off the other gradients,
+//     dg_j = z + sum_{i = j .. end of the chunk} (q_i . dq_i - v_i . dv_i),
+// with z = <dS_C, S_C> per chunk from k_bwd_chunk_wide.  One workgroup per (chunk, head), 256 threads.
+template <typename T, int DK, int DV>
+__global__ __launch_bounds__(NTHR) void k_gate_grad(SeqMap sm, int H, Ptrs p) {
+    __shared__ float sC[C];
+    const TilePos tp = tile_pos(sm, H, blockIdx.x, blockIdx.y);
+    if (!tp.ok) return;
+    const int tid = threadIdx.x;
+    auto row_dots = [&](auto &a, auto &b, float sign) __attribute__((always_inline)) { // sC[row] += sign * a[row] . b[row]
+        typedef typename std::remove_reference<decltype(a)>::type TR;
+#pragma unroll
+        for (int it = 0; it < TR::NIT; ++it) {
+            alignas(16) T x[TR::VEC], y[TR::VEC];
+            *reinterpret_cast<uint4 *>(x) = a.v[it];
+            *reinterpret_cast<uint4 *>(y) = b.v[it];
+            float s = 0.f;
+#pragma unroll
+            for (int u = 0; u < TR::VEC; ++u) s += to_f32(x[u]) * to_f32(y[u]);
+#pragma unroll
+            for (int d = 1; d < TR::TPR; d <<= 1) s += __shfl_xor(s, d); // the TPR lanes of a row are adjacent
+            if (tid % TR::TPR == 0) sC[it * TR::RPI + tid / TR::TPR] += sign * s; // one lane per row, rows differ between lanes
+        }
+    };
+    if (tid < C) sC[tid] = 0.f;
+    __syncthreads();
+    {
+        TileRegs<T, C, DK, NTHR> a, b;
+        a.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
+        b.load((const T *)p.dq + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
+        row_dots(a, b, 1.f);
+    }
+    __syncthreads();
+    {
+        TileRegs<T, C, DV, NTHR> a, b;
+        a.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
+        b.load((const T *)p.dv + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
+        row_dots(a, b, -1.f);
+    }
+    __syncthreads();
+    if (tid < C) { // thread t takes token C - 1 - t; an inclusive scan over t is the suffix sum over tokens
+        const int tok = C - 1 - tid;
+        float c = sC[tok];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float up = __shfl_up(c, d);
+            if (tid >= d) c += up;
+        }
+        if (tok < tp.nvalid) p.dg[(tp.row0 + tok) * H + tp.h] = c + p.zg[tp.tile];
+    }
 }
 
 } // namespace dn

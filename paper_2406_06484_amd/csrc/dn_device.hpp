@@ -297,6 +297,19 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
         }
         return s;
     }
+    // sum over the elements this lane holds of (this tile) * (another held tile of the same shape)
+    __device__ inline float dot(const TileRegs &o) const {
+        float s = 0.f;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            alignas(16) T a[VEC], b[VEC];
+            *reinterpret_cast<uint4 *>(a) = v[it];
+            *reinterpret_cast<uint4 *>(b) = o.v[it];
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) s += to_f32(a[u]) * to_f32(b[u]);
+        }
+        return s;
+    }
     // The query/key feature map of section 3.3 on the held tile, in place: every row x becomes
     // SiLU(x) / ||SiLU(x)||_2 (a row whose image is exactly zero, such as a row past the end, stays zero).
     // The TPR lanes that share a row are adjacent, so the row sum is a butterfly over them.

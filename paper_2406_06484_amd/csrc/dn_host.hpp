@@ -31,6 +31,7 @@ struct Ptrs {
     // ([tile][2][C] fp32)
     const float *g;
     float *dg, *gam;
+    float *zg; // gated, head sizes that take the streaming chunk kernel: <dS_C, S_C> per (chunk, head), for the gate gradient
     // prologue variant: q and k hold the pre-activations of the feature map, beta the logits; dq, dk and
     // dbeta receive the gradients with respect to those; workspace: Qm, Km = q, k after the map (layout of q, k)
     int pro;

@@ -36,7 +36,7 @@ static inline int launch_offsets(const Problem &pb) {
 
 constexpr size_t kLdsPerWorkgroup = 160 * 1024; // gfx950
 
-// Head sizes whose chunk operands do not fit the LDS at once take the streaming chunk kernel (plain delta rule only).
+// Head sizes whose chunk operands do not fit the LDS at once take the streaming chunk kernel.
 template <typename T, int DK, int DV> constexpr bool kChunkFits = ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
 template <typename T, int DK, int DV> constexpr bool kWideBwd = !kChunkFits<T, DK, DV> && sizeof(T) == 2 && DK % 128 == 0 && DV % 64 == 0;
 // whether the backward pass is compiled for this head size
@@ -71,13 +71,6 @@ template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
     do {                                                                                                    \
         if (p.g) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_GATED>), grid, nthreads, lds, __VA_ARGS__);            \
         else DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__);                \
-    } while (0)
-// the kernels of the backward pass at head sizes that have only the plain variant
-#define DN_LAUNCH_PLAIN(kernel, grid, nthreads, lds, ...) DN_LAUNCH_NT((kernel<T, DK, DV, VAR_PLAIN>), grid, nthreads, lds, __VA_ARGS__)
-#define DN_LAUNCH_SCAN_BWD(kernel, grid, nthreads, lds, ...)                                                \
-    do {                                                                                                    \
-        if constexpr (kWideBwd<T, DK, DV>) DN_LAUNCH_PLAIN(kernel, grid, nthreads, lds, __VA_ARGS__);       \
-        else DN_LAUNCH_SCAN(kernel, grid, nthreads, lds, __VA_ARGS__);                                      \
     } while (0)
 #define DN_LAUNCH_VAR(kernel, grid, nthreads, lds, ...)                                                     \
     do {                                                                                                    \
@@ -118,8 +111,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     }
     if constexpr (kHasBwd<T, DK, DV>) {
         if (pb.save) {
-            if (kWideBwd<T, DK, DV> && p.g) return -1; // no backward pass for the gated rule at this head size
-            DN_LAUNCH_SCAN_BWD(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
+            DN_LAUNCH_SCAN(k_scan_fwd_save, gchain, NTS, (ScanFwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
             return 0;
         }
     }
@@ -129,7 +121,6 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
 
 template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs &p) {
     if (pb.N == 0) return 0;
-    if (kWideBwd<T, DK, DV> && p.g) return -1; // the streaming chunk kernel does not know the gated rule
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
@@ -159,26 +150,29 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
             }
         }
     } else if (pb.save) { // T, X, Ut and the chunk-initial states are the forward pass's: only the reverse scan is left
-        DN_LAUNCH_SCAN_BWD(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
+        DN_LAUNCH_SCAN(k_scan_bwd, gchain, NTS, (ScanBwdSmem<T, DK, DV>::bytes), sm, pb.H, ps);
     } else {
         if (pb.chunks_ub) DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
         // both scans of the backward pass as one grid: reverse scan first, recompute scan behind it
         const dim3 gpair(2 * gchain.x);
-        DN_LAUNCH_SCAN_BWD(k_scan_pair, gpair, NTS, lds_pair, sm, pb.H, ps, (int)gchain.x);
+        DN_LAUNCH_SCAN(k_scan_pair, gpair, NTS, lds_pair, sm, pb.H, ps, (int)gchain.x);
     }
     if (pb.chunks_ub) {
         const long tiles = (long)pb.chunks_ub * pb.H;
         const dim3 gpers((unsigned)(tiles < pb.num_cus ? tiles : pb.num_cus)); // one persistent workgroup per CU
         if constexpr (kWideBwd<T, DK, DV>) {
             if (p.pro) { // on the mapped q, k; then dq and dk go back through the feature map, in place
-                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, true>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, ps, pb.chunks_ub);
+                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, VAR_PROLOGUE>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, ps, pb.chunks_ub);
                 const long rows = (long)(pb.cu ? pb.L : (long)pb.N * pb.L) * pb.H;
                 const dim3 grows((unsigned)((rows + C - 1) / C));
                 constexpr size_t lds_map = sizeof(T) * C * ldn<T>(DK);
                 DN_LAUNCH((k_feature_map_bwd<T, DK>), grows, lds_map, (const T *)p.q, (T *)p.dq, rows);
                 DN_LAUNCH((k_feature_map_bwd<T, DK>), grows, lds_map, (const T *)p.k, (T *)p.dk, rows);
+            } else if (p.g) { // the kernel leaves <dS_C, S_C> per chunk; the per-token terms of the gate gradient follow
+                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, VAR_GATED>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+                DN_LAUNCH((k_gate_grad<T, DK, DV>), gchunk, 0, sm, pb.H, p);
             } else {
-                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, false>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+                DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, VAR_PLAIN>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
             }
         } else
             DN_LAUNCH_VAR(k_bwd_chunk, gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);

@@ -106,11 +106,12 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     # the pair that keeps the forward pass's tiles: the buffer has the backward pass's size
     assert lib.deltanet_fwd_save(ctypes.byref(s), *args, fake, fwd_only_bytes(lib, s), None) == -5
     assert lib.deltanet_fwd_save(ctypes.byref(s), None, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == -1
-    # at d = 256 the gated rule has no backward pass, so there is nothing to keep for it
+    # d = 256 has all three variants; a pair of head sizes that is not compiled is refused
     assert lib.deltanet_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), *args, fake, 16, None) == -5
     assert lib.deltanet_fused_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), *args, fake, 16, None) == -5
     assert lib.deltanet_gated_fwd_save(ctypes.byref(_shape(d_k=256, d_v=256)), fake, fake, fake, fake, fake, None, fake, None,
-                                       fake, 1 << 40, None) == -3
+                                       fake, 16, None) == -5
+    assert lib.deltanet_fwd_save(ctypes.byref(_shape(d_k=128, d_v=256)), *args, fake, 1 << 40, None) == -3
     sargs = [fake] * 4 + [fake, None, fake, fake, fake, fake, None]
     assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, fake, 16, None) == -5
     assert lib.deltanet_bwd_saved(ctypes.byref(s), *sargs, odd, 1 << 40, None) == -4
@@ -125,7 +126,7 @@ def test_fwd_bwd_reject_bad_arguments_before_any_launch():
     fb = [fake] * 4 + [None, fake, None, fake, fake, fake, fake, None]
     assert lib.deltanet_fused_bwd(ctypes.byref(s), *fb, fake, 16, None) == -5
     assert lib.deltanet_fused_bwd(ctypes.byref(_shape(d_k=256, d_v=256)), *fb, fake, 16, None) == -5
-    assert lib.deltanet_gated_bwd(ctypes.byref(_shape(d_k=256, d_v=256)), *gb, fake, 1 << 40, None) == -3
+    assert lib.deltanet_gated_bwd(ctypes.byref(_shape(d_k=128, d_v=256)), *gb, fake, 1 << 40, None) == -3
     assert lib.deltanet_fused_fwd_save(ctypes.byref(s), *args, fake, fwd_only_bytes(lib, s), None) == -5
     fs = [fake] * 4 + [fake, None, fake, fake, fake, None, None]  # dbeta_logit missing
     assert lib.deltanet_fused_bwd_saved(ctypes.byref(s), *fs, fake, 1 << 40, None) == -1

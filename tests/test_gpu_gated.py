@@ -32,14 +32,14 @@ def run_gated(inp, g, bwd=True, label=""):
         assert e < tol, (label, name, e)
 
 
-@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128)])
+@pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 256, 256)])
 def test_gated_ragged_multi_chunk_with_states(dtype, dk, dv):
     inp = make_inputs(300 + dk + dv, B=2, L=200, H=3, dk=dk, dv=dv, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
     inp.initial_state *= 10.0
     run_gated(inp, make_gate(1, inp.beta.shape), label="gated %s %dx%d" % (dtype, dk, dv))
 
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 256)])
 def test_gated_strong_decay_and_packed(dtype, d):
     cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)
     inp = make_inputs(8, H=2, dk=d, dv=d, dtype=dtype, cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk_wide(SeqMap sm, int H, Ptrs p
     using SM = WideSmem<T, DK, DV>;
     constexpr int BV1 = SM::BV1, BV2 = SM::BV2, NB1 = DV / BV1, NB2 = DV / BV2;
     static_assert(DK == 32 * NWC && DV % BV1 == 0 && NB1 % 2 == 0 && NB2 % 2 == 0, "one block of 32 columns of d_k per wave");
-    constexpr int MB = 2; // operand fragments per request batch
+    constexpr int MB = 4; // operand fragments per request batch
     extern __shared__ __align__(16) unsigned char smem[];
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
     T *sX = reinterpret_cast<T *>(smem + SM::oX);

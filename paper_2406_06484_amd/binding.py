@@ -123,8 +123,11 @@ def _dt(t) -> int:
     raise TypeError("q/k/v/beta must be float32 or bfloat16, got %s" % t.dtype)
 
 
-def _shape_of(q, v, cu_seqlens, chunk, cu_host_keepalive):
+def _shape_of(q, v, cu_seqlens, chunk, cu_host_keepalive, cu_host=None):
+    """cu_host: the caller's host copy of cu_seqlens (int32), which the library validates; without one the device
+    tensor is copied back for that, except under stream capture, where no copy may run and validation is skipped."""
     import numpy as np
+    import torch
     s = dn_shape()
     if cu_seqlens is None:
         if q.dim() != 4:
@@ -140,9 +143,16 @@ def _shape_of(q, v, cu_seqlens, chunk, cu_host_keepalive):
         s.L, s.H, s.d_k = q.shape
         s.num_seqs = cu_seqlens.numel() - 1
         s.cu_seqlens = cu_seqlens.data_ptr()
-        host = np.ascontiguousarray(cu_seqlens.cpu().numpy().astype(np.int32))
+        if cu_host is not None:
+            host = np.ascontiguousarray(np.asarray(cu_host, dtype=np.int32))
+            if host.shape != (s.num_seqs + 1,):
+                raise ValueError("cu_seqlens_host must have the shape of cu_seqlens")
+        elif torch.cuda.is_current_stream_capturing():
+            host = None
+        else:
+            host = np.ascontiguousarray(cu_seqlens.cpu().numpy().astype(np.int32))
         cu_host_keepalive.append(host)
-        s.cu_seqlens_host = host.ctypes.data
+        s.cu_seqlens_host = host.ctypes.data if host is not None else None
     s.d_v = v.shape[-1]
     s.chunk = chunk
     s.dtype = _dt(q)
@@ -196,7 +206,7 @@ def _workspace(shape, want_bwd, workspace, device, gated=False, pro=False):
     return workspace, workspace.numel() * workspace.element_size()
 
 
-def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: int = 64,
+def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, cu_seqlens_host=None, chunk: int = 64,
                  output_final_state: bool = True, o=None, final_state=None, workspace=None,
                  stream=None, _g=None, _save=False, _pro=False) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
     """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None)."""
@@ -207,7 +217,7 @@ def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, chunk: i
         _req(_g, "g", torch.float32, beta.shape)
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta")):
         _req(t, n, q.dtype)
-    s = _shape_of(q, v, cu_seqlens, chunk, keep)
+    s = _shape_of(q, v, cu_seqlens, chunk, keep, cu_seqlens_host)
     _req(k, "k", shape=q.shape); _req(v, "v", shape=tuple(q.shape[:-1]) + (s.d_v,))
     _req(beta, "beta", shape=q.shape[:-1])
     N = s.num_seqs if cu_seqlens is not None else s.B
@@ -291,7 +301,7 @@ def deltanet_gated_recurrent_fwd(q, k, v, beta, g, initial_state=None, **kw):
     return deltanet_recurrent_fwd(q, k, v, beta, initial_state, _g=g, **kw)
 
 
-def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None,
+def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None, cu_seqlens_host=None,
                  chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, _g=None,
                  _saved=False, _pro=False):
     """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None)."""
@@ -302,7 +312,7 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
         _req(_g, "g", torch.float32, beta.shape)
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta"), (d_o, "d_o")):
         _req(t, n, q.dtype)
-    s = _shape_of(q, v, cu_seqlens, chunk, keep)
+    s = _shape_of(q, v, cu_seqlens, chunk, keep, cu_seqlens_host)
     _req(k, "k", shape=q.shape); _req(v, "v", shape=tuple(q.shape[:-1]) + (s.d_v,))
     _req(beta, "beta", shape=q.shape[:-1]); _req(d_o, "d_o", shape=v.shape)
     N = s.num_seqs if cu_seqlens is not None else s.B

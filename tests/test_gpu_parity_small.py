@@ -149,6 +149,33 @@ def test_head_size_256():
     run_gated(many, make_gate(6, many.beta.shape, lo=0.9, hi=1.0), label="gated bf16 256x256 330 tiles")
 
 
+def test_head_size_256_degenerate_cases():
+    # beta = 0 (the token writes nothing) and beta = 1 (full overwrite) mixed into a batch, forward and backward
+    inp = make_inputs(35, B=1, L=200, H=2, dk=256, dv=256, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
+    inp.beta[:, 0:70] = 0.0          # a whole chunk and a bit of the next one
+    inp.beta[:, 100:110] = 1.0
+    check_fwd_bwd(inp, label="bf16 256x256 beta in {0, 1}")
+    # one-hot keys and small-integer values are exact in bf16: store-and-retrieve must be exact
+    d, L = 256, 256
+    rng = np.random.default_rng(10)
+    k = np.eye(d)[rng.permutation(d)][None, :, None, :]
+    one = make_inputs(36, B=1, L=L, H=1, dk=d, dv=d, dtype="bf16")
+    one.q = k.copy(); one.k = k.copy(); one.beta[:] = 1.0
+    one.v = rng.integers(-8, 9, size=one.v.shape).astype(np.float64)
+    o, ST = gpu_fwd(one)
+    assert np.array_equal(o[0, :, 0], one.v[0, :, 0])
+    assert np.array_equal(ST[0, 0], k[0, :, 0].T @ one.v[0, :, 0])
+    # the backward pass does not depend on what the workspace held before
+    from paper_2406_06484_amd.binding import _shape_of, deltanet_workspace_bytes
+    dd = dev_inputs(inp)
+    outs = []
+    for fill in (0, 255):
+        ws = torch.full((deltanet_workspace_bytes(_shape_of(dd["q"], dd["v"], None, 64, []), True),), fill, dtype=torch.uint8, device="cuda")
+        outs.append([t.clone() for t in dn.deltanet_bwd(dd["q"], dd["k"], dd["v"], dd["beta"], dd["d_o"], dd["S0"], dd["dST"], workspace=ws)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 # (the last case cuts the forward pass only: 48 scan workgroups are too many for the backward rule)
 @pytest.mark.parametrize("dtype,d,B,H,L", [("f32", 64, 1, 2, 2048), ("bf16", 128, 1, 3, 4096), ("bf16", 64, 2, 1, 1024), ("bf16", 128, 1, 24, 2048)])
 def test_few_long_chains_take_the_segmented_scans(dtype, d, B, H, L):

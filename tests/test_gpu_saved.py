@@ -110,3 +110,9 @@ def test_saved_pair_full_size(cfg):
     # the benchmark shape, the long sequence with states at both ends, and the packed variable-length batch;
     # the self-contained pair is held to the oracle at these sizes elsewhere
     run_saved(make_config(cfg), "saved cfg%d" % cfg, check_oracle=False)
+
+
+def test_saved_pair_head_size_256_at_the_benchmark_size():
+    # the d = 256 step that bench.py times beside the headline one (same tokens, half as many heads), against the oracle
+    inp = make_inputs(28, B=8, L=2048, H=8, dk=256, dv=256, dtype="bf16")
+    run_saved(inp, "saved bf16 256x256 B=8 L=2048 H=8")

@@ -809,7 +809,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     // (head sizes with at most four such tiles give them to waves 4..7: the first four waves own the C x C tiles, and the
     // two kinds of products then run side by side instead of one after the other on the same waves)
     constexpr int TSHIFT = KT <= 4 ? 4 : 0;
-    auto kt = [&](int sI) __attribute__((always_inline)) { return ((wave + TSHIFT) & (NWC - 1)) + sI * NWC; };
+    auto kt = [&](int sI) __attribute__((always_inline)) { return TSHIFT ? ((wave + TSHIFT) & (NWC - 1)) + sI * NWC : wave + sI * NWC; };
     auto ka = [&](int sI) __attribute__((always_inline)) { return kt(sI) / (DK / 32); };
     auto kb = [&](int sI) __attribute__((always_inline)) { return kt(sI) % (DK / 32); };
     auto va = [&](int sI) __attribute__((always_inline)) { return kt(sI) / (DV / 32); };

@@ -209,7 +209,9 @@ def _workspace(shape, want_bwd, workspace, device, gated=False, pro=False):
 def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, cu_seqlens_host=None, chunk: int = 64,
                  output_final_state: bool = True, o=None, final_state=None, workspace=None,
                  stream=None, _g=None, _save=False, _pro=False) -> Tuple["torch.Tensor", Optional["torch.Tensor"]]:
-    """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None)."""
+    """Forward pass of the DeltaNet layer on the GPU; returns (o, final_state or None).  Packed batches: pass
+    cu_seqlens_host (the int32 offsets on the host) as well, or the device tensor is copied back for validation on
+    every call, which waits for the device."""
     import torch
     lib = load_library()
     keep = []
@@ -302,9 +304,12 @@ def deltanet_gated_recurrent_fwd(q, k, v, beta, g, initial_state=None, **kw):
 
 
 def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, cu_seqlens=None, cu_seqlens_host=None,
-                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, _g=None,
-                 _saved=False, _pro=False):
-    """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None)."""
+                 chunk: int = 64, want_dinitial_state: bool = True, workspace=None, stream=None, dq=None, dk=None, dv=None,
+                 dbeta=None, dinitial_state=None, dg=None, _g=None, _saved=False, _pro=False):
+    """Backward pass; returns (dq, dk, dv, dbeta[fp32], dinitial_state[fp32] or None).  dq, dk, dv, dbeta,
+    dinitial_state (and dg of the gated variant) may be passed in to be written in place; a call that is given all of
+    them and a workspace allocates nothing.  Packed batches: pass cu_seqlens_host (the int32 offsets on the host) as
+    well, or the device tensor is copied back for validation on every call, which waits for the device."""
     import torch
     lib = load_library()
     keep = []
@@ -320,9 +325,17 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
     for t, n in ((initial_state, "initial_state"), (dfinal_state, "dfinal_state")):
         if t is not None:
             _req(t, n, torch.float32, st_shape)
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    dbeta = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
-    dS0 = torch.empty(st_shape, dtype=torch.float32, device=q.device) if want_dinitial_state else None
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    dbeta = torch.empty(beta.shape, dtype=torch.float32, device=q.device) if dbeta is None else dbeta
+    dS0 = dinitial_state
+    if dS0 is None and want_dinitial_state:
+        dS0 = torch.empty(st_shape, dtype=torch.float32, device=q.device)
+    _req(dq, "dq", q.dtype, q.shape); _req(dk, "dk", q.dtype, q.shape); _req(dv, "dv", q.dtype, v.shape)
+    _req(dbeta, "dbeta", torch.float32, beta.shape)
+    if dS0 is not None:
+        _req(dS0, "dinitial_state", torch.float32, st_shape)
     if _saved and workspace is None:
         raise ValueError("saved must be the buffer returned by the matching forward call")
     workspace, wbytes = _workspace(s, True, workspace, q.device, _g is not None, _pro)
@@ -337,7 +350,8 @@ def deltanet_bwd(q, k, v, beta, d_o, initial_state=None, dfinal_state=None, *, c
                                 _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dS0), _p(workspace),
                                 wbytes, _stream(stream)))
         return dq, dk, dv, dbeta, dS0
-    dg = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
+    dg = torch.empty(beta.shape, dtype=torch.float32, device=q.device) if dg is None else dg
+    _req(dg, "dg", torch.float32, beta.shape)
     if _saved:
         _check(lib.deltanet_gated_bwd_saved(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(_g), _p(d_o),
                                             _p(dfinal_state), _p(dq), _p(dk), _p(dv), _p(dbeta), _p(dg), _p(dS0),

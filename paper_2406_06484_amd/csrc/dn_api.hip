@@ -5,6 +5,7 @@
 
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -13,7 +14,7 @@ namespace dn {
 namespace {
 struct ProfRec { std::string name; hipEvent_t a, b; };
 std::mutex g_prof_mu;
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
 std::vector<ProfRec> g_prof;
 } // namespace
 
@@ -52,13 +53,8 @@ size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 typedef int (*run_fn)(const Problem &, const Ptrs &);
 struct Impl { int dtype, dk, dv; run_fn fwd, bwd; size_t (*lds)(); };
 
-#define DN_IMPL(ENUM, T, DK, DV) { ENUM, DK, DV, &run_fwd<T, DK, DV>, &run_bwd<T, DK, DV>, &max_lds_bytes<T, DK, DV> }
-const Impl kImpls[] = {
-    DN_IMPL(DN_F32, float, 64, 64),     DN_IMPL(DN_F32, float, 32, 64),    DN_IMPL(DN_F32, float, 64, 32),
-    DN_IMPL(DN_BF16, bf16_t, 128, 128), DN_IMPL(DN_BF16, bf16_t, 64, 64),
-    DN_IMPL(DN_BF16, bf16_t, 64, 128),  DN_IMPL(DN_BF16, bf16_t, 128, 64),
-    DN_IMPL(DN_BF16, bf16_t, 256, 256), // (the chunk tiles of its backward pass are streamed: they do not fit the LDS)
-};
+#define DN_IMPL(ENUM, T, DK, DV) { ENUM, DK, DV, &run_fwd<T, DK, DV>, &run_bwd<T, DK, DV>, &max_lds_bytes<T, DK, DV> },
+const Impl kImpls[] = { DN_FOR_EACH_IMPL(DN_IMPL) };
 
 const Impl *find_impl(const dn_shape *s) {
     for (const Impl &im : kImpls)
@@ -99,7 +95,7 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bo
     pb.N = packed ? s->num_seqs : s->B;
     pb.L = s->L;
     pb.H = s->H;
-    pb.cu = s->cu_seqlens;
+    pb.cu_user = s->cu_seqlens;
     const long long per = (s->L + kChunk - 1) / kChunk;
     pb.chunks_ub = packed ? (int)(s->L / kChunk + s->num_seqs) : (int)(per * s->B);
     if (packed && s->L == 0) pb.chunks_ub = 0;
@@ -108,7 +104,8 @@ void make_plan(const dn_shape *s, int want_bwd, Plan *pl, bool gated = false, bo
     const size_t tV = up256(tiles * kChunk * s->d_v * pl->esz);
     const size_t tS = up256(tiles * (size_t)s->d_k * s->d_v * pl->esz);
     size_t o = 0;
-    pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * (2 * (size_t)pb.N + 1)) : 0; // chunk offsets, then the length order
+    // chunk offsets [N + 1], the length order [N], the bounded copy of cu_seqlens [N + 1]
+    pl->off_coff = o; o += packed ? up256(sizeof(int32_t) * (3 * (size_t)pb.N + 2)) : 0;
     const size_t tC = up256(tiles * kChunk * kChunk * pl->esz);
     pl->off_T = o; o += tC; // T of Eq. 10
     if (want_bwd) {
@@ -140,7 +137,8 @@ bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) !=
 
 void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bwd, bool gated = false, bool prologue = false) {
     unsigned char *b = static_cast<unsigned char *>(ws);
-    pb->coff = pb->cu ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
+    pb->coff = pb->cu_user ? reinterpret_cast<int32_t *>(b + pl.off_coff) : nullptr;
+    pb->cu = pb->cu_user ? pb->coff + 2 * (size_t)pb->N + 1 : nullptr;
     p->Tm = b + pl.off_T;
     p->want_x = want_bwd;
     if (want_bwd) {
@@ -164,13 +162,24 @@ void bind_workspace(const Plan &pl, void *ws, Ptrs *p, Problem *pb, bool want_bw
     }
 }
 
+// LDS capacity and CU count of a device, asked for once per device
+struct DevInfo { std::atomic<int> known{0}; int lds = 0, cus = 0; };
+DevInfo g_dev[64];
+
 int check_device(const Impl *impl, Problem *pb) {
-    int dev = 0, lds = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return DN_ERR_LAUNCH;
-    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return DN_ERR_LAUNCH;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return DN_ERR_LAUNCH;
-    pb->num_cus = cus;
-    return (size_t)lds >= impl->lds() ? DN_OK : DN_ERR_UNSUPPORTED;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DN_ERR_LAUNCH;
+    DevInfo &di = g_dev[dev];
+    if (!di.known.load(std::memory_order_acquire)) {
+        int lds = 0, cus = 0;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return DN_ERR_LAUNCH;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return DN_ERR_LAUNCH;
+        di.lds = lds; di.cus = cus; // (two threads may both write the same values)
+        di.known.store(1, std::memory_order_release);
+    }
+    pb->device = dev;
+    pb->num_cus = di.cus;
+    return (size_t)di.lds >= impl->lds() ? DN_OK : DN_ERR_UNSUPPORTED;
 }
 
 int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta, const float *g,
@@ -179,7 +188,8 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
     if (save && !impl->bwd) return DN_ERR_UNSUPPORTED;
-    if (!q || !k || !v || !beta || !o || (gated && !g)) return DN_ERR_NULL;
+    const bool no_rows = (long long)shape->B * shape->L == 0; // a tensor without rows may come with a null pointer
+    if (!no_rows && (!q || !k || !v || !beta || !o || (gated && !g))) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, workspace, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
     Plan pl;
@@ -203,7 +213,8 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl)) return rc;
     if (!impl->bwd) return DN_ERR_UNSUPPORTED;
-    if (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta || (gated && (!g || !dg))) return DN_ERR_NULL;
+    const bool no_rows = (long long)shape->B * shape->L == 0; // a tensor without rows may come with a null pointer
+    if (!no_rows && (!q || !k || !v || !beta || !d_o || !dq || !dk || !dv || !dbeta || (gated && (!g || !dg)))) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, d_o, dfinal_state, dq, dk, dv, dbeta, dg, dinitial_state,
                         workspace, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
@@ -349,7 +360,8 @@ static int recurrent_impl(const dn_shape *shape, const void *q, const void *k, c
                           void *hip_stream) {
     const Impl *impl = nullptr;
     if (int rc = validate_shape(shape, &impl, false)) return rc;
-    if (!q || !k || !v || !beta || !o || (gated && !g)) return DN_ERR_NULL;
+    const bool no_rows = (long long)shape->B * shape->L == 0; // a tensor without rows may come with a null pointer
+    if (!no_rows && (!q || !k || !v || !beta || !o || (gated && !g))) return DN_ERR_NULL;
     const void *al[] = {q, k, v, beta, g, initial_state, o, final_state, shape->cu_seqlens};
     for (const void *ptr : al) if (misaligned(ptr)) return DN_ERR_ALIGN;
     if (shape->d_v % 16 != 0) return DN_ERR_UNSUPPORTED;
@@ -377,7 +389,7 @@ int deltanet_gated_recurrent_fwd(const dn_shape *shape, const void *q, const voi
 
 int deltanet_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(dn::g_prof_mu);
-    dn::g_prof_on = on != 0;
+    dn::g_prof_on.store(on != 0);
     return DN_OK;
 }
 

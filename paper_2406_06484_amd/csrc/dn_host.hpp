@@ -9,10 +9,12 @@ namespace dn {
 struct Problem {
     int N, L, H;            // N sequences (dense: B sequences of L rows; packed: L = total rows)
     int chunks_ub;          // upper bound on the total number of chunks (grid size of per-chunk kernels)
-    const int32_t *cu;      // device cu_seqlens or nullptr
-    int32_t *coff;          // device chunk-offset prefix [N+1] inside the workspace (packed only)
+    const int32_t *cu;      // packed: the bounded copy of the caller's cu_seqlens that k_chunk_offsets writes (workspace); else nullptr
+    const int32_t *cu_user; // packed: the caller's device cu_seqlens, read by k_chunk_offsets only
+    int32_t *coff;          // device chunk-offset prefix [N+1] inside the workspace (packed only), then the length order [N]
     hipStream_t stream;
-    int num_cus;            // compute units of the current device
+    int device;             // the current device
+    int num_cus;            // its compute units
     int save;               // forward: also leave X, Ut and the chunk-initial states in the workspace;
                             // backward: find them there instead of recomputing them
 };
@@ -79,6 +81,14 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
 // largest dynamic LDS any kernel of this instantiation needs
 template <typename T, int DK, int DV> size_t max_lds_bytes();
 template <typename T, int DK, int DV> size_t max_lds_fwd_bytes(); // prep and forward scan only
+
+// The compiled (element type, d_k, d_v) instantiations: X(enum value of the C header, element type, d_k, d_v).
+// (bf16_t names __bf16 where the list is expanded; d = 256: the chunk tiles of its backward pass are streamed, they do
+// not fit the LDS)
+#define DN_FOR_EACH_IMPL(X)                                                                        \
+    X(DN_F32, float, 64, 64) X(DN_F32, float, 32, 64) X(DN_F32, float, 64, 32)                     \
+    X(DN_BF16, bf16_t, 128, 128) X(DN_BF16, bf16_t, 64, 64) X(DN_BF16, bf16_t, 64, 128)            \
+    X(DN_BF16, bf16_t, 128, 64) X(DN_BF16, bf16_t, 256, 256)
 
 // Token-serial forward (dn_recurrent.hip).  dtype: 0 = fp32, 1 = bf16.  Returns 0, a hipError_t
 // (> 0), or -1 when (dtype, d_k) has no compiled kernel.  d_v must be a multiple of 16.

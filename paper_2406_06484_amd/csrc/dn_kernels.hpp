@@ -27,12 +27,34 @@ enum { VAR_PLAIN = 0, VAR_GATED = 1, VAR_PROLOGUE = 2 };
 constexpr size_t align16(size_t x) { return (x + 15) & ~size_t(15); }
 
 // ---------------------------------------------------------------------------------------------
-// per-sequence chunk-count prefix for the packed layout: coff[n] = sum_{m<n} ceil(len_m / C); behind it, order[i] = the
-// i-th longest sequence (ties by index): the chain-serial kernels start the long chains first, so that the short
-// ones fill the tail (up to kMaxOrdered sequences; more than that balance by themselves and keep their order)
+// Packed layout, one workgroup.  The caller's offsets are first bounded: cus[n] = the running maximum of cu[0..n], held
+// inside [0, L].  For a valid array (0 = cu[0] <= cu[1] <= ... <= cu[N] = L) that is the array itself; a malformed one that
+// no host copy was there to reject becomes some non-decreasing sequence inside the tensors, so that every row index and
+// every workspace tile the other kernels derive from it stays in bounds (the results are then meaningless).  Every other
+// kernel reads cus, never cu.  Then the per-sequence chunk-count prefix coff[n] = sum_{m<n} ceil(len_m / C) and, behind
+// it, order[i] = the i-th longest sequence (ties by index): the chain-serial kernels start the long chains first, so
+// that the short ones fill the tail (up to kMaxOrdered sequences; more than that balance by themselves and keep their order).
+// Workspace: coff [N + 1], order [N], cus [N + 1].
 constexpr int kMaxOrdered = 512;
-static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) {
-    int32_t *order = coff + N + 1;
+static __global__ void k_chunk_offsets(const int32_t *cu_in, int N, int L, int32_t *coff) {
+    int32_t *order = coff + N + 1, *cu = order + N;
+    __shared__ int part[NTHR];
+    const int tid = threadIdx.x;
+    {
+        const int per1 = (N + 1 + NTHR - 1) / NTHR, lo1 = tid * per1, hi1 = min(N + 1, lo1 + per1);
+        int m = 0;
+        for (int n = lo1; n < hi1; ++n) m = max(m, min(cu_in[n], L));
+        part[tid] = m;
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int i = 0; i < NTHR; ++i) { const int t = part[i]; part[i] = run; run = max(run, t); }
+        }
+        __syncthreads();
+        int run = part[tid];
+        for (int n = lo1; n < hi1; ++n) { run = max(run, min(cu_in[n], L)); cu[n] = run; }
+        __syncthreads();
+    }
     if (N <= kMaxOrdered) {
         for (int n = threadIdx.x; n < N; n += NTHR) {
             const int len = cu[n + 1] - cu[n];
@@ -46,8 +68,6 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
     } else {
         for (int n = threadIdx.x; n < N; n += NTHR) order[n] = n;
     }
-    __shared__ int part[NTHR];
-    const int tid = threadIdx.x;
     const int per = (N + NTHR - 1) / NTHR;
     const int lo = tid * per, hi = min(N, lo + per);
     int s = 0;
@@ -62,6 +82,11 @@ static __global__ void k_chunk_offsets(const int32_t *cu, int N, int32_t *coff) 
     __syncthreads();
     int run = part[tid];
     for (int n = lo; n < hi; ++n) { coff[n] = run; run += (cu[n + 1] - cu[n] + C - 1) / C; }
+}
+
+// final_state of a pass over no tokens at all: the initial state, or zero
+static __global__ void k_state_copy(float *dst, const float *src, long count) {
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (long)gridDim.x * blockDim.x) dst[i] = src ? src[i] : 0.f;
 }
 
 // =============================================================================================

@@ -1,40 +1,59 @@
 // Launch sequences of the forward and backward pass for one (T, DK, DV); included only by the
 // instantiation files.
 #pragma once
+#include <atomic>
+#include <tuple>
+
 #include "dn_host.hpp"
 #include "dn_kernels.hpp"
 #include "dn_chunk_wide.hpp"
 
 namespace dn {
 
-template <typename K> static inline int set_lds(K kernel, size_t bytes) {
-    return (int)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+constexpr size_t kLdsPerWorkgroup = 160 * 1024; // gfx950
+
+// Raises the dynamic-LDS limit of `kernel` once per device and call site (every call site names one kernel
+// instantiation), then launches it; returns the launch's own status, so an error some earlier, unrelated call left
+// behind is neither reported as this launch's nor cleared.
+template <typename... Params, typename... Args>
+static inline int launch_kernel(void (*kernel)(Params...), std::atomic<uint64_t> &lds_set, int device, dim3 grid, int nthreads,
+                                size_t lds, hipStream_t stream, Args... args) {
+    const uint64_t bit = 1ull << (device & 63);
+    if (lds > 0 && !(lds_set.load(std::memory_order_relaxed) & bit)) { // (a call site always asks for the same amount)
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+        lds_set.fetch_or(bit, std::memory_order_relaxed);
+    }
+    std::tuple<Params...> held(static_cast<Params>(args)...); // the kernel's own parameter types, by value
+    void *ptrs[sizeof...(Params)];
+    int i = 0;
+    std::apply([&](auto &...a) { ((ptrs[i++] = (void *)&a), ...); }, held);
+    return (int)hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, dim3(nthreads), ptrs, lds, stream);
 }
 
 #define DN_LAUNCH(kernel, grid, lds, ...) DN_LAUNCH_NT(kernel, grid, NTHR, lds, __VA_ARGS__)
-#define DN_LAUNCH_NT(kernel, grid, nthreads, lds, ...)                                 \
-    do {                                                                               \
-        if (int e_ = set_lds(kernel, lds)) return e_;                                  \
-        prof_begin(#kernel, pb.stream);                                                \
-        hipLaunchKernelGGL(kernel, grid, dim3(nthreads), lds, pb.stream, __VA_ARGS__); \
-        prof_end(pb.stream);                                                           \
-        if (int e_ = (int)hipGetLastError()) return e_;                                \
+#define DN_LAUNCH_NT(kernel, grid, nthreads, lds, ...)                                                        \
+    do {                                                                                                      \
+        static std::atomic<uint64_t> lds_set_{0};                                                             \
+        prof_begin(#kernel, pb.stream);                                                                       \
+        const int e_ = launch_kernel(kernel, lds_set_, pb.device, grid, nthreads, lds, pb.stream, __VA_ARGS__); \
+        prof_end(pb.stream);                                                                                  \
+        if (e_) return e_;                                                                                    \
     } while (0)
 
 static inline SeqMap make_map(const Problem &pb) {
     SeqMap sm;
     sm.cu = pb.cu; sm.coff = pb.coff; sm.N = pb.N; sm.L = pb.L; sm.ncd = (pb.L + C - 1) / C;
     sm.order = pb.cu ? pb.coff + pb.N + 1 : nullptr;
+    // (pb.cu is the bounded copy of the caller's offsets that k_chunk_offsets leaves behind the order)
     return sm;
 }
 
 static inline int launch_offsets(const Problem &pb) {
     if (!pb.cu) return 0;
-    hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(NTHR), 0, pb.stream, pb.cu, pb.N, pb.coff);
-    return (int)hipGetLastError();
+    DN_LAUNCH(k_chunk_offsets, dim3(1), 0, pb.cu_user, pb.N, pb.L, pb.coff);
+    return 0;
 }
-
-constexpr size_t kLdsPerWorkgroup = 160 * 1024; // gfx950
 
 // Head sizes whose chunk operands do not fit the LDS at once take the streaming chunk kernel.
 template <typename T, int DK, int DV> constexpr bool kChunkFits = ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
@@ -87,7 +106,14 @@ static inline Ptrs scan_ptrs(const Ptrs &p) {
 }
 
 template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs &p) {
-    if (pb.N == 0 || pb.chunks_ub == 0) return 0;
+    if (pb.N == 0) return 0;
+    if (pb.chunks_ub == 0) { // no tokens at all: the state passes through (section 2.2: nothing is written)
+        if (p.ST) {
+            const long count = (long)pb.N * pb.H * DK * DV;
+            DN_LAUNCH(k_state_copy, dim3((unsigned)((count + 4 * NTHR - 1) / (4 * NTHR))), 0, p.ST, p.S0, count);
+        }
+        return 0;
+    }
     SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H);

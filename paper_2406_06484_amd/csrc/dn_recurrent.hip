@@ -92,7 +92,10 @@ __global__ __launch_bounds__(256) void k_recurrent_fwd(RecArgs a) {
     const int col0 = (blockIdx.y * 4 + wave) * kRecCols, col = col0 + j;
     if (col0 >= a.DV) return; // whole wave past the last column slice (no barriers below)
     int t0, len;
-    if (a.cu) { t0 = a.cu[n]; len = a.cu[n + 1] - t0; }
+    if (a.cu) { // bounded to the tensors' rows, whatever the array holds: a malformed one no host copy was there to reject stays in bounds
+        t0 = min(max(a.cu[n], 0), a.L);
+        len = min(max(a.cu[n + 1], t0), a.L) - t0;
+    }
     else { t0 = n * a.L; len = a.L; }
     const int H = a.H, DV = a.DV;
     unsigned char *buf0 = smem + wave * 2 * ST::bytes, *buf1 = buf0 + ST::bytes;
@@ -216,13 +219,14 @@ template <typename T, int DK> static int launch_rec(const RecArgs &a, hipStream_
     const dim3 grid(a.N * a.H, (a.DV + 4 * kRecCols - 1) / (4 * kRecCols));
     constexpr int lds = 4 * 2 * RecStage<T, DK>::bytes; // four waves, two buffers each
     static_assert(lds <= 160 * 1024, "staging fits the LDS");
-    if (a.g) (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_recurrent_fwd<T, DK, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    else (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_recurrent_fwd<T, DK, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    // the launch's own status (an error some earlier, unrelated call left behind is neither reported nor cleared)
+    void *args[] = {const_cast<RecArgs *>(&a)};
+    const void *fn = a.g ? reinterpret_cast<const void *>(k_recurrent_fwd<T, DK, true>) : reinterpret_cast<const void *>(k_recurrent_fwd<T, DK, false>);
+    if (const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) return (int)e;
     prof_begin("k_recurrent_fwd", stream);
-    if (a.g) hipLaunchKernelGGL((k_recurrent_fwd<T, DK, true>), grid, dim3(256), lds, stream, a);
-    else hipLaunchKernelGGL((k_recurrent_fwd<T, DK, false>), grid, dim3(256), lds, stream, a);
+    const hipError_t e = hipLaunchKernel(fn, grid, dim3(256), args, lds, stream);
     prof_end(stream);
-    return (int)hipGetLastError();
+    return (int)e;
 }
 
 // dtype: 0 = fp32, 1 = bf16.  Returns 0, a hipError_t (> 0), or -1 when (dtype, d_k) is not compiled.

@@ -6,8 +6,23 @@ import torch
 import oracle
 import paper_2406_06484_amd as dn
 
-# "max relative error" of a tensor: max_i |x_i - ref_i| / max_i |ref_i|  (normalised max error)
+# "max relative error" of a tensor: max_i |x_i - ref_i| / max_i |ref_i|  (normalised max error); this is the bound.
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# Logged beside it, so that a few large entries cannot hide errors in the rest of a tensor:
+#   rms  = ||x - ref||_2 / ||ref||_2                                              (RMS relative error; bounded)
+#   p50  = median of |x_i - ref_i| / |ref_i| over the entries with |ref_i| > 1e-3 max|ref|   (bounded)
+#   p99, emax = 99th percentile and maximum of the same element-wise relative error (logged only: an entry at the
+#          1e-3 threshold turns an absolute error of tol * max|ref| into a relative error of 1000 tol, so the tail of
+#          this distribution measures how close to zero the reference gets, not the arithmetic)
+TOL_RMS = {"f32": 1e-5, "bf16": 2e-2}
+TOL_P50 = {"f32": 1e-5, "bf16": 2e-2}
+# The gate gradient of the gated variant is a difference of row dot products (q_i . dq_i - v_i . dv_i, summed over the rest of
+# the chunk) that the bf16 kernels form from gradients already rounded to bf16: its absolute error follows the size of those
+# terms, not of their difference, so the typical entry is less accurate than the largest ones.  Its normalised max error
+# is held to the common bound; these two measures get a wider one in bf16 (observed: rms 2.8e-2, median 4.1e-2 under
+# strong decay).
+TOL_RMS_DG = {"f32": 1e-5, "bf16": 1e-1}
+TOL_P50_DG = {"f32": 1e-5, "bf16": 1e-1}
 
 
 def nerr(x, ref):
@@ -16,6 +31,43 @@ def nerr(x, ref):
     assert np.all(np.isfinite(x)), "non-finite values in GPU output"
     den = np.max(np.abs(ref)) if ref.size else 1.0
     return float(np.max(np.abs(x - ref)) / den) if den > 0 else float(np.max(np.abs(x)))
+
+
+def err_stats(x, ref):
+    """(normalised max error, RMS relative error, median, p99 and max of the element-wise relative error on |ref| > 1e-3 max|ref|)"""
+    x = np.asarray(x, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    n = nerr(x, ref)
+    if ref.size == 0:
+        return n, 0.0, 0.0, 0.0, 0.0
+    den = float(np.sqrt(np.mean(ref * ref)))
+    rms = float(np.sqrt(np.mean((x - ref) ** 2)) / den) if den > 0 else 0.0
+    big = np.abs(ref) > 1e-3 * np.max(np.abs(ref))
+    if not big.any():
+        return n, rms, 0.0, 0.0, 0.0
+    rel = np.abs(x[big] - ref[big]) / np.abs(ref[big])
+    return n, rms, float(np.median(rel)), float(np.percentile(rel, 99)), float(np.max(rel))
+
+
+def check_tensors(named, dtype, tol=None, label=""):
+    """named: iterable of (name, gpu value, oracle value).  Prints all five error measures per tensor and asserts the
+    bounds on the first three; returns {name: normalised max error}."""
+    tol = tol or TOL[dtype]
+    errs, bad = {}, {}
+    parts = []
+    for name, a, b in named:
+        n, rms, p50, p99, emax = err_stats(a, b)
+        errs[name] = n
+        parts.append("%s=%.2e(rms %.1e p50 %.1e p99 %.1e emax %.1e)" % (name, n, rms, p50, p99, emax))
+        tol_rms, tol_p50 = (TOL_RMS_DG, TOL_P50_DG) if name == "dg" else (TOL_RMS, TOL_P50)
+        if not n <= tol:
+            bad[name] = ("normalised max", n, tol)
+        elif not rms <= tol_rms[dtype]:
+            bad[name] = ("rms relative", rms, tol_rms[dtype])
+        elif not p50 <= tol_p50[dtype]:
+            bad[name] = ("median element-wise relative", p50, tol_p50[dtype])
+    print(label, " ".join(parts), flush=True)
+    assert not bad, "error above the bound: %s" % bad
+    return errs
 
 
 def to_dev(a, dtype):
@@ -51,13 +103,9 @@ def check_fwd_bwd(inp, tol=None, bwd=True, label=""):
     tol = tol or TOL[inp.dtype]
     o, ST = gpu_fwd(inp)
     o_ref, ST_ref = oracle.fwd(inp.q, inp.k, inp.v, inp.beta, inp.initial_state, inp.cu_seqlens)
-    errs = {"o": nerr(o, o_ref), "final_state": nerr(ST, ST_ref)}
+    named = [("o", o, o_ref), ("final_state", ST, ST_ref)]
     if bwd:
         g = gpu_bwd(inp)
         g_ref = oracle.bwd(inp.q, inp.k, inp.v, inp.beta, inp.d_o, inp.initial_state, inp.dfinal_state, inp.cu_seqlens)
-        for name, a, b in zip(("dq", "dk", "dv", "dbeta", "dinitial_state"), g, g_ref):
-            errs[name] = nerr(a, b)
-    print(label, " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
-    bad = {k: v for k, v in errs.items() if not v <= tol}
-    assert not bad, "normalised max error above %g: %s" % (tol, bad)
-    return errs
+        named += list(zip(("dq", "dk", "dv", "dbeta", "dinitial_state"), g, g_ref))
+    return check_tensors(named, inp.dtype, tol, label)

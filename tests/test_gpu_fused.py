@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2406_06484_amd as dn
 from paper_2406_06484_amd.synth import make_config, make_inputs, make_pre_activations
-from tests.gpu_util import TOL, dev_inputs, nerr
+from tests.gpu_util import TOL, check_tensors, dev_inputs, nerr
 
 pytestmark = pytest.mark.gpu
 
@@ -22,12 +22,7 @@ def run_fused(inp, label, check_saved=True):
     torch.cuda.synchronize()
     ref = list(oracle.fused_fwd(inp.q, inp.k, inp.v, inp.beta, inp.initial_state, inp.cu_seqlens))
     ref += list(oracle.fused_bwd(inp.q, inp.k, inp.v, inp.beta, inp.d_o, inp.initial_state, inp.dfinal_state, inp.cu_seqlens))
-    errs = {}
-    for name, a, b in zip(NAMES, [o, ST] + list(grads), ref):
-        errs[name] = nerr(a.float().cpu().numpy(), b)
-    print(label, " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
-    for name, e in errs.items():
-        assert e < TOL[inp.dtype], (label, name, e)
+    check_tensors([(name, a.float().cpu().numpy(), b) for name, a, b in zip(NAMES, [o, ST] + list(grads), ref)], inp.dtype, label=label)
     if check_saved:  # the pair that keeps the forward's tiles does the same arithmetic
         o2, ST2, saved = dn.deltanet_fused_fwd_save(d["q"], d["k"], d["v"], d["beta"], d["S0"], cu_seqlens=d["cu"])
         grads2 = dn.deltanet_fused_bwd_saved(d["q"], d["k"], d["v"], d["beta"], d["d_o"], saved, d["dST"], cu_seqlens=d["cu"])

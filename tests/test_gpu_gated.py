@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2406_06484_amd as dn
 from paper_2406_06484_amd.synth import make_gate, make_inputs
-from tests.gpu_util import TOL, dev_inputs, nerr
+from tests.gpu_util import TOL, check_tensors, dev_inputs, nerr
 
 pytestmark = pytest.mark.gpu
 
@@ -18,18 +18,14 @@ def run_gated(inp, g, bwd=True, label=""):
     o, ST = dn.deltanet_gated_fwd(d["q"], d["k"], d["v"], d["beta"], gd, d["S0"], cu_seqlens=d["cu"])
     torch.cuda.synchronize()
     o_ref, ST_ref = oracle.gated_fwd(inp.q, inp.k, inp.v, inp.beta, g, inp.initial_state, inp.cu_seqlens)
-    errs = {"o": nerr(o.float().cpu().numpy(), o_ref), "final_state": nerr(ST.cpu().numpy(), ST_ref)}
+    named = [("o", o.float().cpu().numpy(), o_ref), ("final_state", ST.cpu().numpy(), ST_ref)]
     if bwd:
         out = dn.deltanet_gated_bwd(d["q"], d["k"], d["v"], d["beta"], gd, d["d_o"], d["S0"], d["dST"], cu_seqlens=d["cu"])
         torch.cuda.synchronize()
         ref = oracle.gated_bwd(inp.q, inp.k, inp.v, inp.beta, g, inp.d_o, inp.initial_state, inp.dfinal_state, inp.cu_seqlens)
         # binding order: dq, dk, dv, dbeta, dg, dS0 -- same as the oracle's
-        for name, a, b in zip(("dq", "dk", "dv", "dbeta", "dg", "dinitial_state"), out, ref):
-            errs[name] = nerr(a.float().cpu().numpy(), b)
-    print(label, " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
-    tol = TOL[inp.dtype]
-    for name, e in errs.items():
-        assert e < tol, (label, name, e)
+        named += [(name, a.float().cpu().numpy(), b) for name, a, b in zip(("dq", "dk", "dv", "dbeta", "dg", "dinitial_state"), out, ref)]
+    check_tensors(named, inp.dtype, label=label)
 
 
 @pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 256, 256)])

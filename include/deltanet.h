@@ -81,6 +81,21 @@ int deltanet_fwd(const dn_shape *shape, const void *q, const void *k, const void
                  size_t workspace_bytes, void *hip_stream);
 
 /*
+ * deltanet_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as deltanet_fwd, minus the workspace: the
+ * scratch the pass needs is a device array of DN_STATIC_SCRATCH_BYTES that is part of the library (every GPU the
+ * library runs on holds its own copy until the process ends).  The call allocates and frees nothing.  Shapes whose
+ * deltanet_workspace_bytes(shape, 0) exceeds DN_STATIC_SCRATCH_BYTES are refused with DN_ERR_WORKSPACE before anything
+ * is enqueued (one C x C tile per chunk and head: 36 MiB covers 16 384 tokens x 16 heads in bf16, half as many in
+ * fp32).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it; calls on one stream, or otherwise ordered, do not.  Nothing in the array needs clearing
+ * between calls.
+ */
+#define DN_STATIC_SCRATCH_BYTES (36u << 20)
+int deltanet_fwd_static(const dn_shape *shape, const void *q, const void *k, const void *v, const void *beta,
+                        const float *initial_state, void *o, float *final_state, void *hip_stream);
+
+/*
  * Backward pass: exact gradient of  sum(o * d_o) + sum(final_state * dfinal_state)  with respect to
  * q, k, v, beta and initial_state.  Self-contained: chunk states are recomputed from the inputs
  * (section 3.2, "hidden states recomputed during the backward pass"), so nothing from the forward

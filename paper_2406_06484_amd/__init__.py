@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     deltanet_fused_workspace_bytes,
     deltanet_fwd,
     deltanet_fwd_save,
+    deltanet_fwd_static,
     deltanet_gated_bwd,
     deltanet_gated_bwd_saved,
     deltanet_gated_fwd,

@@ -71,6 +71,8 @@ def load_library():
         lib.deltanet_fused_bwd.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
         lib.deltanet_fused_bwd_saved.restype = ctypes.c_int
         lib.deltanet_fused_bwd_saved.argtypes = [sp] + [vp] * 11 + [vp, sz, vp]
+        lib.deltanet_fwd_static.restype = ctypes.c_int
+        lib.deltanet_fwd_static.argtypes = [sp] + [vp] * 7 + [vp]
         lib.deltanet_recurrent_fwd.restype = ctypes.c_int
         lib.deltanet_recurrent_fwd.argtypes = [sp] + [vp] * 7 + [vp]
         lib.deltanet_gated_workspace_bytes.restype = ctypes.c_int
@@ -247,6 +249,34 @@ def deltanet_fwd(q, k, v, beta, initial_state=None, *, cu_seqlens=None, cu_seqle
                   _p(final_state), _p(workspace), wbytes, _stream(stream)))
     if _save:
         return o, final_state, workspace
+    return o, final_state
+
+
+def deltanet_fwd_static(q, k, v, beta, initial_state=None, *, cu_seqlens=None, cu_seqlens_host=None, chunk: int = 64,
+                        output_final_state: bool = True, o=None, final_state=None, stream=None):
+    """deltanet_fwd on the library's own scratch array instead of a workspace (for callers that cannot allocate: pass
+    o and final_state in, and the call allocates nothing); returns (o, final_state or None)."""
+    import torch
+    lib = load_library()
+    keep = []
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (beta, "beta")):
+        _req(t, n, q.dtype)
+    s = _shape_of(q, v, cu_seqlens, chunk, keep, cu_seqlens_host)
+    _req(k, "k", shape=q.shape); _req(v, "v", shape=tuple(q.shape[:-1]) + (s.d_v,))
+    _req(beta, "beta", shape=q.shape[:-1])
+    N = s.num_seqs if cu_seqlens is not None else s.B
+    st_shape = (N, s.H, s.d_k, s.d_v)
+    if initial_state is not None:
+        _req(initial_state, "initial_state", torch.float32, st_shape)
+    if o is None:
+        o = torch.empty_like(v)
+    _req(o, "o", q.dtype, v.shape)
+    if final_state is None and output_final_state:
+        final_state = torch.empty(st_shape, dtype=torch.float32, device=q.device)
+    if final_state is not None:
+        _req(final_state, "final_state", torch.float32, st_shape)
+    _check(lib.deltanet_fwd_static(ctypes.byref(s), _p(q), _p(k), _p(v), _p(beta), _p(initial_state), _p(o), _p(final_state),
+                                   _stream(stream)))
     return o, final_state
 
 

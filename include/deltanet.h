@@ -232,6 +232,18 @@ typedef struct {
 int deltanet_profile_enable(int on);
 int deltanet_profile_collect(dn_kernel_time *out, int max_entries, int *num_entries);
 
+/*
+ * Process-wide options (each 0 by default).
+ *  DN_OPT_STREAMED_CHUNK_KERNEL: the backward pass of the plain delta rule in bf16 (head sizes up to 128) takes the chunk
+ *    kernel that reads the chunk states in blocks of 32 state columns and rebuilds U - W S of Eq. 8 and its gradient on
+ *    chip instead of reading them back from the scans, which then do not store them: 13 % fewer bytes through HBM per
+ *    training step, and on MI355X a slower step (the blocks take more barrier intervals than they save in traffic).
+ *    Same results to within rounding.  deltanet_fwd_save and the deltanet_bwd_saved that follows it must run under the
+ *    same setting.  Unknown options return DN_ERR_UNSUPPORTED.
+ */
+typedef enum { DN_OPT_STREAMED_CHUNK_KERNEL = 0 } dn_option;
+int deltanet_set_option(int option, int value);
+
 /* Static, NUL-terminated description of a dn_status value. */
 const char *deltanet_status_string(int status);
 

@@ -5,6 +5,7 @@
 library has not been built, calling them raises.
 """
 from .binding import (  # noqa: F401
+    DN_OPT_STREAMED_CHUNK_KERNEL,
     DeltaNetError,
     deltanet_bwd,
     deltanet_bwd_saved,
@@ -24,6 +25,7 @@ from .binding import (  # noqa: F401
     deltanet_gated_workspace_bytes,
     deltanet_profile_collect,
     deltanet_recurrent_fwd,
+    deltanet_set_option,
     deltanet_profile_enable,
     deltanet_status_string,
     deltanet_workspace_bytes,

@@ -85,6 +85,8 @@ def load_library():
         lib.deltanet_gated_bwd.argtypes = [sp] + [vp] * 14 + [vp, sz, vp]
         lib.deltanet_gated_recurrent_fwd.restype = ctypes.c_int
         lib.deltanet_gated_recurrent_fwd.argtypes = [sp] + [vp] * 8 + [vp]
+        lib.deltanet_set_option.restype = ctypes.c_int
+        lib.deltanet_set_option.argtypes = [ctypes.c_int, ctypes.c_int]
         lib.deltanet_profile_enable.restype = ctypes.c_int
         lib.deltanet_profile_enable.argtypes = [ctypes.c_int]
         lib.deltanet_profile_collect.restype = ctypes.c_int
@@ -97,6 +99,14 @@ def load_library():
 
 def deltanet_status_string(status: int) -> str:
     return load_library().deltanet_status_string(int(status)).decode()
+
+
+DN_OPT_STREAMED_CHUNK_KERNEL = 0
+
+
+def deltanet_set_option(option: int, value: int) -> None:
+    """Process-wide option of the library (see include/deltanet.h)."""
+    _check(load_library().deltanet_set_option(int(option), int(value)))
 
 
 def deltanet_profile_enable(on: bool) -> None:

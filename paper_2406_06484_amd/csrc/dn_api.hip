@@ -13,6 +13,7 @@
 namespace dn {
 namespace {
 struct ProfRec { std::string name; hipEvent_t a, b; };
+std::atomic<int> g_opt_streamed{0}; // DN_OPT_STREAMED_CHUNK_KERNEL
 std::mutex g_prof_mu;
 std::atomic<bool> g_prof_on{false};
 std::vector<ProfRec> g_prof;
@@ -202,6 +203,7 @@ int fwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     pl.pb.save = save;
     p.pro = prologue;
+    p.streamed = dn::g_opt_streamed.load(std::memory_order_relaxed);
     bind_workspace(pl, workspace, &p, &pl.pb, save, gated, prologue);
     return impl->fwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
@@ -229,6 +231,7 @@ int bwd_impl(const dn_shape *shape, const void *q, const void *k, const void *v,
     pl.pb.stream = static_cast<hipStream_t>(hip_stream);
     pl.pb.save = saved;
     p.pro = prologue;
+    p.streamed = dn::g_opt_streamed.load(std::memory_order_relaxed);
     bind_workspace(pl, workspace, &p, &pl.pb, true, gated, prologue);
     return impl->bwd(pl.pb, p) == 0 ? DN_OK : DN_ERR_LAUNCH;
 }
@@ -385,6 +388,12 @@ int deltanet_gated_recurrent_fwd(const dn_shape *shape, const void *q, const voi
                                  const float *g, const float *initial_state, void *o, float *final_state,
                                  void *hip_stream) {
     return recurrent_impl(shape, q, k, v, beta, g, true, initial_state, o, final_state, hip_stream);
+}
+
+int deltanet_set_option(int option, int value) {
+    if (option != DN_OPT_STREAMED_CHUNK_KERNEL) return DN_ERR_UNSUPPORTED;
+    dn::g_opt_streamed.store(value != 0, std::memory_order_relaxed);
+    return DN_OK;
 }
 
 int deltanet_profile_enable(int on) {

@@ -90,15 +90,18 @@ struct SeqMap {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-__device__ inline bf16x8 frag_kc(const bf16 *base, int ld, int k0) {
-    const int lane = threadIdx.x & 63;
+// (`tx`: the thread index as the caller wants it seen.  The default is threadIdx.x itself; a kernel that wants the per-lane
+// address arithmetic formed where it is used, rather than hoisted out of its outer loop and carried through it, passes a
+// copy it has taken through an empty asm.)
+__device__ inline bf16x8 frag_kc(const bf16 *base, int ld, int k0, int tx = threadIdx.x) {
+    const int lane = tx & 63;
     return *reinterpret_cast<const bf16x8 *>(base + (lane & 31) * ld + k0 + 8 * (lane >> 5));
 }
-__device__ inline bf16x8 frag_ks(const bf16 *base, int ld, int k0) {
+__device__ inline bf16x8 frag_ks(const bf16 *base, int ld, int k0, int tx = threadIdx.x) {
     // Within each group of 16 lanes the transposing read hands lane i the 16-bit element (i & 3) of
     // the four 8-byte rows addressed by lanes (i >> 2), (i >> 2) + 4, + 8, + 12.  With lane i
     // pointing at row k0' + (i >> 2), columns 4*(i & 3).., lane i ends up with column i, rows k0'..k0'+3.
-    const int lane = threadIdx.x & 63, i = lane & 15;
+    const int lane = tx & 63, i = lane & 15;
     const bf16 *p = base + (k0 + 8 * (lane >> 5) + (i >> 2)) * ld + (lane & 16) + 4 * (i & 3);
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
@@ -106,12 +109,12 @@ __device__ inline bf16x8 frag_ks(const bf16 *base, int ld, int k0) {
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
-__device__ inline float frag_kc(const float *base, int ld, int k0) {
-    const int lane = threadIdx.x & 63;
+__device__ inline float frag_kc(const float *base, int ld, int k0, int tx = threadIdx.x) {
+    const int lane = tx & 63;
     return base[(lane & 31) * ld + k0 + (lane >> 5)];
 }
-__device__ inline float frag_ks(const float *base, int ld, int k0) {
-    const int lane = threadIdx.x & 63;
+__device__ inline float frag_ks(const float *base, int ld, int k0, int tx = threadIdx.x) {
+    const int lane = tx & 63;
     return base[(k0 + (lane >> 5)) * ld + (lane & 31)];
 }
 __device__ inline void mfma32(f32x16 &acc, bf16x8 a, bf16x8 b) { acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0); }
@@ -131,7 +134,7 @@ template <typename T> struct MmaBatch;
 template <> struct MmaBatch<bf16> { static constexpr int value = 8; };   // 8 steps x 2 operands x 4 VGPRs
 template <> struct MmaBatch<float> { static constexpr int value = 16; }; // 16 steps x 2 operands x 1 VGPR
 template <int KDIM, bool AKS, bool BKS, typename T, bool FENCE = true, int BATCH_ = 0>
-__device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb) {
+__device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb, int tx = threadIdx.x) {
     constexpr int KS = KStep<T>::value, N = KDIM / KS;
     constexpr int WANT = BATCH_ ? BATCH_ : MmaBatch<T>::value;
     constexpr int BATCH = N < WANT ? N : WANT, NB = (N + BATCH - 1) / BATCH;
@@ -140,8 +143,8 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
     frag_t a[2][BATCH], b[2][BATCH];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-        a[0][j] = AKS ? frag_ks(A, lda, j * KS) : frag_kc(A, lda, j * KS);
-        b[0][j] = BKS ? frag_ks(B, ldb, j * KS) : frag_kc(B, ldb, j * KS);
+        a[0][j] = AKS ? frag_ks(A, lda, j * KS, tx) : frag_kc(A, lda, j * KS, tx);
+        b[0][j] = BKS ? frag_ks(B, ldb, j * KS, tx) : frag_kc(B, ldb, j * KS, tx);
     }
 #pragma unroll
     for (int ib = 0; ib < NB; ++ib) {
@@ -149,8 +152,8 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 const int k0 = ((ib + 1) * BATCH + j) * KS;
-                a[(ib + 1) & 1][j] = AKS ? frag_ks(A, lda, k0) : frag_kc(A, lda, k0);
-                b[(ib + 1) & 1][j] = BKS ? frag_ks(B, ldb, k0) : frag_kc(B, ldb, k0);
+                a[(ib + 1) & 1][j] = AKS ? frag_ks(A, lda, k0, tx) : frag_kc(A, lda, k0, tx);
+                b[(ib + 1) & 1][j] = BKS ? frag_ks(B, ldb, k0, tx) : frag_kc(B, ldb, k0, tx);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -170,8 +173,8 @@ __device__ inline f32x16 zero16() {
 }
 
 // visit every accumulator element: f(row, col, value&) with row, col inside the 32x32 tile
-template <typename F> __device__ inline void acc_each(f32x16 &acc, F f) {
-    const int lane = threadIdx.x & 63, col = lane & 31, h = lane >> 5;
+template <typename F> __device__ inline void acc_each(f32x16 &acc, F f, int tx = threadIdx.x) {
+    const int lane = tx & 63, col = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -182,8 +185,8 @@ template <typename F> __device__ inline void acc_each(f32x16 &acc, F f) {
         }
 }
 // visit runs of 4 consecutive rows: f(row0, col, v0, v1, v2, v3)
-template <typename F> __device__ inline void acc_each4(const f32x16 &acc, F f) {
-    const int lane = threadIdx.x & 63, col = lane & 31, h = lane >> 5;
+template <typename F> __device__ inline void acc_each4(const f32x16 &acc, F f, int tx = threadIdx.x) {
+    const int lane = tx & 63, col = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int g = 0; g < 4; ++g) f(8 * g + 4 * h, col, acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
 }
@@ -196,14 +199,14 @@ __device__ inline void st4(bf16 *p, float a, float b, float c, float d) {
 }
 
 // tile (32x32) of the accumulator -> LDS, row-major destination dst[row][col]
-template <typename T> __device__ inline void acc_to_lds(T *dst, int ld, int row0, int col0, f32x16 &acc) {
-    acc_each(acc, [&](int r, int c, float &v) { dst[(row0 + r) * ld + col0 + c] = from_f32<T>(v); });
+template <typename T> __device__ inline void acc_to_lds(T *dst, int ld, int row0, int col0, f32x16 &acc, int tx = threadIdx.x) {
+    acc_each(acc, [&](int r, int c, float &v) { dst[(row0 + r) * ld + col0 + c] = from_f32<T>(v); }, tx);
 }
 // ... and transposed: dstT[col][row], 4 consecutive rows per store
-template <typename T> __device__ inline void acc_to_lds_t(T *dstT, int ldT, int row0, int col0, const f32x16 &acc) {
+template <typename T> __device__ inline void acc_to_lds_t(T *dstT, int ldT, int row0, int col0, const f32x16 &acc, int tx = threadIdx.x) {
     acc_each4(acc, [&](int r, int c, float a, float b, float cc, float d) {
         st4(dstT + (col0 + c) * ldT + row0 + r, a, b, cc, d);
-    });
+    }, tx);
 }
 // Wave-private LDS staging for coalesced tile stores.  A 32 x 32 accumulator tile is first laid
 // out row-major in LDS (cheap narrow LDS writes), then each lane moves 16 bytes at a time to global
@@ -217,8 +220,8 @@ template <typename T> struct Stage {
 __device__ inline void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 template <typename T>
-__device__ inline void stage_flush(const T *stage, T *dst, long row_stride, int row0, int col0, int nvalid) {
-    const int lane = threadIdx.x & 63;
+__device__ inline void stage_flush(const T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, int tx = threadIdx.x) {
+    const int lane = tx & 63;
     wave_lds_fence();
 #pragma unroll
     for (int it = 0; it < 32 * Stage<T>::SEGS / 64; ++it) {
@@ -257,9 +260,9 @@ __device__ inline void stage_flush_dot(const T *stage, T *dst, long row_stride, 
 }
 // dst[row0 + r][col0 + c] = acc(r, c), rows >= nvalid dropped; `stage` is this wave's staging tile
 template <typename T>
-__device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc) {
-    acc_to_lds<T>(stage, Stage<T>::LD, 0, 0, acc);
-    stage_flush<T>(stage, dst, row_stride, row0, col0, nvalid);
+__device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc, int tx = threadIdx.x) {
+    acc_to_lds<T>(stage, Stage<T>::LD, 0, 0, acc, tx);
+    stage_flush<T>(stage, dst, row_stride, row0, col0, nvalid, tx);
 }
 // ---------------------------------------------------------------------------------------------
 // A ROWS x COLS tile fetched from global memory into registers (16 bytes per lane and step; rows >=

@@ -44,6 +44,8 @@ struct Ptrs {
     // ... and of the backward pass: per segment the gradient the reverse scan produces from zero, and the gradient
     // with respect to the segment's end state
     float *Rseg, *dSout;
+    int streamed;   // option: the backward pass takes the chunk kernel that streams S and dS' and rebuilds Ut, dUt (k_bwd_stream)
+    int skip_ut;    // that kernel will run: the scans do not write Ut and dUt
     int unit_state; // set inside k_scan_state for its transition-matrix pass
 };
 

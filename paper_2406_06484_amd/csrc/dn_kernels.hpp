@@ -367,7 +367,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             // the tiles kept for the backward pass leave in this interval, in which the loader waves have no product
             // of their own: the chunk-initial state (transposed, as it sits in LDS) and the previous chunk's Ut^T
             copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
-            if (ic > 0) copy_out<T, BV, C, NTL>((T *)p.Ut + ((tile - H) * DV + vb) * C, ((ic - 1) & 1) ? sUT1 : sUT0, SM::LT, lt);
+            if (ic > 0 && !p.skip_ut) copy_out<T, BV, C, NTL>((T *)p.Ut + ((tile - H) * DV + vb) * C, ((ic - 1) & 1) ? sUT1 : sUT0, SM::LT, lt);
         }
         f32x16 acc = zero16();
         if (!loader) {
@@ -422,7 +422,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         lds_barrier();
-        if (MODE == SCAN_STORE && loader && ic > 0) flush_ut(ic - 1);
+        if (MODE == SCAN_STORE && loader && ic > 0 && !p.skip_ut) flush_ut(ic - 1);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T, true, MB>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T, true, MB>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -437,7 +437,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (loader && ic + 1 < nchunks) stash();
     }
     if (loader && nchunks > 0) {
-        if (SAVE) flush_ut(nchunks - 1);
+        if (SAVE && !p.skip_ut) flush_ut(nchunks - 1);
         if (OUT) flush_out(nchunks - 1);
     }
     if ((OUT || MODE == SCAN_STATE) && p.ST && m.has_s) {
@@ -705,7 +705,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         }
         if (m.has_s) mma<C, true, true, T, true, MB>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         lds_barrier();
-        if (!STATE && loader && ic + 1 < nchunks) flush_dut(ic + 1);
+        if (!STATE && loader && ic + 1 < nchunks && !p.skip_ut) flush_dut(ic + 1);
         if (m.has_s) { // - W^T dUt
             f32x16 wd = zero16();
             mma<C, true, false, T, true, MB>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
@@ -714,7 +714,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader && ic > 0) stash(); // see k_scan_fwd
     }
-    if (!STATE && loader && nchunks > 0) flush_dut(0);
+    if (!STATE && loader && nchunks > 0 && !p.skip_ut) flush_dut(0);
     if (p.dS0 && m.has_s) {
         float *dst = p.dS0 + (long)chain * DK * DV + vb;
         acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
@@ -826,7 +826,12 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
     constexpr int MB = PRO ? 2 : (sizeof(T) == 4 ? 2 : ((DK > 128 || GATED) ? 4 : 0));
-    const int tid = threadIdx.x, lane = tid & 63;
+    // The thread index as the helpers see it: re-read through an empty asm at the top of every barrier interval, so that the
+    // per-lane offsets and masks derived from it are formed where they are used.  Left to itself the compiler forms all of
+    // them ahead of the tile loop and carries them through it, which costs more registers than the kernel has to spare.
+    int tq = threadIdx.x;
+    auto fresh = [&]() __attribute__((always_inline)) { tq = threadIdx.x; asm volatile("" : "+v"(tq)); };
+    const int tid = threadIdx.x;
     // The wave number, and with it every tile offset derived from it, is recomputed per tile in the variants
     // that are short of registers: hoisted out of the tile loop, those offsets alone would take some 90 VGPRs.
     int wave = tid >> 6;
@@ -850,29 +855,31 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         // gated: gamma of this lane's dO rows, 1 / gamma of its V rows; entry tid of the chunk's table of gamma_i, 1 / gamma_i
         float dos[TileRegs<T, C, DV, NTC>::NIT], vsc[TileRegs<T, C, DV, NTC>::NIT], gm;
     } r;
-    // The first four tiles of a chunk are requested separately: where registers allow (the plain variant),
-    // the next chunk's are already on their way while this chunk's last products run.
+    // Every tile of a chunk waits in registers from the moment it is requested.  As soon as one has moved to LDS, the same
+    // registers request that tile of the workgroup's next chunk (where there is none, of the current one again: no
+    // branch around a request, so the compiler knows how many are in flight and waits for exactly the one it needs), so
+    // about one chunk's worth of loads is in flight at any time.  The prologue variant keeps the pre-activations of k in
+    // registers to the end of the chunk; it requests the next chunk only then.
     auto fetch_early = [&](const TilePos &tp) __attribute__((always_inline)) {
-        if (!tp.ok) return;
-        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
-        r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV);
-        r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV);
-        r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV);
+        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid, tq);
+        r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV, tq);
+        r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV, tq);
+        r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV, tq);
         if (gated) r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
     };
-    auto fetch = [&](const TilePos &tp) __attribute__((always_inline)) {
-        if (!tp.ok) return;
-        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
-        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid);
-        if (tid < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tid, tp.nvalid - 1)) * H + tp.h];
-        r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV);
-        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid);
-        r.x.load((const T *)p.Xm + tp.tile * C * C, C, C);
-        if (gated) {
-            r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
-            if (tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
-        }
+    auto fetch_kq = [&](const TilePos &tp) __attribute__((always_inline)) {
+        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid, tq);
+        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid, tq);
+        if (tq < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tq, tp.nvalid - 1)) * H + tp.h];
+        if (gated && tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
     };
+    auto fetch_ds = [&](const TilePos &tp) __attribute__((always_inline)) { r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV, tq); };
+    auto fetch_v = [&](const TilePos &tp) __attribute__((always_inline)) {
+        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid, tq);
+        if (gated) r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
+    };
+    auto fetch_x = [&](const TilePos &tp) __attribute__((always_inline)) { r.x.load((const T *)p.Xm + tp.tile * C * C, C, C, tq); };
+    auto fetch_all = [&](const TilePos &tp) __attribute__((always_inline)) { fetch_early(tp); fetch_kq(tp); fetch_ds(tp); fetch_v(tp); fetch_x(tp); };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
 
     // Workgroups that start together stay in lockstep: every CU issues its tile's load burst at the same
@@ -883,16 +890,18 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     if ((long)chunks_total * H >= 4l * gridDim.x)
         for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(64);
     constexpr bool AHEAD = VAR != VAR_PROLOGUE;
-    bool ahead = false; // this chunk's first four tiles were requested during the previous chunk
-    for (TileIter it(chunks_total, H); it.valid(); it.next()) {
-        const TilePos cur = pos_of(it);
-        if (!cur.ok) continue; // packed layout: past the last real chunk (so is every later one)
+    TileIter it(chunks_total, H);
+    TilePos cur = pos_of(it);
+    if (cur.ok) fetch_all(cur);
+    while (cur.ok) { // packed layout: the first chunk past the last real one ends the walk (so would every later one)
+        TileIter nx = it;
+        nx.next();
+        const TilePos np = pos_of(nx);
+        const TilePos nf = np.ok ? np : cur; // what the freed registers request
         asm volatile("" : "+v"(wave)); // opaque: see above
         const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
         const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
         T *stg = reinterpret_cast<T *>(smem + SM::oStage) + wave * Stage<T>::ELEMS;
-        if (!ahead) fetch_early(cur);
-        fetch(cur);
         const int nvalid = cur.nvalid, h = cur.h;
         const long row0 = cur.row0;
         // ---- adjoint of Eq. 8-9
@@ -901,8 +910,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         // zp: this thread's share of <dS_C, S_C> = <dS~', S_0> + <K, Ut dS~'^T>, for the gate gradient
         float zp = 0.f;
         if (gated) r.d_o.scale_rows(r.dos);
-        r.d_o.store(sDO, SM::LV); r.ut.store(sUt, SM::LU); r.s.store(sS, SM::LSK);
-        r.dut.store(sDU, SM::LU);
+        r.d_o.store(sDO, SM::LV, tq); r.ut.store(sUt, SM::LU, tq); r.s.store(sS, SM::LSK, tq);
+        r.dut.store(sDU, SM::LU, tq);
+        if (AHEAD) fetch_early(nf);
         // prologue variant: the feature map of section 3.3 on the way to LDS; the pre-activations stay in
         // r.q / r.k and the norms in qinv / kinv for the way back
         float qinv[TileRegs<T, C, DK, NTC>::NIT], kinv[TileRegs<T, C, DK, NTC>::NIT];
@@ -910,136 +920,133 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             r.k.feature_map_to(sK, SM::LK, kinv);
             r.q.feature_map_to(sQ, SM::LK, qinv);
         } else {
-            r.k.store(sK, SM::LK); r.q.store(sQ, SM::LK);
+            r.k.store(sK, SM::LK, tq); r.q.store(sQ, SM::LK, tq);
         }
-        if (tid < C) {
-            float b = tid < nvalid ? to_f32(r.beta) : 0.f;
-            if (PRO) b = tid < nvalid ? sigmoid_f32(b) : 0.f; // beta = sigmoid(logit), section 2.2
-            sBeta[tid] = b;
+        if (tq < C) {
+            float b = tq < nvalid ? to_f32(r.beta) : 0.f;
+            if (PRO) b = tq < nvalid ? sigmoid_f32(b) : 0.f; // beta = sigmoid(logit), section 2.2
+            sBeta[tq] = b;
         }
         if (gated && tid < 2 * C) sGam[tid] = r.gm;
-        lds_barrier();
+        if (AHEAD) fetch_kq(nf);
+        lds_barrier(); fresh();
         if (cc) { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
-            if (!upper) mma<DV, false, true, T, true, MB>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni, SM::LU);
-            acc_each(acc, [&](int rr, int c, float &val) { if (32 * ni + c > 32 * mi + rr) val = 0.f; });
-            acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc);
+            if (!upper) mma<DV, false, true, T, true, MB>(acc, sDO + 32 * mi * SM::LV, SM::LV, sUt + 32 * ni, SM::LU, tq);
+            acc_each(acc, [&](int rr, int c, float &val) { if (32 * ni + c > 32 * mi + rr) val = 0.f; }, tq);
+            acc_to_lds<T>(sDP, SM::LT, 32 * mi, 32 * ni, acc, tq);
         }
         f32x16 dq[KW], dw[KW], dk1[KW];
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) {
             dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
             if (kt(sI) < KT) {
-                mma<DV, false, true, T, true, MB>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI), SM::LSK); // dO S^T
-                mma<DV, true, true, T, true, MB>(dw[sI], sDU + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);           // dUt S^T
+                mma<DV, false, true, T, true, MB>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI), SM::LSK, tq); // dO S^T
+                mma<DV, true, true, T, true, MB>(dw[sI], sDU + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK, tq);           // dUt S^T
             }
         }
-        lds_barrier(); // dP visible; S is dead
+        lds_barrier(); fresh(); // dP visible; S is dead
         if (gated) zp = r.ds.dot_lds(sS, SM::LSK); // <dS~', S_0>: each thread meets the S values it parked there itself
-        r.ds.store(sS, SM::LSK);
+        r.ds.store(sS, SM::LSK, tq);
+        if (AHEAD) fetch_ds(nf);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dQ += dP K
-            if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK);
-            else mma<C, false, true, T, true, MB>(dq[sI], sDP + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
+            if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
+            else mma<C, false, true, T, true, MB>(dq[sI], sDP + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
             if (gated) { // also q_i . dq_i over this tile's columns, for the gate gradient
-                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI]);
+                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, dq[sI], tq);
                 stage_flush_dot<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, sQ, SM::LK,
                                    sCq + kb(sI) * C);
             } else if (PRO) { // dO's bytes are free: dq is assembled there for the way back through the map
-                acc_to_lds<T>(sDQ, SM::LQO, 32 * ka(sI), 32 * kb(sI), dq[sI]);
+                acc_to_lds<T>(sDQ, SM::LQO, 32 * ka(sI), 32 * kb(sI), dq[sI], tq);
             } else {
-                acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI]);
+                acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI], tq);
             }
         }
-        lds_barrier();
+        lds_barrier(); fresh();
         if (PRO) // gradient through the feature map: dq~ = SiLU'(q~) (dq - q (q . dq)) / ||SiLU(q~)||
             r.q.feature_map_bwd_store(sDQ, SM::LQO, qinv, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, nvalid);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
             if (gated) { // <K, Ut dS~'^T>, the second half of <dS_C, S_C>, taken while dK1 holds just that product
-                mma<DV, true, true, T, true, MB>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
-                acc_each(dk1[sI], [&](int rr, int c, float &val) { zp += val * to_f32(sK[(32 * ka(sI) + rr) * SM::LK + 32 * kb(sI) + c]); });
+                mma<DV, true, true, T, true, MB>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK, tq);
+                acc_each(dk1[sI], [&](int rr, int c, float &val) { zp += val * to_f32(sK[(32 * ka(sI) + rr) * SM::LK + 32 * kb(sI) + c]); }, tq);
             }
-            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK);
-            else mma<C, true, true, T, true, MB>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK);
-            if (!gated) mma<DV, true, true, T, true, MB>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK);
+            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDP + 32 * SM::LT + 32, SM::LT, sQ + 32 * SM::LK + 32 * kb(sI), SM::LK, tq);
+            else mma<C, true, true, T, true, MB>(dk1[sI], sDP, SM::LT, sQ + 32 * kb(sI), SM::LK, tq);
+            if (!gated) mma<DV, true, true, T, true, MB>(dk1[sI], sUt + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK, tq);
         }
-        lds_barrier(); // dO, Ut, Q, dP, dS' are dead
+        lds_barrier(); fresh(); // dO, Ut, Q, dP, dS' are dead
         // ---- adjoint of Eq. 10-11
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dW = -dUt S^T, as an operand
-            acc_each(dw[sI], [&](int, int, float &val) { val = -val; });
-            acc_to_lds<T>(sDW, SM::LK, 32 * ka(sI), 32 * kb(sI), dw[sI]);
+            acc_each(dw[sI], [&](int, int, float &val) { val = -val; }, tq);
+            acc_to_lds<T>(sDW, SM::LK, 32 * ka(sI), 32 * kb(sI), dw[sI], tq);
         }
         if (gated) r.v.scale_rows(r.vsc);
-        r.v.store(sV, SM::LV);
-        lds_barrier();
+        r.v.store(sV, SM::LV, tq);
+        if (AHEAD) fetch_v(nf);
+        lds_barrier(); fresh();
         f32x16 g = zero16(), dxp = zero16();
         if (cc && !upper) {
-            mma<DK, false, false, T, true, MB>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-            mma<DK, false, false, T, true, MB>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK);
-            mma<DV, true, false, T, true, MB>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV);
+            mma<DK, false, false, T, true, MB>(g, sK + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK, tq);
+            mma<DK, false, false, T, true, MB>(dxp, sDW + 32 * mi * SM::LK, SM::LK, sK + 32 * ni * SM::LK, SM::LK, tq);
+            mma<DV, true, false, T, true, MB>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV, tq);
         }
-        acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }); // strictly lower G
-        lds_barrier(); // V and dS' are dead
-        r.x.store(sXn, SM::LT);
-        lds_barrier();
+        acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }, tq); // strictly lower G
+        lds_barrier(); fresh(); // V and dS' are dead
+        r.x.store(sXn, SM::LT, tq);
+        if (AHEAD) fetch_x(nf);
+        lds_barrier(); fresh();
         if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
             float part = 0.f;
             acc_each(dxp, [&](int rr, int c, float &val) {
                 const int i = 32 * mi + rr, j = 32 * ni + c;
                 part += to_f32(sXn[i * SM::LT + j]) * val;
                 val *= sBeta[j];
-            });
-            sDb[(2 * mi + (lane >> 5)) * C + 32 * ni + (lane & 31)] = part; // summed in a fixed order at the end
-            acc_to_lds<T>(sDX, SM::LT, 32 * mi, 32 * ni, dxp);
+            }, tq);
+            sDb[(2 * mi + ((tq & 63) >> 5)) * C + 32 * ni + (tq & 31)] = part; // summed in a fixed order at the end
+            acc_to_lds<T>(sDX, SM::LT, 32 * mi, 32 * ni, dxp, tq);
         }
-        lds_barrier();
+        lds_barrier(); fresh();
         f32x16 m1 = zero16(); // M1 = dX X^T
-        if (cc) mma<C, false, false, T, true, MB>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT);
+        if (cc) mma<C, false, false, T, true, MB>(m1, sDX + 32 * mi * SM::LT, SM::LT, sXn + 32 * ni * SM::LT, SM::LT, tq);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dKb = X^T dW (X^T is upper triangular)
             f32x16 dKb = zero16();
-            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb(sI), SM::LK);
-            else mma<C, true, true, T, true, MB>(dKb, sXn, SM::LT, sDW + 32 * kb(sI), SM::LK);
-            acc_each(dKb, [&](int rr, int, float &val) { val *= sBeta[32 * ka(sI) + rr]; });
+            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dKb, sXn + 32 * SM::LT + 32, SM::LT, sDW + 32 * SM::LK + 32 * kb(sI), SM::LK, tq);
+            else mma<C, true, true, T, true, MB>(dKb, sXn, SM::LT, sDW + 32 * kb(sI), SM::LK, tq);
+            acc_each(dKb, [&](int rr, int, float &val) { val *= sBeta[32 * ka(sI) + rr]; }, tq);
             dk1[sI] += dKb; // dK1 + diag(beta) dKb
         }
 #pragma unroll
         for (int sI = 0; sI < VW; ++sI) if (kt(sI) < VT) { // dV = diag(beta) X^T dU
             f32x16 acc = zero16();
-            if (va(sI) == 1) mma<32, true, false, T, true, MB>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * vbk(sI) * SM::LU + 32, SM::LU);
-            else mma<C, true, false, T, true, MB>(acc, sXn, SM::LT, sDU + 32 * vbk(sI) * SM::LU, SM::LU);
+            if (va(sI) == 1) mma<32, true, false, T, true, MB>(acc, sXn + 32 * SM::LT + 32, SM::LT, sDU + 32 * vbk(sI) * SM::LU + 32, SM::LU, tq);
+            else mma<C, true, false, T, true, MB>(acc, sXn, SM::LT, sDU + 32 * vbk(sI) * SM::LU, SM::LU, tq);
             acc_each(acc, [&](int rr, int, float &val) {
                 val *= gated ? sBeta[32 * va(sI) + rr] * sGi[32 * va(sI) + rr] : sBeta[32 * va(sI) + rr];
-            });
+            }, tq);
             if (gated) { // also (v_i / gamma_i) . dv_i over this tile's columns
-                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc);
+                acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc, tq);
                 stage_flush_dot<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, sV, SM::LV,
                                    sCv + vbk(sI) * C);
             } else {
-                acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc);
+                acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc, tq);
             }
         }
-        if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1); // Q's bytes: dead since dK1 (the inverse scratch, too)
-        lds_barrier(); // dX is dead
+        if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1, tq); // Q's bytes: dead since dK1 (the inverse scratch, too)
+        lds_barrier(); fresh(); // dX is dead
         // prologue variant: the pre-activations of k are needed once more at the very end; they are requested again here
         // rather than kept in registers through the products above
-        if (PRO) r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
-        if (AHEAD) { // d_o, Ut^T, S^T, dUt^T of the next chunk: their registers have been free since this chunk's first barrier
-            TileIter nx = it;
-            nx.next();
-            const TilePos np = pos_of(nx);
-            ahead = np.ok;
-            fetch_early(np);
-        }
+        if (PRO) r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, tq);
         if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {
-                if (mi == 1) mma<32, true, false, T, true, MB>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT);
-                else mma<C, true, false, T, true, MB>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT);
+                if (mi == 1) mma<32, true, false, T, true, MB>(acc, sXn + 32 * SM::LT + 32, SM::LT, sM1T + 32 * ni * SM::LT + 32, SM::LT, tq);
+                else mma<C, true, false, T, true, MB>(acc, sXn, SM::LT, sM1T + 32 * ni * SM::LT, SM::LT, tq);
             }
-            const int l31 = lane & 31, hh = lane >> 5;
+            const int l31 = tq & 31, hh = (tq & 63) >> 5;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int i = 32 * mi + 8 * (e >> 2) + 4 * hh + (e & 3), j = 32 * ni + l31;
@@ -1052,19 +1059,19 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             float zw = zp;
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) zw += __shfl_xor(zw, d);
-            if (lane == 0) sZ[wave] = zw;
+            if ((tq & 63) == 0) sZ[wave] = zw;
         }
-        lds_barrier();
+        lds_barrier(); fresh();
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK = dK1 + diag(beta) dKb + Ah K + Ah^T K; Ah is strictly lower triangular
-            if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
-            else mma<C, false, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK);
-            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK);
-            else mma<C, true, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK);
+            if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
+            else mma<C, false, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
+            if (ka(sI) == 1) mma<32, true, true, T, true, MB>(dk1[sI], sDX + 32 * SM::LT + 32, SM::LT, sK + 32 * SM::LK + 32 * kb(sI), SM::LK, tq);
+            else mma<C, true, true, T, true, MB>(dk1[sI], sDX, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
             if (PRO) { // dW's bytes are free
-                acc_to_lds<T>(sDK, SM::LQO, 32 * ka(sI), 32 * kb(sI), dk1[sI]);
+                acc_to_lds<T>(sDK, SM::LQO, 32 * ka(sI), 32 * kb(sI), dk1[sI], tq);
             } else {
-                acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI]);
+                acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI], tq);
             }
         }
         if (gated && tid < C) {
@@ -1088,8 +1095,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             const float z = ((sZ[0] + sZ[1]) + (sZ[2] + sZ[3])) + ((sZ[4] + sZ[5]) + (sZ[6] + sZ[7]));
             if (tok < nvalid) p.dg[(row0 + tok) * H + h] = c + z;
         }
-        if (tid < 256) { // dbeta = column sums from part 1 + row sums of dA o G
-            const int i = tid >> 2, seg = tid & 3;
+        if (tq < 256) { // dbeta = column sums from part 1 + row sums of dA o G
+            const int i = tq >> 2, seg = tq & 3;
             float sum = 0.f;
 #pragma unroll
             for (int j = 0; j < 16; ++j) sum += sProd[i * SM::LF + seg * 16 + j];
@@ -1102,10 +1109,13 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             }
         }
         if (PRO) { // dk is assembled: back through the feature map, as for dq
-            lds_barrier();
+            lds_barrier(); fresh();
             r.k.feature_map_bwd_store(sDK, SM::LQO, kinv, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, nvalid);
         }
-        lds_barrier(); // every buffer is free for the next tile
+        lds_barrier(); fresh(); // every buffer is free for the next tile
+        if (!AHEAD && np.ok) fetch_all(np);
+        it = nx;
+        cur = np;
     }
 }
 

@@ -7,6 +7,7 @@
 #include "dn_host.hpp"
 #include "dn_kernels.hpp"
 #include "dn_chunk_wide.hpp"
+#include "dn_chunk_stream.hpp"
 
 namespace dn {
 
@@ -58,6 +59,14 @@ static inline int launch_offsets(const Problem &pb) {
 // Head sizes whose chunk operands do not fit the LDS at once take the streaming chunk kernel.
 template <typename T, int DK, int DV> constexpr bool kChunkFits = ChunkSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
 template <typename T, int DK, int DV> constexpr bool kWideBwd = !kChunkFits<T, DK, DV> && sizeof(T) == 2 && DK % 128 == 0 && DV % 64 == 0;
+// The plain delta rule in bf16 at head sizes whose resident tiles fit can take the chunk kernel that rebuilds Ut and dUt
+// from the streamed blocks of S and dS' (k_bwd_stream; option DN_OPT_STREAMED_CHUNK_KERNEL); the scans then skip those two stores.
+template <typename T, int DK, int DV> constexpr bool stream_fits() {
+    if constexpr (sizeof(T) == 2 && DK % 64 == 0 && DV % 64 == 0 && DK <= 128 && DV <= 128) return StreamSmem<T, DK, DV>::bytes <= kLdsPerWorkgroup;
+    else return false;
+}
+template <typename T, int DK, int DV> constexpr bool kStreamBwd = stream_fits<T, DK, DV>();
+static inline bool use_stream_kernel(bool compiled, const Ptrs &p) { return compiled && p.streamed && !p.g && !p.pro; }
 // whether the backward pass is compiled for this head size
 template <typename T, int DK, int DV> constexpr bool kHasBwd = kChunkFits<T, DK, DV> || kWideBwd<T, DK, DV>;
 
@@ -68,6 +77,8 @@ template <typename T, int DK, int DV> size_t max_lds_bytes() {
     size_t m = PrepSmem<T, DK, DV>::bytes;
     if (ScanFwdSmem<T, DK, DV>::bytes > m) m = ScanFwdSmem<T, DK, DV>::bytes;
     if (ScanBwdSmem<T, DK, DV>::bytes > m) m = ScanBwdSmem<T, DK, DV>::bytes;
+    if constexpr (kStreamBwd<T, DK, DV>)
+        if (StreamSmem<T, DK, DV>::bytes > m) m = StreamSmem<T, DK, DV>::bytes;
     if constexpr (kChunkFits<T, DK, DV>) {
         if (ChunkSmem<T, DK, DV>::bytes > m) m = ChunkSmem<T, DK, DV>::bytes;
     } else {
@@ -99,8 +110,9 @@ template <typename T, int DK, int DV> size_t max_lds_fwd_bytes() {
     } while (0)
 
 // what the scans see: with the prologue, the mapped q and k in the workspace
-static inline Ptrs scan_ptrs(const Ptrs &p) {
+static inline Ptrs scan_ptrs(const Ptrs &p, bool stream_compiled) {
     Ptrs ps = p;
+    ps.skip_ut = use_stream_kernel(stream_compiled, p);
     if (p.pro) { ps.q = p.Qm; ps.k = p.Km; ps.pro = 0; }
     return ps;
 }
@@ -119,7 +131,7 @@ template <typename T, int DK, int DV> int run_fwd(const Problem &pb, const Ptrs 
     const dim3 gchunk(pb.chunks_ub, pb.H);
     dim3 gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
     DN_LAUNCH((k_wy_prep<T, DK, DV>), gchunk, (PrepSmem<T, DK, DV>::bytes), sm, pb.H, p);
-    Ptrs ps = scan_ptrs(p);
+    Ptrs ps = scan_ptrs(p, kStreamBwd<T, DK, DV>);
     if constexpr (DK == DV && DK <= 128) {
         // few long chains: cut the sequences into G segments, get every segment's start state from a first pass
         // (k_scan_state, k_seg_combine), then run the scan below over the segments side by side
@@ -150,7 +162,7 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
     const SeqMap sm = make_map(pb);
     if (int e = launch_offsets(pb)) return e;
     const dim3 gchunk(pb.chunks_ub, pb.H), gchain(chain_grid(pb.N * pb.H, VBlock<T, DV, DK>::NV));
-    Ptrs ps = scan_ptrs(p);
+    Ptrs ps = scan_ptrs(p, kStreamBwd<T, DK, DV>);
     constexpr size_t lds_pair = cmax(ScanFwdSmem<T, DK, DV>::bytes, ScanBwdSmem<T, DK, DV>::bytes);
     // few long chains: the scans run over G segments of the sequences side by side (see k_scan_state)
     int G = 1;
@@ -200,8 +212,15 @@ template <typename T, int DK, int DV> int run_bwd(const Problem &pb, const Ptrs 
             } else {
                 DN_LAUNCH_NT((k_bwd_chunk_wide<T, DK, DV, VAR_PLAIN>), gpers, NTC, (WideSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
             }
-        } else
+        } else {
+            if constexpr (kStreamBwd<T, DK, DV>) {
+                if (use_stream_kernel(true, p)) {
+                    DN_LAUNCH_NT((k_bwd_stream<T, DK, DV>), gpers, NTC, (StreamSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+                    return 0;
+                }
+            }
             DN_LAUNCH_VAR(k_bwd_chunk, gpers, NTC, (ChunkSmem<T, DK, DV>::bytes), sm, pb.H, p, pb.chunks_ub);
+        }
     }
     return 0;
 }

@@ -111,3 +111,23 @@ def test_saved_pair_head_size_256_at_the_benchmark_size():
     # the d = 256 step that bench.py times beside the headline one (same tokens, half as many heads), against the oracle
     inp = make_inputs(28, B=8, L=2048, H=8, dk=256, dv=256, dtype="bf16")
     run_saved(inp, "saved bf16 256x256 B=8 L=2048 H=8")
+
+
+@pytest.mark.parametrize("dk,dv", [(128, 128), (64, 128), (128, 64), (64, 64)])
+def test_streamed_chunk_kernel_option(dk, dv):
+    """DN_OPT_STREAMED_CHUNK_KERNEL: the backward pass through the chunk kernel that streams S and dS' in blocks of state
+    columns and rebuilds U - W S and its gradient on chip (the scans then do not store them): against the oracle, for the
+    self-contained pair and the pair that keeps the forward's tiles, dense ragged and packed, and at the benchmark size."""
+    dn.deltanet_set_option(dn.DN_OPT_STREAMED_CHUNK_KERNEL, 1)
+    try:
+        inp = make_inputs(900 + dk + dv, B=2, L=200, H=3, dk=dk, dv=dv, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
+        run_saved(inp, "streamed bf16 %dx%d" % (dk, dv))
+        cu = np.array([0, 0, 5, 69, 199, 262, 263, 263, 520], dtype=np.int32)
+        inp = make_inputs(29, H=2, dk=dk, dv=dv, dtype="bf16", cu_seqlens=cu, with_initial_state=True, with_dfinal_state=True)
+        run_saved(inp, "streamed packed bf16 %dx%d" % (dk, dv))
+        if dk == dv == 128:
+            run_saved(make_config(2), "streamed cfg2")
+    finally:
+        dn.deltanet_set_option(dn.DN_OPT_STREAMED_CHUNK_KERNEL, 0)
+    with pytest.raises(dn.DeltaNetError):
+        dn.deltanet_set_option(77, 1)

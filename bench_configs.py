@@ -2,14 +2,19 @@
 """Times the five benchmark configurations on one MI355X: forward, backward, and the training step as the
 self-contained pair and as the pair that keeps the forward pass's tiles.  Inputs are the seeded synthetic
 batches of ``synth.CONFIGS``, resident on the device; times are wall-clock per call over ``--steps`` calls.
+Prints a table and, per configuration and mode, one JSON line (prefix ``JSON ``) with the same figures.
 
-    python -m paper_2406_06484_amd.config_timings [--steps 20]
+    python bench_configs.py [--steps 20]
 """
 from __future__ import annotations
 
 import argparse
+import json
+import os
 import sys
 import time
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main() -> int:
@@ -38,6 +43,7 @@ def main() -> int:
         torch.cuda.synchronize()
         return 1e3 * (time.perf_counter() - t0) / args.steps
 
+    lines = []
     print("%3s %-44s %8s | %8s %8s %10s %10s | %12s" % ("cfg", "shape", "tokens", "fwd ms", "bwd ms", "fwd+bwd ms", "kept ms", "M tokens/s"))
     for idx in sorted(CONFIGS):
         inp = make_config(idx)
@@ -60,6 +66,11 @@ def main() -> int:
         shape = "%s %s H=%d d=%d" % (inp.dtype, ("packed %d seqs" % (len(inp.cu_seqlens) - 1)) if cu is not None else "B=%d L=%d" % (c["B"], c["L"]),
                                     c["H"], c["dk"])
         print("%3d %-44s %8d | %8.3f %8.3f %10.3f %10.3f | %12.2f" % (idx, shape, tokens, t_f, t_b, t_f + t_b, t_k, tokens / t_k / 1e3), flush=True)
+        for mode, ms in (("fwd", t_f), ("bwd", t_b), ("fwd+bwd", t_f + t_b), ("fwd_save+bwd_saved", t_k)):
+            lines.append(json.dumps({"config": idx, "shape": shape, "mode": mode, "tokens": tokens, "ms": round(ms, 4),
+                                     "tokens_per_s": round(tokens / (ms * 1e-3), 1), "steps": args.steps}))
+    for l in lines:
+        print("JSON " + l)
     return 0
 
 

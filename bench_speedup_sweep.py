@@ -7,13 +7,16 @@ q, k.  For each (d, L) it times the forward pass of both forms through the C ABI
 forward + backward as the self-contained pair and as the pair that keeps the forward pass's tiles,
 and prints one table row.
 
-    python -m paper_2406_06484_amd.speedup_sweep [--steps 20]
+    python bench_speedup_sweep.py [--steps 20]
 """
 from __future__ import annotations
 
 import argparse
+import os
 import sys
 import time
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main() -> int:

@@ -126,26 +126,26 @@ __global__ __launch_bounds__(NTC) void k_bwd_stream(SeqMap sm, int H, Ptrs p, in
     const bool first_half = __builtin_amdgcn_readfirstlane((int)(threadIdx.x < 256)) != 0; // wave-uniform, in a scalar register
     const long sk = (long)H * DK, sv = (long)H * DV;
     // (no branches around the requests: the compiler then knows how many are in flight at every point and waits for
-    // exactly the tile it needs; where the workgroup has no next chunk the current one is requested again)
+    // exactly the tile it needs; where the workgroup has no next chunk the request is issued with every row masked)
     // (the row count and the tile number pass through an empty asm where they are used, for the same reason as `smem`
     // below: the per-lane offsets and row masks of a request or a store are then formed at that point, not carried)
     auto here = [](int x) __attribute__((always_inline)) { asm volatile("" : "+s"(x)); return x; };
     auto herel = [](long x) __attribute__((always_inline)) { asm volatile("" : "+s"(x)); return x; };
-    auto fetch_k = [&](const TilePos &t) __attribute__((always_inline)) { r.k.load((const T *)p.k + (herel(t.row0) * H + t.h) * DK, sk, here(t.nvalid), tq); };
-    auto fetch_q = [&](const TilePos &t) __attribute__((always_inline)) { r.q.load((const T *)p.q + (herel(t.row0) * H + t.h) * DK, sk, here(t.nvalid), tq); };
-    auto fetch_do = [&](const TilePos &t) __attribute__((always_inline)) { r.d_o.load((const T *)p.d_o + (herel(t.row0) * H + t.h) * DV, sv, here(t.nvalid), tq); };
-    auto fetch_v = [&](const TilePos &t) __attribute__((always_inline)) { r.v.load((const T *)p.v + (herel(t.row0) * H + t.h) * DV, sv, here(t.nvalid), tq); };
-    auto fetch_x = [&](const TilePos &t) __attribute__((always_inline)) {
-        r.x.load((const T *)p.Xm + herel(t.tile) * C * C, C, here(C), tq);
+    auto fetch_k = [&](const TilePos &t, int live = 1) __attribute__((always_inline)) { r.k.load((const T *)p.k + (herel(t.row0) * H + t.h) * DK, sk, here(t.nvalid) * live, tq); };
+    auto fetch_q = [&](const TilePos &t, int live = 1) __attribute__((always_inline)) { r.q.load((const T *)p.q + (herel(t.row0) * H + t.h) * DK, sk, here(t.nvalid) * live, tq); };
+    auto fetch_do = [&](const TilePos &t, int live = 1) __attribute__((always_inline)) { r.d_o.load((const T *)p.d_o + (herel(t.row0) * H + t.h) * DV, sv, here(t.nvalid) * live, tq); };
+    auto fetch_v = [&](const TilePos &t, int live = 1) __attribute__((always_inline)) { r.v.load((const T *)p.v + (herel(t.row0) * H + t.h) * DV, sv, here(t.nvalid) * live, tq); };
+    auto fetch_x = [&](const TilePos &t, int live = 1) __attribute__((always_inline)) {
+        r.x.load((const T *)p.Xm + herel(t.tile) * C * C, C, here(C) * live, tq);
         if (tq < C) r.beta = ((const T *)p.beta)[(herel(t.row0) + min(tq, here(t.nvalid) - 1)) * H + t.h];
     };
-    auto fetch_blk = [&](const TilePos &t, int b) __attribute__((always_inline)) { // into register set b & 1
+    auto fetch_blk = [&](const TilePos &t, int b, int live = 1) __attribute__((always_inline)) { // into register set b & 1
         const long off = (herel(t.tile) * DV + (long)b * BV) * DK;
         if constexpr (SPLIT) {
-            r.s[b & 1].load((first_half ? (const T *)p.Sc : (const T *)p.dSc) + off, DK, BV, tq & (NTB - 1));
+            r.s[b & 1].load((first_half ? (const T *)p.Sc : (const T *)p.dSc) + off, DK, BV * live, tq & (NTB - 1));
         } else {
-            r.s[b & 1].load((const T *)p.Sc + off, DK, BV, tq);
-            r.ds[b & 1].load((const T *)p.dSc + off, DK, BV, tq);
+            r.s[b & 1].load((const T *)p.Sc + off, DK, BV * live, tq);
+            r.ds[b & 1].load((const T *)p.dSc + off, DK, BV * live, tq);
         }
     };
     auto stash_blk = [&](int b) __attribute__((always_inline)) { // block b: registers -> its stream buffer
@@ -157,9 +157,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_stream(SeqMap sm, int H, Ptrs p, in
         }
     };
     // the block two ahead of b: of this chunk, or the first ones of the workgroup's next chunk
-    auto fetch_ahead = [&](const TilePos &cur, const TilePos &next, int b) __attribute__((always_inline)) {
+    auto fetch_ahead = [&](const TilePos &cur, const TilePos &next, int next_live, int b) __attribute__((always_inline)) {
         if (b + 2 < NB) fetch_blk(cur, b + 2);
-        else fetch_blk(next, b + 2 - NB);
+        else fetch_blk(next, b + 2 - NB, next_live);
     };
     // where a tile lives: the same for every lane, so it is moved to scalar registers
     auto uni = [](int x) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(x); };
@@ -186,7 +186,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_stream(SeqMap sm, int H, Ptrs p, in
         TileIter nx = it;
         nx.next();
         const TilePos np = pos_of(nx);
-        const TilePos nf = np.ok ? np : tp; // what the freed registers request
+        const TilePos nf = np.ok ? np : tp; // what the freed registers request (every row masked where there is no next chunk)
+        const int nl = np.ok ? 1 : 0;
         const bool first = wave < 4;
         const int mi = wave & 1;                                   // row block of this wave's C x 32 tile (waves 0..3)
         // C x C tile of this wave (waves 1, 2, 3): (1,1), (0,0), (1,0); wave 0 has none and clears the masked tile
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_stream(SeqMap sm, int H, Ptrs p, in
         r.q.store(sQ0(), SM::LK, tq); // (stays in registers: it is needed in LDS once more at the end of the chunk)
         stash_blk(0);
         if (tq < C) sBeta()[tq] = tq < nvalid ? to_f32(r.beta) : 0.f;
-        fetch_k(nf); fetch_do(nf); fetch_v(nf); fetch_x(nf); fetch_ahead(tp, nf, 0);
+        fetch_k(nf, nl); fetch_do(nf, nl); fetch_v(nf, nl); fetch_x(nf, nl); fetch_ahead(tp, nf, nl, 0);
         lds_barrier();
             fresh();
 
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_stream(SeqMap sm, int H, Ptrs p, in
             //    dV_b; dP += dO_b Ut_b^T, dX' += dUt_b R_b^T; dK += Ut_b dS'_b^T
             if (b + 1 < NB) {
                 stash_blk(b + 1);
-                fetch_ahead(tp, nf, b + 1);
+                fetch_ahead(tp, nf, nl, b + 1);
             }
             if (first) {
                 if (wave < 2) { // dV_b = diag(beta) X^T dUt_b (X^T is upper triangular), rows 32 mi ..
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_stream(SeqMap sm, int H, Ptrs p, in
         // ---- after the last block
         // dV S^T of the last block; Q back to LDS; dP, dX = dX' diag(beta), K K^T; dbeta part 1
         r.q.store(sQ1(), SM::LK, tq);
-        fetch_q(nf);
+        fetch_q(nf, nl);
         if (!first) {
 #pragma unroll
             for (int s = 0; s < KW; ++s)

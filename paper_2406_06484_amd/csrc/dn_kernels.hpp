@@ -856,29 +856,30 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         float dos[TileRegs<T, C, DV, NTC>::NIT], vsc[TileRegs<T, C, DV, NTC>::NIT], gm;
     } r;
     // Every tile of a chunk waits in registers from the moment it is requested.  As soon as one has moved to LDS, the same
-    // registers request that tile of the workgroup's next chunk (where there is none, of the current one again: no
-    // branch around a request, so the compiler knows how many are in flight and waits for exactly the one it needs), so
-    // about one chunk's worth of loads is in flight at any time.  The prologue variant keeps the pre-activations of k in
+    // registers request that tile of the workgroup's next chunk (where there is none the request is issued with every
+    // row masked: no branch around a request, so the compiler knows how many are in flight and waits for exactly the
+    // one it needs), so about one chunk's worth of loads is in flight at any time.  The prologue variant keeps the pre-activations of k in
     // registers to the end of the chunk; it requests the next chunk only then.
-    auto fetch_early = [&](const TilePos &tp) __attribute__((always_inline)) {
-        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid, tq);
-        r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV, tq);
-        r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV, tq);
-        r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV, tq);
+    // (`live` = 0 masks every row of a request: the instruction is issued, no memory is touched)
+    auto fetch_early = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
+        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
+        r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV * live, tq);
+        r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV * live, tq);
+        r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV * live, tq);
         if (gated) r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
     };
-    auto fetch_kq = [&](const TilePos &tp) __attribute__((always_inline)) {
-        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid, tq);
-        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid, tq);
+    auto fetch_kq = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
+        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
+        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
         if (tq < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tq, tp.nvalid - 1)) * H + tp.h];
         if (gated && tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
     };
-    auto fetch_ds = [&](const TilePos &tp) __attribute__((always_inline)) { r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV, tq); };
-    auto fetch_v = [&](const TilePos &tp) __attribute__((always_inline)) {
-        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid, tq);
+    auto fetch_ds = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) { r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV * live, tq); };
+    auto fetch_v = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
+        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
         if (gated) r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
     };
-    auto fetch_x = [&](const TilePos &tp) __attribute__((always_inline)) { r.x.load((const T *)p.Xm + tp.tile * C * C, C, C, tq); };
+    auto fetch_x = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) { r.x.load((const T *)p.Xm + tp.tile * C * C, C, C * live, tq); };
     auto fetch_all = [&](const TilePos &tp) __attribute__((always_inline)) { fetch_early(tp); fetch_kq(tp); fetch_ds(tp); fetch_v(tp); fetch_x(tp); };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
 
@@ -897,7 +898,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         TileIter nx = it;
         nx.next();
         const TilePos np = pos_of(nx);
-        const TilePos nf = np.ok ? np : cur; // what the freed registers request
+        const TilePos nf = np.ok ? np : cur; // what the freed registers request (masked where there is no next chunk)
+        const int nl = np.ok ? 1 : 0;
         asm volatile("" : "+v"(wave)); // opaque: see above
         const int mi = (wave >> 1) & 1, ni = wave & 1; // tile of every C x C matrix, for the first four waves
         const bool cc = wave < 4, upper = (mi == 0 && ni == 1);
@@ -912,7 +914,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (gated) r.d_o.scale_rows(r.dos);
         r.d_o.store(sDO, SM::LV, tq); r.ut.store(sUt, SM::LU, tq); r.s.store(sS, SM::LSK, tq);
         r.dut.store(sDU, SM::LU, tq);
-        if (AHEAD) fetch_early(nf);
+        if (AHEAD) fetch_early(nf, nl);
         // prologue variant: the feature map of section 3.3 on the way to LDS; the pre-activations stay in
         // r.q / r.k and the norms in qinv / kinv for the way back
         float qinv[TileRegs<T, C, DK, NTC>::NIT], kinv[TileRegs<T, C, DK, NTC>::NIT];
@@ -928,7 +930,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             sBeta[tq] = b;
         }
         if (gated && tid < 2 * C) sGam[tid] = r.gm;
-        if (AHEAD) fetch_kq(nf);
+        if (AHEAD) fetch_kq(nf, nl);
         lds_barrier(); fresh();
         if (cc) { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
@@ -948,7 +950,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         lds_barrier(); fresh(); // dP visible; S is dead
         if (gated) zp = r.ds.dot_lds(sS, SM::LSK); // <dS~', S_0>: each thread meets the S values it parked there itself
         r.ds.store(sS, SM::LSK, tq);
-        if (AHEAD) fetch_ds(nf);
+        if (AHEAD) fetch_ds(nf, nl);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dQ += dP K
             if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
@@ -985,7 +987,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         if (gated) r.v.scale_rows(r.vsc);
         r.v.store(sV, SM::LV, tq);
-        if (AHEAD) fetch_v(nf);
+        if (AHEAD) fetch_v(nf, nl);
         lds_barrier(); fresh();
         f32x16 g = zero16(), dxp = zero16();
         if (cc && !upper) {
@@ -996,7 +998,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }, tq); // strictly lower G
         lds_barrier(); fresh(); // V and dS' are dead
         r.x.store(sXn, SM::LT, tq);
-        if (AHEAD) fetch_x(nf);
+        if (AHEAD) fetch_x(nf, nl);
         lds_barrier(); fresh();
         if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
             float part = 0.f;

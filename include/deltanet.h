@@ -29,6 +29,10 @@
  *    segments that are scanned side by side; the per-segment states this needs are part of that size.)
  *  - Return value: DN_OK (0) or a negative dn_status.  All validation happens before the first
  *    launch; on a validation error nothing has been enqueued.  No exceptions, no abort.
+ *  - Packed layout without cu_seqlens_host: nothing can be validated on the host; the kernels then work on the
+ *    running maximum of the device array held inside [0, L] (the array itself if it is valid), so a malformed array
+ *    gives meaningless results but no access outside the tensors or the workspace.
+ *  - A tensor without rows (B * L == 0) may come with a NULL pointer; final_state is then initial_state (or zero).
  *  - Sequences of length 0 are allowed in the packed layout; lengths need not be multiples of
  *    the chunk size (a ragged last chunk is handled exactly, as beta = 0 leaves the state
  *    unchanged, section 2.2).
@@ -138,9 +142,12 @@ int deltanet_bwd_saved(const dn_shape *shape, const void *q, const void *k, cons
  *
  * per token and head (fp32 arithmetic, result rounded to the element type).  The kernel that builds T
  * maps q and k once and leaves them in the workspace for the chain scans; the backward's chunk kernel
- * maps its tiles on their way to the LDS and sends dq, dk back through the map on their way out, so the
- * gradients never reach HBM in the mapped coordinates and no separate elementwise pass runs in either
- * direction.  A row whose SiLU image is exactly zero maps to zero (the paper gives no epsilon).
+ * maps its tiles on their way to the LDS and sends dq, dk back through the map on their way out, so at head
+ * sizes up to 128 the gradients never reach HBM in the mapped coordinates and no separate elementwise pass runs
+ * in either direction.  At head size 256 the way back is not fused: the chunk kernel writes dq, dk in the mapped
+ * coordinates (element type dtype) and one more kernel per tensor takes them through the map in place, so those
+ * two gradients are rounded to the element type twice.  A row whose SiLU image is exactly zero maps to zero (the
+ * paper gives no epsilon).
  * deltanet_fused_bwd returns the gradients with respect to q_pre, k_pre and beta_logit (through the
  * normalisation, the SiLU and the sigmoid) in dq_pre, dk_pre (element type dtype) and dbeta_logit
  * (fp32); dv and dinitial_state are as for deltanet_bwd.  Workspace (and `saved`) sizes come from

@@ -1,6 +1,6 @@
 // The chunk-parallel backward kernel for head sizes whose chunk operands do not fit the LDS at once
 // (d_k = d_v = 256 in bf16: S and dS' alone are 2 x 128 KB per chunk).  Same mathematics as k_bwd_chunk
-// (adjoint of Eq. 8-11, plain delta rule only); the operands with a d_v axis are streamed in blocks of
+// (adjoint of Eq. 8-11; all three variants, see VAR_* below); the operands with a d_v axis are streamed in blocks of
 // state columns, each read from global memory exactly once except Ut (twice):
 //
 //   sweep 1 (blocks of 32 state columns: S_b with all of d_k, dO_b, Ut_b, dUt_b, V_b):

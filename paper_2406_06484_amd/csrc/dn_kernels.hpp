@@ -108,7 +108,7 @@ template <typename T, int DK, int DV> struct PrepSmem {
 };
 
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTHR) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
+__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(6, 6))) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     using SM = PrepSmem<T, DK, DV>;
     extern __shared__ __align__(16) unsigned char smem[];
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
@@ -249,7 +249,13 @@ template <typename T, int DK, int DV> struct ScanFwdSmem {
     static constexpr size_t oStage = oP + align16(sizeof(T) * C * LT); // per-wave output staging tiles
     static constexpr int NSTG = ScanMap<DK, BV>::U_TILES; // only the output waves stage tiles
     static constexpr size_t oGam = oStage + NSTG * sizeof(T) * Stage<T>::ELEMS; // gated: gamma_i, 1 / gamma_i of the chunk
-    static constexpr size_t bytes = oGam + sizeof(float) * 2 * C;
+    static constexpr size_t bytes1 = oGam + sizeof(float) * 2 * C;
+    // Where a second K tile and a second gamma table fit, the tiles of the next chunk move to LDS in the interval that
+    // updates the state (which still reads the current K), and a chunk step takes three barrier intervals instead of four.
+    static constexpr size_t szK = align16(sizeof(T) * C * LK);
+    static constexpr bool kMerge = bytes1 + szK + sizeof(float) * 2 * C <= 160 * 1024;
+    static constexpr size_t oK2 = bytes1, oGam2 = oK2 + szK;
+    static constexpr size_t bytes = kMerge ? oGam2 + sizeof(float) * 2 * C : bytes1;
 };
 
 template <typename T, int DK, int DV, int MODE, int VAR>
@@ -264,14 +270,15 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     extern __shared__ __align__(16) unsigned char smem[];
     T *stg = reinterpret_cast<T *>(smem + SM::oStage) + ((threadIdx.x >> 6) % SM::NSTG) * Stage<T>::ELEMS;
     T *sQ = reinterpret_cast<T *>(smem + SM::oQ);
-    T *sK = reinterpret_cast<T *>(smem + SM::oK);
+    constexpr bool MERGE = SM::kMerge;
+    T *sK0 = reinterpret_cast<T *>(smem + SM::oK), *sK1 = MERGE ? reinterpret_cast<T *>(smem + SM::oK2) : sK0;
     T *sV = reinterpret_cast<T *>(smem + SM::oV);
     T *sW = reinterpret_cast<T *>(smem + SM::oW);
     T *sST = reinterpret_cast<T *>(smem + SM::oST);
     T *sUT0 = reinterpret_cast<T *>(smem + SM::oUT), *sUT1 = reinterpret_cast<T *>(smem + SM::oUT + SM::szUT);
     T *sT = reinterpret_cast<T *>(smem + SM::oT);
     T *sP = reinterpret_cast<T *>(smem + SM::oP);
-    float *sGam = reinterpret_cast<float *>(smem + SM::oGam);
+    float *sGam0 = reinterpret_cast<float *>(smem + SM::oGam), *sGam1 = MERGE ? reinterpret_cast<float *>(smem + SM::oGam2) : sGam0;
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
     constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (sizeof(T) == 4 ? 2 : (DK > 128 ? 4 : 0)); // SCAN_BOTH: the loader waves hold more
@@ -340,17 +347,17 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             stage_flush<T>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
                            min(C, len - icp * C));
     };
-    auto stash = [&]() __attribute__((always_inline)) { // fetched tiles: registers -> LDS
+    auto stash = [&](int par) __attribute__((always_inline)) { // fetched tiles of a chunk of parity `par`: registers -> LDS
         if (OUT) r.q.store(sQ, SM::LQ, lt);
-        r.k.store(sK, SM::LK, lt);
+        r.k.store(par ? sK1 : sK0, SM::LK, lt);
         if (gated) { // the chunk runs the plain rule on v_i / gamma_i
             r.v.scale_rows(r.vs);
-            if (lt < 2 * C) sGam[lt] = r.gm;
+            if (lt < 2 * C) (par ? sGam1 : sGam0)[lt] = r.gm;
         }
         r.v.store(sV, SM::LV, lt);
         r.t.store(sT, SM::LT, lt);
     };
-    if (loader && nchunks > 0) { fetch_a(0); fetch_b(0); stash(); }
+    if (loader && nchunks > 0) { fetch_a(0); fetch_b(0); stash(0); }
     // gated: gamma at the end of the chunk, which rescales the state when the chunk is done; every wave
     // requests the next chunk's value one step ahead
     float gC = 1.f, gCn = 1.f;
@@ -358,9 +365,13 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     for (int ic = 0; ic < nchunks; ++ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sUT = (ic & 1) ? sUT1 : sUT0;
+        T *sK = (ic & 1) ? sK1 : sK0;
+        float *sGam = (ic & 1) ? sGam1 : sGam0;
         gC = gCn;
         if (gated && ic + 1 < nchunks) gCn = p.gam[(tile + H) * 2 * C + C - 1];
-        if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
+        if (!MERGE || ic == 0) {
+            if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
+        }
         lds_barrier();
         if (loader && ic + 1 < nchunks) fetch_a(ic + 1);
         if (MODE == SCAN_BOTH && loader) {
@@ -431,10 +442,16 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         }
         if (m.has_s) mma<C, true, false, T, true, MB>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
         if (gated) S *= gC; // back from S / gamma to the state itself at the chunk boundary
-        lds_barrier();
+        if (MERGE) {
+            // nothing read in this interval is written here: the state's LDS copy serves only the first two intervals of a
+            // step, Q, V, T only the first, and the next K and gamma table go to the buffers of the other parity
+            if (m.has_s && ic + 1 < nchunks) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
+        } else {
+            lds_barrier();
+        }
         // The next chunk's tiles move to LDS here, in the iteration that requested them: the wait the
         // compiler puts in front counts the stores issued after the loads and lets those stay in flight.
-        if (loader && ic + 1 < nchunks) stash();
+        if (loader && ic + 1 < nchunks) stash((ic + 1) & 1);
     }
     if (loader && nchunks > 0) {
         if (SAVE && !p.skip_ut) flush_ut(nchunks - 1);
@@ -655,14 +672,15 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     // gamma_C on entry; every wave requests the value for the next step one step ahead
     float gCn = 1.f;
     if (gated && nchunks > 0) gCn = p.gam[((long)(cb + nchunks - 1) * H + h) * 2 * C + C - 1];
+    // dS' of the last chunk (the gradient with respect to the state after it) goes to LDS here; every later one at the end
+    // of the step that produced it: that interval reads only W and dUt^T, so the state gradient's LDS copy and the next
+    // chunk's tiles can be written in it, and a chunk step takes three barrier intervals.
+    if (gated) dS *= gCn;
+    if (m.has_s && nchunks > 0) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS);
     for (int ic = nchunks - 1; ic >= 0; --ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sDUT = (ic & 1) ? sDUT1 : sDUT0;
-        if (gated) {
-            dS *= gCn;
-            if (ic > 0) gCn = p.gam[(tile - H) * 2 * C + C - 1];
-        }
-        if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' (gradient w.r.t. the state after this chunk)
+        if (gated && ic > 0) gCn = p.gam[(tile - H) * 2 * C + C - 1]; // for the end of this step
         lds_barrier();
         if (loader && ic > 0) fetch_a(ic - 1);
         f32x16 acc = zero16();
@@ -711,8 +729,11 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
             mma<C, true, false, T, true, MB>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
             dS -= wd;
         }
-        lds_barrier();
-        if (loader && ic > 0) stash(); // see k_scan_fwd
+        if (ic > 0) {
+            if (gated) dS *= gCn;
+            if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' of the next step
+            if (loader) stash(); // see k_scan_fwd
+        }
     }
     if (!STATE && loader && nchunks > 0 && !p.skip_ut) flush_dut(0);
     if (p.dS0 && m.has_s) {

@@ -29,12 +29,21 @@ __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_b
 // pointing their lanes beyond the descriptor's range, which makes the hardware return zeros.
 // This keeps 64-bit per-load address pairs and exec-mask branches out of the prefetch code.
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+// Cache-policy bits of the loads and stores, per stream of tiles (0 = default, 2 = non-temporal; measured variant by
+// variant on the fwd+bwd step, kernels of one step timed side by side on the same device):
+//   tiles the launch reads once and no later kernel of the same call needs: non-temporal loads (every operand of the
+//     chunk kernel; V in the forward scan, whose two workgroups per chain read different column blocks)
+//   tiles that the other workgroup of the chain reads too (Q, K, T in the scans) or that the next kernel of the call reads
+//     (K in k_wy_prep, dO in the reverse scan): default policy, they are found in the L2 or the memory-side cache
+//   every tile store of the scans, k_wy_prep and the chunk kernel: non-temporal (nothing is read back by the same launch)
+constexpr int kAuxOnce = 2, kAuxKeep = 0;
 constexpr int kBufRange = 0x40000000; // bytes covered by a descriptor; offsets >= this read as zero
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, kBufRange, 0x00020000);
 }
-__device__ inline uint4 buf_load16(__amdgpu_buffer_rsrc_t rs, int voff, int soff) {
-    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
+// AUX = the instruction's cache-policy bits: 0 = default, 2 = non-temporal (data that this launch reads once)
+template <int AUX = 0> __device__ inline uint4 buf_load16(__amdgpu_buffer_rsrc_t rs, int voff, int soff) {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, AUX));
 }
 
 // Per-element-type constants: LDS row padding (elements) and elements per 16 bytes.
@@ -219,16 +228,21 @@ template <typename T> struct Stage {
 };
 __device__ inline void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <typename T>
+// ONCE: non-temporal store, for output that nothing reads again before the launch ends
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+template <typename T, bool ONCE = false>
 __device__ inline void stage_flush(const T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, int tx = threadIdx.x) {
     const int lane = tx & 63;
     wave_lds_fence();
 #pragma unroll
     for (int it = 0; it < 32 * Stage<T>::SEGS / 64; ++it) {
         const int idx = it * 64 + lane, r = idx / Stage<T>::SEGS, sg = idx % Stage<T>::SEGS;
-        if (row0 + r < nvalid)
-            *reinterpret_cast<uint4 *>(dst + (long)(row0 + r) * row_stride + col0 + sg * El<T>::VEC) =
-                *reinterpret_cast<const uint4 *>(stage + r * Stage<T>::LD + sg * El<T>::VEC);
+        if (row0 + r < nvalid) {
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(stage + r * Stage<T>::LD + sg * El<T>::VEC);
+            u32x4 *to = reinterpret_cast<u32x4 *>(dst + (long)(row0 + r) * row_stride + col0 + sg * El<T>::VEC);
+            if (ONCE) __builtin_nontemporal_store(val, to);
+            else *to = val;
+        }
     }
     wave_lds_fence(); // the staging tile may be rewritten right away
 }
@@ -259,10 +273,10 @@ __device__ inline void stage_flush_dot(const T *stage, T *dst, long row_stride, 
     wave_lds_fence();
 }
 // dst[row0 + r][col0 + c] = acc(r, c), rows >= nvalid dropped; `stage` is this wave's staging tile
-template <typename T>
+template <typename T, bool ONCE = false>
 __device__ inline void acc_store(T *stage, T *dst, long row_stride, int row0, int col0, int nvalid, f32x16 &acc, int tx = threadIdx.x) {
     acc_to_lds<T>(stage, Stage<T>::LD, 0, 0, acc, tx);
-    stage_flush<T>(stage, dst, row_stride, row0, col0, nvalid, tx);
+    stage_flush<T, ONCE>(stage, dst, row_stride, row0, col0, nvalid, tx);
 }
 // ---------------------------------------------------------------------------------------------
 // A ROWS x COLS tile fetched from global memory into registers (16 bytes per lane and step; rows >=
@@ -272,15 +286,18 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
     static_assert(COLS % VEC == 0 && NT % TPR == 0 && ROWS % RPI == 0, "tile shape");
     uint4 v[NIT];
     // `t` is the caller's index among the NT threads that share the tile (defaults to the whole workgroup)
-    __device__ inline void load(const T *src, long row_stride, int nvalid, int t = threadIdx.x) {
+    template <int AUX> __device__ inline void load_aux(const T *src, long row_stride, int nvalid, int t) {
         const int tr = t / TPR, tc = (t % TPR) * VEC;
         const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
         const int rs_bytes = (int)row_stride * (int)sizeof(T);
         const int voff = tr * rs_bytes + tc * (int)sizeof(T);
 #pragma unroll
         for (int it = 0; it < NIT; ++it)
-            v[it] = buf_load16(rs, it * RPI + tr < nvalid ? voff : kBufRange, it * RPI * rs_bytes);
+            v[it] = buf_load16<AUX>(rs, it * RPI + tr < nvalid ? voff : kBufRange, it * RPI * rs_bytes);
     }
+    __device__ inline void load(const T *src, long row_stride, int nvalid, int t = threadIdx.x) { load_aux<0>(src, row_stride, nvalid, t); }
+    // for a tile that no other workgroup of the launch reads: non-temporal, it does not displace what the caches hold
+    __device__ inline void load_once(const T *src, long row_stride, int nvalid, int t = threadIdx.x) { load_aux<kAuxOnce>(src, row_stride, nvalid, t); }
     __device__ inline void store(T *dst, int ld, int t = threadIdx.x) const {
         const int tr = t / TPR, tc = (t % TPR) * VEC;
 #pragma unroll
@@ -411,14 +428,18 @@ __device__ inline void load_tile(T *dst, int ld, const T *src, long row_stride, 
 }
 // LDS -> global copy of a ROWS x COLS tile by NT cooperating threads (t = index among them); the
 // destination is a contiguous row-major block
-template <typename T, int ROWS, int COLS, int NT>
+template <typename T, int ROWS, int COLS, int NT, bool ONCE = false>
 __device__ inline void copy_out(T *dst, const T *src, int ld, int t) {
     constexpr int VEC = El<T>::VEC, TPR = COLS / VEC, RPI = NT / TPR;
     static_assert(COLS % VEC == 0 && NT % TPR == 0 && ROWS % RPI == 0, "tile shape");
     const int tr = t / TPR, tc = (t % TPR) * VEC;
 #pragma unroll
-    for (int r0 = 0; r0 < ROWS; r0 += RPI)
-        *reinterpret_cast<uint4 *>(dst + (long)(r0 + tr) * COLS + tc) = *reinterpret_cast<const uint4 *>(src + (r0 + tr) * ld + tc);
+    for (int r0 = 0; r0 < ROWS; r0 += RPI) {
+        const u32x4 val = *reinterpret_cast<const u32x4 *>(src + (r0 + tr) * ld + tc);
+        u32x4 *to = reinterpret_cast<u32x4 *>(dst + (long)(r0 + tr) * COLS + tc);
+        if (ONCE) __builtin_nontemporal_store(val, to);
+        else *to = val;
+    }
 }
 // ---------------------------------------------------------------------------------------------
 // X = (I + A)^{-1} for a 64x64 strictly-lower-triangular A (section 3.2: the inverse of the unit

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(6, 6))) vo
 
     {
         TileRegs<T, C, DK> kr;
-        kr.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        kr.template load_aux<kAuxKeep>((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, threadIdx.x);
         if (p.pro) { // prologue variant: q and k arrive before the feature map of section 3.3
             TileRegs<T, C, DK> qr;
             qr.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid);
@@ -181,8 +181,8 @@ __global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(6, 6))) vo
             tv[u] = from_f32<T>(x * sBeta[j0 + u]);
             xv[u] = from_f32<T>(x);
         }
-        *reinterpret_cast<uint4 *>((T *)p.Tm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(tv);
-        if (p.want_x) *reinterpret_cast<uint4 *>((T *)p.Xm + tile * C * C + i * C + j0) = *reinterpret_cast<const uint4 *>(xv);
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(tv), reinterpret_cast<u32x4 *>((T *)p.Tm + tile * C * C + i * C + j0));
+        if (p.want_x) __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(xv), reinterpret_cast<u32x4 *>((T *)p.Xm + tile * C * C + i * C + j0));
     }
 }
 
@@ -319,10 +319,10 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.k.template load_aux<kAuxKeep>((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         // (the transition-matrix pass of k_scan_state runs on v = 0: no row is valid)
-        r.v.load((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, (MODE == SCAN_STATE && p.unit_state) ? 0 : nvalid, lt);
-        r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+        r.v.template load_aux<kAuxOnce>((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, (MODE == SCAN_STATE && p.unit_state) ? 0 : nvalid, lt);
+        r.t.template load_aux<kAuxKeep>((const T *)p.Tm + tile * C * C, C, C, lt);
         if (gated) {
             r.v.load_row_factors(r.vs, p.gam + tile * 2 * C + C, lt);
             if (lt < 2 * C) r.gm = p.gam[tile * 2 * C + lt];
@@ -331,7 +331,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     auto fetch_b = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
-        if (OUT) r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        if (OUT) r.q.template load_aux<kAuxKeep>((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
     };
     // Everything that touches global memory is issued by the loader waves in one burst right after
     // the first barrier of a step: the loads for the next chunk, then the stores of what the previous
@@ -340,11 +340,11 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     // full step old.
     auto flush_ut = [&](int icp) __attribute__((always_inline)) { // Ut^T of chunk icp, still in LDS
         const long tile = ((long)(cb + icp) * H + h);
-        copy_out<T, BV, C, NTL>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt);
+        copy_out<T, BV, C, NTL, true>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt);
     };
     auto flush_out = [&](int icp) __attribute__((always_inline)) { // this wave's staged output tile of chunk icp
         if (m.does_o)
-            stage_flush<T>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
+            stage_flush<T, true>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
                            min(C, len - icp * C));
     };
     auto stash = [&](int par) __attribute__((always_inline)) { // fetched tiles of a chunk of parity `par`: registers -> LDS
@@ -377,8 +377,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (MODE == SCAN_BOTH && loader) {
             // the tiles kept for the backward pass leave in this interval, in which the loader waves have no product
             // of their own: the chunk-initial state (transposed, as it sits in LDS) and the previous chunk's Ut^T
-            copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
-            if (ic > 0 && !p.skip_ut) copy_out<T, BV, C, NTL>((T *)p.Ut + ((tile - H) * DV + vb) * C, ((ic - 1) & 1) ? sUT1 : sUT0, SM::LT, lt);
+            copy_out<T, BV, DK, NTL, true>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (ic > 0 && !p.skip_ut) copy_out<T, BV, C, NTL, true>((T *)p.Ut + ((tile - H) * DV + vb) * C, ((ic - 1) & 1) ? sUT1 : sUT0, SM::LT, lt);
         }
         f32x16 acc = zero16();
         if (!loader) {
@@ -423,7 +423,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (loader) {
             if (ic + 1 < nchunks) fetch_b(ic + 1);
             // the chunk-initial state leaves transposed, as it sits in LDS
-            if (MODE == SCAN_STORE) copy_out<T, BV, DK, NTL>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
+            if (MODE == SCAN_STORE) copy_out<T, BV, DK, NTL, true>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
             if (OUT && ic > 0) flush_out(ic - 1);
         }
         if (m.does_u) { // Ut = U - W S (inner term of Eq. 8-9)
@@ -645,19 +645,19 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     auto fetch_a = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
-        r.q.load((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
-        r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.q.template load_aux<kAuxKeep>((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
+        r.k.template load_aux<kAuxKeep>((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
     };
     auto fetch_b = [&](int ic) __attribute__((always_inline)) {
         const int nvalid = min(C, len - ic * C);
         const long row0 = (long)t0 + (long)ic * C;
         const long tile = ((long)(cb + ic) * H + h);
-        r.d_o.load((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
-        r.t.load((const T *)p.Tm + tile * C * C, C, C, lt);
+        r.d_o.template load_aux<kAuxKeep>((const T *)p.d_o + (row0 * H + h) * DV + vb, (long)H * DV, nvalid, lt);
+        r.t.template load_aux<kAuxKeep>((const T *)p.Tm + tile * C * C, C, C, lt);
         if (gated) r.d_o.load_row_factors(r.dos, p.gam + tile * 2 * C, lt);
     };
     auto flush_dut = [&](int icp) __attribute__((always_inline)) { // dUt^T of chunk icp, still in LDS
-        copy_out<T, BV, C, NTL>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, lt);
+        copy_out<T, BV, C, NTL, true>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, lt);
     };
     // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
@@ -714,7 +714,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader) {
             if (ic > 0) fetch_b(ic - 1);
-            if (!STATE) copy_out<T, BV, DK, NTL>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
+            if (!STATE) copy_out<T, BV, DK, NTL, true>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
         }
         if (m.does_u) { // + P^T dO; P^T is upper triangular
             if (m.ua == 0) mma<C, false, true, T, true, MB>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);
@@ -883,24 +883,24 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     // registers to the end of the chunk; it requests the next chunk only then.
     // (`live` = 0 masks every row of a request: the instruction is issued, no memory is touched)
     auto fetch_early = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
-        r.d_o.load((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
-        r.ut.load((const T *)p.Ut + tp.tile * DV * C, C, DV * live, tq);
-        r.s.load((const T *)p.Sc + tp.tile * DV * DK, DK, DV * live, tq);
-        r.dut.load((const T *)p.dUt + tp.tile * DV * C, C, DV * live, tq);
+        r.d_o.load_once((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
+        r.ut.load_once((const T *)p.Ut + tp.tile * DV * C, C, DV * live, tq);
+        r.s.load_once((const T *)p.Sc + tp.tile * DV * DK, DK, DV * live, tq);
+        r.dut.load_once((const T *)p.dUt + tp.tile * DV * C, C, DV * live, tq);
         if (gated) r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
     };
     auto fetch_kq = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
-        r.k.load((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
-        r.q.load((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
+        r.k.load_once((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
+        r.q.load_once((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
         if (tq < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tq, tp.nvalid - 1)) * H + tp.h];
         if (gated && tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
     };
-    auto fetch_ds = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) { r.ds.load((const T *)p.dSc + tp.tile * DV * DK, DK, DV * live, tq); };
+    auto fetch_ds = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) { r.ds.load_once((const T *)p.dSc + tp.tile * DV * DK, DK, DV * live, tq); };
     auto fetch_v = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
-        r.v.load((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
+        r.v.load_once((const T *)p.v + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
         if (gated) r.v.load_row_factors(r.vsc, p.gam + tp.tile * 2 * C + C);
     };
-    auto fetch_x = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) { r.x.load((const T *)p.Xm + tp.tile * C * C, C, C * live, tq); };
+    auto fetch_x = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) { r.x.load_once((const T *)p.Xm + tp.tile * C * C, C, C * live, tq); };
     auto fetch_all = [&](const TilePos &tp) __attribute__((always_inline)) { fetch_early(tp); fetch_kq(tp); fetch_ds(tp); fetch_v(tp); fetch_x(tp); };
     auto pos_of = [&](const TileIter &it) __attribute__((always_inline)) { return it.valid() ? tile_pos(sm, H, it.gid(), it.head()) : TilePos{0, 0, 0, 0, false}; };
 
@@ -983,7 +983,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             } else if (PRO) { // dO's bytes are free: dq is assembled there for the way back through the map
                 acc_to_lds<T>(sDQ, SM::LQO, 32 * ka(sI), 32 * kb(sI), dq[sI], tq);
             } else {
-                acc_store<T>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI], tq);
+                acc_store<T, true>(stg, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dq[sI], tq);
             }
         }
         lds_barrier(); fresh();
@@ -1055,7 +1055,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
                 stage_flush_dot<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, sV, SM::LV,
                                    sCv + vbk(sI) * C);
             } else {
-                acc_store<T>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc, tq);
+                acc_store<T, true>(stg, (T *)p.dv + (row0 * H + h) * DV, (long)H * DV, 32 * va(sI), 32 * vbk(sI), nvalid, acc, tq);
             }
         }
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1, tq); // Q's bytes: dead since dK1 (the inverse scratch, too)
@@ -1094,7 +1094,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             if (PRO) { // dW's bytes are free
                 acc_to_lds<T>(sDK, SM::LQO, 32 * ka(sI), 32 * kb(sI), dk1[sI], tq);
             } else {
-                acc_store<T>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI], tq);
+                acc_store<T, true>(stg, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, 32 * ka(sI), 32 * kb(sI), nvalid, dk1[sI], tq);
             }
         }
         if (gated && tid < C) {

@@ -24,6 +24,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--width", type=int, default=2048)
+    ap.add_argument("--head-sizes", type=int, nargs="+", default=[64, 128, 256])
     args = ap.parse_args()
     import torch
 
@@ -48,7 +49,7 @@ def main() -> int:
 
     print("%5s %6s %4s %4s | %12s %12s %9s | %16s %16s" % ("d", "L", "B", "H", "recurrent ms", "chunkwise ms", "speed-up",
                                                         "fwd+bwd ms", "fwd+bwd kept ms"))
-    for d in (64, 128, 256):
+    for d in args.head_sizes:
         H = args.width // d
         for L in (512, 1024, 2048, 4096, 8192, 16384):
             B = max(1, args.tokens // L)

@@ -251,6 +251,15 @@ int deltanet_profile_collect(dn_kernel_time *out, int max_entries, int *num_entr
 typedef enum { DN_OPT_STREAMED_CHUNK_KERNEL = 0 } dn_option;
 int deltanet_set_option(int option, int value);
 
+/*
+ * Measurement aid (not part of the method): one launch of a probe kernel that repeats, `iters` times, ONE of the LDS
+ * access patterns the kernels are built from (pattern 0..17: operand-fragment reads in both storage orders, accumulator
+ * and register tiles written to LDS, row-segment reads; the list is in csrc/dn_lds_probe.hip), so that a profiler's LDS
+ * counters can be read per pattern.  256 workgroups of 512 threads, no global memory traffic.  iters in [0, 2^20];
+ * DN_ERR_UNSUPPORTED for an unknown pattern.  The launch is enqueued on hip_stream.
+ */
+int deltanet_lds_probe(int pattern, int iters, void *hip_stream);
+
 /* Static, NUL-terminated description of a dn_status value. */
 const char *deltanet_status_string(int status);
 

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     deltanet_gated_fwd_save,
     deltanet_gated_recurrent_fwd,
     deltanet_gated_workspace_bytes,
+    deltanet_lds_probe,
     deltanet_profile_collect,
     deltanet_recurrent_fwd,
     deltanet_set_option,

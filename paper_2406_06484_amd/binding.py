@@ -87,6 +87,8 @@ def load_library():
         lib.deltanet_gated_recurrent_fwd.argtypes = [sp] + [vp] * 8 + [vp]
         lib.deltanet_set_option.restype = ctypes.c_int
         lib.deltanet_set_option.argtypes = [ctypes.c_int, ctypes.c_int]
+        lib.deltanet_lds_probe.restype = ctypes.c_int
+        lib.deltanet_lds_probe.argtypes = [ctypes.c_int, ctypes.c_int, vp]
         lib.deltanet_profile_enable.restype = ctypes.c_int
         lib.deltanet_profile_enable.argtypes = [ctypes.c_int]
         lib.deltanet_profile_collect.restype = ctypes.c_int
@@ -107,6 +109,11 @@ DN_OPT_STREAMED_CHUNK_KERNEL = 0
 def deltanet_set_option(option: int, value: int) -> None:
     """Process-wide option of the library (see include/deltanet.h)."""
     _check(load_library().deltanet_set_option(int(option), int(value)))
+
+
+def deltanet_lds_probe(pattern: int, iters: int) -> None:
+    """Measurement aid: one launch of the probe kernel for LDS access pattern `pattern` (see include/deltanet.h)."""
+    _check(load_library().deltanet_lds_probe(int(pattern), int(iters), ctypes.c_void_p(_stream(None))))
 
 
 def deltanet_profile_enable(on: bool) -> None:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdeltanet_hip.so")
-SOURCES = ["dn_api.hip", "dn_inst_f32.hip", "dn_inst_bf16.hip", "dn_inst_bf16_wide.hip", "dn_recurrent.hip", "dn_noalloc.hip"]
+SOURCES = ["dn_api.hip", "dn_inst_f32.hip", "dn_inst_bf16.hip", "dn_inst_bf16_wide.hip", "dn_recurrent.hip", "dn_noalloc.hip", "dn_lds_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

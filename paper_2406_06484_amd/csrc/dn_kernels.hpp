@@ -107,8 +107,11 @@ template <typename T, int DK, int DV> struct PrepSmem {
     static constexpr size_t bytes = oBeta + sizeof(float) * C;
 };
 
+// (bf16 up to d_k = 128: held to the registers of six workgroups per CU, which is what its LDS allows; the other
+// instantiations would spill under that cap)
+template <typename T, int DK> struct PrepWaves { static constexpr int lo = (sizeof(T) == 2 && DK <= 128) ? 6 : 1, hi = (sizeof(T) == 2 && DK <= 128) ? 6 : 8; };
 template <typename T, int DK, int DV>
-__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(6, 6))) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
+__global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(PrepWaves<T, DK>::lo, PrepWaves<T, DK>::hi))) void k_wy_prep(SeqMap sm, int H, Ptrs p) {
     using SM = PrepSmem<T, DK, DV>;
     extern __shared__ __align__(16) unsigned char smem[];
     T *sK = reinterpret_cast<T *>(smem + SM::oK);
@@ -282,6 +285,9 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
     constexpr int MB = (GATED || MODE == SCAN_BOTH) ? 2 : (sizeof(T) == 4 ? 2 : (DK > 128 ? 4 : 0)); // SCAN_BOTH: the loader waves hold more
+    // a workgroup's rows of V and O are whole 128-byte lines: non-temporal; with narrower column blocks a line is shared with
+    // the neighbouring workgroup of the chain and keeps the default policy
+    constexpr bool kWholeLines = BV * sizeof(T) >= 128;
 
     int chain, vbi;
     if (!chain_of_block(bid, sm.N * H, NV, chain, vbi)) return;
@@ -321,7 +327,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         const long tile = ((long)(cb + ic) * H + h);
         r.k.template load_aux<kAuxKeep>((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, lt);
         // (the transition-matrix pass of k_scan_state runs on v = 0: no row is valid)
-        r.v.template load_aux<kAuxOnce>((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, (MODE == SCAN_STATE && p.unit_state) ? 0 : nvalid, lt);
+        r.v.template load_aux<kWholeLines ? kAuxOnce : kAuxKeep>((const T *)p.v + (row0 * H + h) * DV + vb, (long)H * DV, (MODE == SCAN_STATE && p.unit_state) ? 0 : nvalid, lt);
         r.t.template load_aux<kAuxKeep>((const T *)p.Tm + tile * C * C, C, C, lt);
         if (gated) {
             r.v.load_row_factors(r.vs, p.gam + tile * 2 * C + C, lt);
@@ -344,7 +350,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     };
     auto flush_out = [&](int icp) __attribute__((always_inline)) { // this wave's staged output tile of chunk icp
         if (m.does_o)
-            stage_flush<T, true>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
+            stage_flush<T, kWholeLines>(stg, (T *)p.o + (((long)t0 + (long)icp * C) * H + h) * DV + vb, (long)H * DV, 32 * m.ua, 32 * m.ub,
                            min(C, len - icp * C));
     };
     auto stash = [&](int par) __attribute__((always_inline)) { // fetched tiles of a chunk of parity `par`: registers -> LDS

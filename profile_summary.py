@@ -15,6 +15,8 @@ split counters over passes), then `python3 profile_summary.py`.  The raw output 
   rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/fetch_s -o fetch_s --output-format csv -- $S --steps 3 --warmup 1 --copy-calibration
   rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/write_s -o write_s --output-format csv -- $S --steps 3 --warmup 1 --copy-calibration
 
+  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d gpurun_out/prof/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py
+
 bench.py --mode headline runs the timed step (deltanet_fwd_save + deltanet_bwd_saved: k_wy_prep, k_scan_fwd_save,
 k_scan_bwd, k_bwd_chunk) and the self-contained pair (deltanet_fwd + deltanet_bwd: k_wy_prep, k_scan_fwd; k_wy_prep,
 k_scan_pair, k_bwd_chunk) and nothing else, so every row below belongs to one of the two.
@@ -209,6 +211,42 @@ def write_counters():
         f.write("\nThe counters are taken under the profiler, where the kernels run a few percent slower than in the timed region.\n" + KEY)
 
 
+def write_lds_patterns():
+    rows = rows_of("lds_patterns", "counter_collection.csv")
+    if rows is None:
+        return
+    sys.path.insert(0, ROOT)
+    from bench_lds_patterns import PATTERNS  # the probe's pattern list (names only; importing it runs nothing)
+    agg = collections.defaultdict(dict)
+    for r in rows:
+        m = re.search(r"k_lds_probe<(\d+)>", r["Kernel_Name"])
+        if m:  # the long launch of each pattern (the short warm-up launch counts less)
+            d = agg[int(m.group(1))]
+            d[r["Counter_Name"]] = max(d.get(r["Counter_Name"], 0.0), float(r["Counter_Value"]))
+    with open(os.path.join(OUT, "lds_conflicts_by_access_pattern.txt"), "w") as f:
+        f.write("LDS counters of the access patterns the kernels are built from, one probe kernel per pattern (deltanet_lds_probe: the\n"
+                "kernels' own helpers at the kernels' own leading dimensions, 8 wavefronts per workgroup, bf16 tiles), MI355X\n\n"
+                "command (from the repo root on the GPU box), then python3 profile_summary.py:\n"
+                "  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d gpurun_out/prof/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py\n\n"
+                "conflict = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE (the ratio profiles/mfma_lds_counters_cfg2_fwd_bwd.txt gives per kernel);\n"
+                "idx/inst = SQ_LDS_IDX_ACTIVE / SQ_INSTS_LDS: cycles the LDS spends indexing one instruction of the pattern.  An instruction\n"
+                "that moves 1024 bytes per wavefront (16 bytes per lane) occupies the 128-byte-per-clock data path for 8 cycles whatever its\n"
+                "index cycles are, one that moves 512 bytes for 4.\n\n")
+        f.write("%2s  %-92s %9s %9s\n" % ("#", "pattern", "conflict", "idx/inst"))
+        for pat in sorted(agg):
+            d = agg[pat]
+            idx, inst = d.get("SQ_LDS_IDX_ACTIVE", 0.0), d.get("SQ_INSTS_LDS", 0.0)
+            f.write("%2d  %-92s %9.3f %9.2f\n" % (pat, PATTERNS[pat][0], d.get("SQ_LDS_BANK_CONFLICT", 0.0) / idx if idx else 0.0,
+                                                  idx / inst if inst else 0.0))
+        f.write("\nReading: the 16-byte fragment reads are conflict-free at leading dimensions of 8 (mod 32) elements (136, 72) and take two\n"
+                "index passes at 16 (mod 32) (144, 80): 8 index cycles, the same 8 cycles the data path needs for the instruction, so that\n"
+                "conflict costs no time.  The transposing 8-byte reads take 4 index cycles against 4 data cycles at 144, 80 and 72, and 8 at 136,\n"
+                "which is why tiles that are read in both orders carry the padding of 16 elements.  The 2-byte accumulator writes have no\n"
+                "conflicts (they are bound by instruction issue).  The 8-byte transposed accumulator writes (issued in pairs, 16 bytes per\n"
+                "lane) need 16 index cycles where 8 would do, and 31 at 144 or 80: the one pattern whose conflicts cost LDS time, about 30\n"
+                "cycles per 32 x 32 tile and wavefront, at the better of the two paddings a 16-byte-aligned row allows.\n")
+
+
 def main() -> int:
     if not os.path.isdir(PROF):
         print("profile_summary.py: %s is missing; run the rocprofv3 commands in this file's header first" % PROF, file=sys.stderr)
@@ -217,6 +255,7 @@ def main() -> int:
     write_trace()
     write_traffic()
     write_counters()
+    write_lds_patterns()
     return 0
 
 

@@ -381,10 +381,9 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader && ic + 1 < nchunks) fetch_a(ic + 1);
         if (MODE == SCAN_BOTH && loader) {
-            // the tiles kept for the backward pass leave in this interval, in which the loader waves have no product
-            // of their own: the chunk-initial state (transposed, as it sits in LDS) and the previous chunk's Ut^T
+            // the chunk-initial state, kept for the backward pass, leaves in this interval (transposed, as it sits in
+            // LDS); the previous chunk's Ut^T follows in the third one: both in one interval make it the longest
             copy_out<T, BV, DK, NTL, true>((T *)p.Sc + (tile * DV + vb) * DK, sST, SM::LS, lt);
-            if (ic > 0 && !p.skip_ut) copy_out<T, BV, C, NTL, true>((T *)p.Ut + ((tile - H) * DV + vb) * C, ((ic - 1) & 1) ? sUT1 : sUT0, SM::LT, lt);
         }
         f32x16 acc = zero16();
         if (!loader) {
@@ -439,7 +438,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         lds_barrier();
-        if (MODE == SCAN_STORE && loader && ic > 0 && !p.skip_ut) flush_ut(ic - 1);
+        if (SAVE && loader && ic > 0 && !p.skip_ut) flush_ut(ic - 1);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T, true, MB>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T, true, MB>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -689,6 +688,8 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         if (gated && ic > 0) gCn = p.gam[(tile - H) * 2 * C + C - 1]; // for the end of this step
         lds_barrier();
         if (loader && ic > 0) fetch_a(ic - 1);
+        // dS'^T to the workspace, in the interval whose length the chain waves' products set
+        if (loader && !STATE) copy_out<T, BV, DK, NTL, true>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt);
         f32x16 acc = zero16();
         if (!loader) { // straight-line, as in the forward scan; the loader waves are busy with global memory meanwhile
             // (with more than two W tiles per wave, d_k = 256, the tiles are finished one at a time, as in the forward scan)
@@ -720,7 +721,6 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         lds_barrier();
         if (loader) {
             if (ic > 0) fetch_b(ic - 1);
-            if (!STATE) copy_out<T, BV, DK, NTL, true>((T *)p.dSc + (tile * DV + vb) * DK, sDST, SM::LS, lt); // dS'^T to the workspace
         }
         if (m.does_u) { // + P^T dO; P^T is upper triangular
             if (m.ua == 0) mma<C, false, true, T, true, MB>(acc, sPT, SM::LT, sDO + 32 * m.ub, SM::LD);

@@ -102,3 +102,15 @@ def test_packed_offsets_without_a_host_copy_stay_in_bounds():
     bounded = torch.tensor([0, 0, 69, 69, 199, 262, 263, 520, 520], dtype=torch.int32, device="cuda")
     o2, ST2, g2 = raw_call(bounded)
     assert torch.equal(o, o2) and torch.equal(ST, ST2) and all(torch.equal(a, b) for a, b in zip(g, g2))
+
+
+def test_lds_probe_launches_every_pattern_and_rejects_unknown_ones():
+    """The measurement aid deltanet_lds_probe: every documented pattern launches and finishes; a pattern outside the list
+    and a repeat count outside the documented range are refused before any launch."""
+    for pattern in range(18):
+        dn.deltanet_lds_probe(pattern, 3)
+    torch.cuda.synchronize()
+    with pytest.raises(dn.DeltaNetError):
+        dn.deltanet_lds_probe(18, 3)
+    with pytest.raises(dn.DeltaNetError):
+        dn.deltanet_lds_probe(0, -1)

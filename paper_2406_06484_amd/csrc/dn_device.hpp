@@ -174,6 +174,42 @@ __device__ inline void mma(f32x16 &acc, const T *A, int lda, const T *B, int ldb
     if (FENCE) __builtin_amdgcn_sched_barrier(0);
 }
 
+// Two products with the same B operand: acc1 += A1 * B, acc2 += A2 * B; B's fragments are read from LDS once.
+template <int KDIM, bool A1KS, bool A2KS, bool BKS, typename T, int BATCH_>
+__device__ inline void mma_shared_b(f32x16 &acc1, f32x16 &acc2, const T *A1, int lda1, const T *A2, int lda2, const T *B, int ldb,
+                                    int tx = threadIdx.x) {
+    constexpr int KS = KStep<T>::value, N = KDIM / KS;
+    constexpr int BATCH = N < BATCH_ ? N : BATCH_, NB = N / BATCH;
+    static_assert(N % BATCH == 0, "contraction length must be a multiple of the batch");
+    typedef typename FragOf<T>::type frag_t;
+    frag_t a1[2][BATCH], a2[2][BATCH], b[2][BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+        b[0][j] = BKS ? frag_ks(B, ldb, j * KS, tx) : frag_kc(B, ldb, j * KS, tx);
+        a1[0][j] = A1KS ? frag_ks(A1, lda1, j * KS, tx) : frag_kc(A1, lda1, j * KS, tx);
+        a2[0][j] = A2KS ? frag_ks(A2, lda2, j * KS, tx) : frag_kc(A2, lda2, j * KS, tx);
+    }
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+        if (ib + 1 < NB) {
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const int k0 = ((ib + 1) * BATCH + j) * KS;
+                b[(ib + 1) & 1][j] = BKS ? frag_ks(B, ldb, k0, tx) : frag_kc(B, ldb, k0, tx);
+                a1[(ib + 1) & 1][j] = A1KS ? frag_ks(A1, lda1, k0, tx) : frag_kc(A1, lda1, k0, tx);
+                a2[(ib + 1) & 1][j] = A2KS ? frag_ks(A2, lda2, k0, tx) : frag_kc(A2, lda2, k0, tx);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+            mfma32(acc1, a1[ib & 1][j], b[ib & 1][j]);
+            mfma32(acc2, a2[ib & 1][j], b[ib & 1][j]);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 __device__ inline f32x16 zero16() {
     f32x16 z;
 #pragma unroll

@@ -970,8 +970,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         for (int sI = 0; sI < KW; ++sI) {
             dq[sI] = zero16(); dw[sI] = zero16(); dk1[sI] = zero16();
             if (kt(sI) < KT) {
-                mma<DV, false, true, T, true, MB>(dq[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sS + 32 * kb(sI), SM::LSK, tq); // dO S^T
-                mma<DV, true, true, T, true, MB>(dw[sI], sDU + 32 * ka(sI), SM::LU, sS + 32 * kb(sI), SM::LSK, tq);           // dUt S^T
+                // dO S^T and dUt S^T: the fragments of S are read once for both
+                mma_shared_b<DV, false, true, true, T, 2>(dq[sI], dw[sI], sDO + 32 * ka(sI) * SM::LV, SM::LV, sDU + 32 * ka(sI), SM::LU,
+                                                          sS + 32 * kb(sI), SM::LSK, tq);
             }
         }
         lds_barrier(); fresh(); // dP visible; S is dead
@@ -1015,6 +1016,8 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (gated) r.v.scale_rows(r.vsc);
         r.v.store(sV, SM::LV, tq);
         if (AHEAD) fetch_v(nf, nl);
+        r.x.store(sXn, SM::LT, tq); // over dS', which dK1 was the last to read
+        if (AHEAD) fetch_x(nf, nl);
         lds_barrier(); fresh();
         f32x16 g = zero16(), dxp = zero16();
         if (cc && !upper) {
@@ -1023,10 +1026,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             mma<DV, true, false, T, true, MB>(dxp, sDU + 32 * mi, SM::LU, sV + 32 * ni * SM::LV, SM::LV, tq);
         }
         acc_each(g, [&](int rr, int c, float &val) { if (32 * ni + c >= 32 * mi + rr) val = 0.f; }, tq); // strictly lower G
-        lds_barrier(); fresh(); // V and dS' are dead
-        r.x.store(sXn, SM::LT, tq);
-        if (AHEAD) fetch_x(nf, nl);
-        lds_barrier(); fresh();
+        // (dX goes to dP's bytes, dead since dK1: no barrier between the product and its scaled copy)
         if (cc) { // dbeta part 1 (column sums of X o dX'), dX = dX' diag(beta)
             float part = 0.f;
             acc_each(dxp, [&](int rr, int c, float &val) {

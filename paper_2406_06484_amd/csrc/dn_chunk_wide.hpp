@@ -354,14 +354,9 @@ __global__ __launch_bounds__(NTHR) void k_feature_map_bwd(const T *x, T *dy, lon
     TileRegs<T, C, DK, NTHR> rx, rd;
     rx.load(x + r0 * DK, DK, nvalid);
     rd.load(dy + r0 * DK, DK, nvalid);
-    float inv[TileRegs<T, C, DK, NTHR>::NIT];
-    {
-        TileRegs<T, C, DK, NTHR> y = rx;
-        y.feature_map(inv); // only the norms are needed
-    }
     rd.store(sD, LD);
     wave_lds_fence();
-    rx.feature_map_bwd_store(sD, LD, inv, dy + r0 * DK, DK, nvalid);
+    rx.feature_map_bwd_store(sD, LD, dy + r0 * DK, DK, nvalid);
 }
 
 // The gate gradient of the gated variant for head sizes that take k_bwd_chunk_wide: o_t is linear in q_t and in the state, so

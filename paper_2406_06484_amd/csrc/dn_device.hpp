@@ -397,13 +397,30 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
         y.feature_map(inv);
         y.store(dst, ld, t);
     }
-    // Gradient through the map, for a tile whose pre-activations x this object still holds: src = dy in LDS
-    // (same shape, leading dimension ld), inv[] from feature_map_to;
-    //     dx = SiLU'(x) (dy - y (y . dy)) / ||SiLU(x)||,  SiLU'(x) = sig (1 + x (1 - sig)),
-    // written to global memory (rows >= nvalid dropped).  A row's dot product is a butterfly over its TPR lanes.
-    __device__ inline void feature_map_bwd_store(const T *src, int ld, const float (&inv)[NIT], T *dst, long row_stride, int nvalid,
-                                                 int t = threadIdx.x) const {
+    // Gradient through the map, for a tile whose pre-activations x this object holds: src = dy in LDS
+    // (same shape, leading dimension ld);
+    //     dx = SiLU'(x) (dy - y (y . dy)) / ||SiLU(x)||,  SiLU'(x) = sig (1 + x (1 - sig)),  y = SiLU(x) / ||SiLU(x)||,
+    // written to global memory (rows >= nvalid dropped).  A first pass forms the rows' norms (as feature_map does, so y has
+    // the bits of the mapped tile) and keeps every sigmoid; a row's sums are butterflies over its TPR lanes.
+    __device__ inline void feature_map_bwd_store(const T *src, int ld, T *dst, long row_stride, int nvalid, int t = threadIdx.x) const {
         const int tr = t / TPR, tc = (t % TPR) * VEC;
+        float sg[NIT][VEC], inv[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            alignas(16) T x[VEC];
+            *reinterpret_cast<uint4 *>(x) = v[it];
+            float ss = 0.f;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) {
+                const float xv = to_f32(x[u]);
+                sg[it][u] = sigmoid_f32(xv);
+                const float sv = __fmul_rn(xv, sg[it][u]);
+                ss = __fmaf_rn(sv, sv, ss);
+            }
+#pragma unroll
+            for (int d = 1; d < TPR; d <<= 1) ss = __fadd_rn(ss, __shfl_xor(ss, d));
+            inv[it] = ss > 0.f ? __frsqrt_rn(ss) : 0.f;
+        }
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             alignas(16) T x[VEC], a[VEC];
@@ -412,9 +429,9 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
             float y[VEC], dsl[VEC], dot = 0.f;
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
-                const float xv = to_f32(x[u]), sg = sigmoid_f32(xv);
-                y[u] = __fmul_rn(__fmul_rn(xv, sg), inv[it]);
-                dsl[u] = sg * (1.f + xv * (1.f - sg)) * inv[it];
+                const float xv = to_f32(x[u]), s1 = sg[it][u];
+                y[u] = __fmul_rn(__fmul_rn(xv, s1), inv[it]);
+                dsl[u] = s1 * (1.f + xv * (1.f - s1)) * inv[it];
                 dot += to_f32(a[u]) * y[u];
             }
 #pragma unroll

@@ -877,6 +877,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         TileRegs<T, DV, C, NTC> ut, dut;
         TileRegs<T, DV, DK, NTC> s, ds;
         TileRegs<T, C, DK, NTC> k, q;
+        TileRegs<T, C, DK, NTC> raw; // prologue variant: the pre-activations of q, then of k, for the way back through the map
         TileRegs<T, C, C, NTC> x;
         T beta; // kept in storage format: converting here would wait for the whole prefetch
         // gated: gamma of this lane's dO rows, 1 / gamma of its V rows; entry tid of the chunk's table of gamma_i, 1 / gamma_i
@@ -885,8 +886,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     // Every tile of a chunk waits in registers from the moment it is requested.  As soon as one has moved to LDS, the same
     // registers request that tile of the workgroup's next chunk (where there is none the request is issued with every
     // row masked: no branch around a request, so the compiler knows how many are in flight and waits for exactly the
-    // one it needs), so about one chunk's worth of loads is in flight at any time.  The prologue variant keeps the pre-activations of k in
-    // registers to the end of the chunk; it requests the next chunk only then.
+    // one it needs), so about one chunk's worth of loads is in flight at any time.
     // (`live` = 0 masks every row of a request: the instruction is issued, no memory is touched)
     auto fetch_early = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
         r.d_o.load_once((const T *)p.d_o + (tp.row0 * H + tp.h) * DV, (long)H * DV, tp.nvalid * live, tq);
@@ -896,8 +896,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (gated) r.d_o.load_row_factors(r.dos, p.gam + tp.tile * 2 * C);
     };
     auto fetch_kq = [&](const TilePos &tp, int live = 1) __attribute__((always_inline)) {
-        r.k.load_once((const T *)p.k + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
-        r.q.load_once((const T *)p.q + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
+        // (prologue variant: the q and k that k_wy_prep mapped and left in the workspace, in the layout of q and k)
+        r.k.load_once((const T *)(PRO ? p.Km : p.k) + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
+        r.q.load_once((const T *)(PRO ? p.Qm : p.q) + (tp.row0 * H + tp.h) * DK, (long)H * DK, tp.nvalid * live, tq);
         if (tq < C) r.beta = ((const T *)p.beta)[(tp.row0 + min(tq, tp.nvalid - 1)) * H + tp.h];
         if (gated && tid < 2 * C) r.gm = p.gam[tp.tile * 2 * C + tid];
     };
@@ -917,7 +918,6 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     // each other's MFMA phases.
     if ((long)chunks_total * H >= 4l * gridDim.x)
         for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(64);
-    constexpr bool AHEAD = VAR != VAR_PROLOGUE;
     TileIter it(chunks_total, H);
     TilePos cur = pos_of(it);
     if (cur.ok) fetch_all(cur);
@@ -941,23 +941,18 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         if (gated) r.d_o.scale_rows(r.dos);
         r.d_o.store(sDO, SM::LV, tq); r.ut.store(sUt, SM::LU, tq); r.s.store(sS, SM::LSK, tq);
         r.dut.store(sDU, SM::LU, tq);
-        if (AHEAD) fetch_early(nf, nl);
-        // prologue variant: the feature map of section 3.3 on the way to LDS; the pre-activations stay in
-        // r.q / r.k and the norms in qinv / kinv for the way back
-        float qinv[TileRegs<T, C, DK, NTC>::NIT], kinv[TileRegs<T, C, DK, NTC>::NIT];
-        if (PRO) {
-            r.k.feature_map_to(sK, SM::LK, kinv);
-            r.q.feature_map_to(sQ, SM::LK, qinv);
-        } else {
-            r.k.store(sK, SM::LK, tq); r.q.store(sQ, SM::LK, tq);
-        }
+        fetch_early(nf, nl);
+        // prologue variant: q and k come mapped (section 3.3) from the workspace, as k_wy_prep left them; the pre-activations
+        // are fetched on the side, q's now and k's once q's gradient has left, for the way back through the map
+        r.k.store(sK, SM::LK, tq); r.q.store(sQ, SM::LK, tq);
+        if (PRO) r.raw.load_once((const T *)p.q + (row0 * H + h) * DK, (long)H * DK, nvalid, tq); // the pre-activations of q
         if (tq < C) {
             float b = tq < nvalid ? to_f32(r.beta) : 0.f;
             if (PRO) b = tq < nvalid ? sigmoid_f32(b) : 0.f; // beta = sigmoid(logit), section 2.2
             sBeta[tq] = b;
         }
         if (gated && tid < 2 * C) sGam[tid] = r.gm;
-        if (AHEAD) fetch_kq(nf, nl);
+        fetch_kq(nf, nl);
         lds_barrier(); fresh();
         if (cc) { // dP = tril(dO Ut^T)
             f32x16 acc = zero16();
@@ -978,7 +973,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         lds_barrier(); fresh(); // dP visible; S is dead
         if (gated) zp = r.ds.dot_lds(sS, SM::LSK); // <dS~', S_0>: each thread meets the S values it parked there itself
         r.ds.store(sS, SM::LSK, tq);
-        if (AHEAD) fetch_ds(nf, nl);
+        fetch_ds(nf, nl);
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dQ += dP K
             if (ka(sI) == 0) mma<32, false, true, T, true, MB>(dq[sI], sDP, SM::LT, sK + 32 * kb(sI), SM::LK, tq);
@@ -994,8 +989,10 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
             }
         }
         lds_barrier(); fresh();
-        if (PRO) // gradient through the feature map: dq~ = SiLU'(q~) (dq - q (q . dq)) / ||SiLU(q~)||
-            r.q.feature_map_bwd_store(sDQ, SM::LQO, qinv, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, nvalid);
+        if (PRO) { // gradient through the feature map: dq~ = SiLU'(q~) (dq - q (q . dq)) / ||SiLU(q~)||
+            r.raw.feature_map_bwd_store(sDQ, SM::LQO, (T *)p.dq + (row0 * H + h) * DK, (long)H * DK, nvalid, tq);
+            r.raw.load_once((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, tq); // ... and those of k, for the end of the chunk
+        }
 #pragma unroll
         for (int sI = 0; sI < KW; ++sI) if (kt(sI) < KT) { // dK1 = dP^T Q + Ut dS'^T
             if (gated) { // <K, Ut dS~'^T>, the second half of <dS_C, S_C>, taken while dK1 holds just that product
@@ -1015,9 +1012,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         if (gated) r.v.scale_rows(r.vsc);
         r.v.store(sV, SM::LV, tq);
-        if (AHEAD) fetch_v(nf, nl);
+        fetch_v(nf, nl);
         r.x.store(sXn, SM::LT, tq); // over dS', which dK1 was the last to read
-        if (AHEAD) fetch_x(nf, nl);
+        fetch_x(nf, nl);
         lds_barrier(); fresh();
         f32x16 g = zero16(), dxp = zero16();
         if (cc && !upper) {
@@ -1066,9 +1063,6 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         if (cc) acc_to_lds_t<T>(sM1T, SM::LT, 32 * mi, 32 * ni, m1, tq); // Q's bytes: dead since dK1 (the inverse scratch, too)
         lds_barrier(); fresh(); // dX is dead
-        // prologue variant: the pre-activations of k are needed once more at the very end; they are requested again here
-        // rather than kept in registers through the products above
-        if (PRO) r.k.load((const T *)p.k + (row0 * H + h) * DK, (long)H * DK, nvalid, tq);
         if (cc) { // dA = -tril(X^T M1, -1); dA o G to sProd; Ah = diag(beta) dA into sDX
             f32x16 acc = zero16();
             if (!upper) {
@@ -1139,10 +1133,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
         }
         if (PRO) { // dk is assembled: back through the feature map, as for dq
             lds_barrier(); fresh();
-            r.k.feature_map_bwd_store(sDK, SM::LQO, kinv, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, nvalid);
+            r.raw.feature_map_bwd_store(sDK, SM::LQO, (T *)p.dk + (row0 * H + h) * DK, (long)H * DK, nvalid, tq);
         }
         lds_barrier(); fresh(); // every buffer is free for the next tile
-        if (!AHEAD && np.ok) fetch_all(np);
         it = nx;
         cur = np;
     }

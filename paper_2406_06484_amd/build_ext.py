@@ -17,7 +17,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, "_build", os.path.splitext(src)[0] + ".o")
     os.makedirs(os.path.dirname(obj), exist_ok=True)
-    cmd = ["hipcc"] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    # DELTANET_HIPCC_FLAGS: extra compiler flags, e.g. -DDN_VBLOCK_COLS=32 for the tiling study
+    cmd = ["hipcc"] + FLAGS + os.environ.get("DELTANET_HIPCC_FLAGS", "").split() + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -66,9 +66,13 @@ inline int segment_count(int N, int L, int H, int d_k, int d_v, int nv, bool pac
 inline int segment_count_bwd(int N, int L, int H, int d_k, int d_v, int nv, bool packed, int chunk = 64) {
     return (long)N * H * nv <= 32 ? segment_count(N, L, H, d_k, d_v, nv, packed, chunk) : 1;
 }
-// state columns per scan workgroup, as the kernels choose them (VBlock)
+// State columns per scan workgroup: 64 in bf16 up to d_k = 128, else 32 (what fits the LDS).  DN_VBLOCK_COLS (a build
+// option, for the tiling study: 32 or 64) overrides the 64.
+#ifndef DN_VBLOCK_COLS
+#define DN_VBLOCK_COLS 64
+#endif
 inline int scan_vblock_cols(int elem_bytes, int d_k, int d_v) {
-    const int want = (elem_bytes == 2 && d_k <= 128) ? 64 : 32;
+    const int want = (elem_bytes == 2 && d_k <= 128) ? DN_VBLOCK_COLS : 32;
     return d_v < want ? d_v : want;
 }
 

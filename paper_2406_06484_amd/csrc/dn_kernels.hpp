@@ -203,7 +203,7 @@ constexpr int NTS = 512, NWS = 8, NTL = 256; // threads / waves of a scan workgr
 // bf16 workgroups own 64 state columns; fp32 ones, and bf16 ones with d_k = 256, own 32, so that the
 // tiles (whose rows are d_k long) still fit the 160 KB of LDS
 template <typename T, int DV, int DK> struct VBlock {
-    static constexpr int WANT = (sizeof(T) == 2 && DK <= 128) ? 64 : 32;
+    static constexpr int WANT = (sizeof(T) == 2 && DK <= 128) ? DN_VBLOCK_COLS : 32;
     static constexpr int BV = DV < WANT ? DV : WANT;
     static constexpr int NV = DV / BV;
 };

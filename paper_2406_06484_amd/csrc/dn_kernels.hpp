@@ -193,10 +193,11 @@ __global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(PrepWaves<
 // The two chain-serial kernels.  One workgroup of 8 wavefronts owns one chain and BV = 64 columns
 // of the state; the state lives in accumulator registers, one 32 x 32 tile per wave.
 // Waves 0..3 own the Ut / dUt tiles of the dependent chain; waves 4..7 have the lighter work between
-// barriers and double as loaders: they alone touch global memory, one burst per step (the next
-// chunk's tiles into registers, the previous chunk's results out of LDS), so the chain waves never
-// queue behind the CU's 64 B/clk vector-memory path.  W = T K (Eq. 11) is rebuilt per chunk from
-// the 64 x 64 T.
+// barriers and double as loaders: they request the next chunk's tiles and send most of the results
+// out of LDS, so that the chain waves do not queue behind the CU's 64 B/clk vector-memory path in the
+// intervals whose length they set (the one exception: the kept Ut / dUt tile of the previous step
+// leaves through the chain waves in the last interval, where the loader waves are the busier side).
+// W = T K (Eq. 11) is rebuilt per chunk from the 64 x 64 T.
 // Workgroup ids are laid out so that the v-blocks of one chain land on the same XCD (ids are dealt
 // round-robin over the 8 XCDs) and share its L2 for the Q, K, T tiles they both read.
 constexpr int NTS = 512, NWS = 8, NTL = 256; // threads / waves of a scan workgroup; loader threads
@@ -344,9 +345,9 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     // step left in LDS (its Ut^T, or its staged output tile).  The compiler drains the memory counter
     // when the loaded registers are moved to LDS at the top of the next step; by then all of it is a
     // full step old.
-    auto flush_ut = [&](int icp) __attribute__((always_inline)) { // Ut^T of chunk icp, still in LDS
+    auto flush_ut = [&](int icp, int t) __attribute__((always_inline)) { // Ut^T of chunk icp, still in LDS; t = 0 .. NTL - 1
         const long tile = ((long)(cb + icp) * H + h);
-        copy_out<T, BV, C, NTL, true>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, lt);
+        copy_out<T, BV, C, NTL, true>((T *)p.Ut + (tile * DV + vb) * C, (icp & 1) ? sUT1 : sUT0, SM::LT, t);
     };
     auto flush_out = [&](int icp) __attribute__((always_inline)) { // this wave's staged output tile of chunk icp
         if (m.does_o)
@@ -438,7 +439,8 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             acc_to_lds_t<T>(sUT, SM::LT, 32 * m.ua, 32 * m.ub, acc);
         }
         lds_barrier();
-        if (SAVE && loader && ic > 0 && !p.skip_ut) flush_ut(ic - 1);
+        // the previous chunk's Ut^T leaves here, sent by the chain waves, which have no output tile to form in this interval
+        if (SAVE && !loader && ic > 0 && !p.skip_ut) flush_ut(ic - 1, (int)threadIdx.x);
         if (does_o) { // O = Q S + P Ut (Eq. 9); the tile waits in this wave's staging area until the next step
             if (m.ua == 0) mma<32, false, false, T, true, MB>(acc, sP, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
             else mma<C, false, false, T, true, MB>(acc, sP + 32 * SM::LT, SM::LT, sUT + 32 * m.ub * SM::LT, SM::LT);
@@ -459,7 +461,7 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
         if (loader && ic + 1 < nchunks) stash((ic + 1) & 1);
     }
     if (loader && nchunks > 0) {
-        if (SAVE && !p.skip_ut) flush_ut(nchunks - 1);
+        if (SAVE && !p.skip_ut) flush_ut(nchunks - 1, lt);
         if (OUT) flush_out(nchunks - 1);
     }
     if ((OUT || MODE == SCAN_STATE) && p.ST && m.has_s) {
@@ -661,8 +663,8 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         r.t.template load_aux<kAuxKeep>((const T *)p.Tm + tile * C * C, C, C, lt);
         if (gated) r.d_o.load_row_factors(r.dos, p.gam + tile * 2 * C, lt);
     };
-    auto flush_dut = [&](int icp) __attribute__((always_inline)) { // dUt^T of chunk icp, still in LDS
-        copy_out<T, BV, C, NTL, true>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, lt);
+    auto flush_dut = [&](int icp, int t) __attribute__((always_inline)) { // dUt^T of chunk icp, still in LDS; t = 0 .. NTL - 1
+        copy_out<T, BV, C, NTL, true>((T *)p.dUt + (((long)(cb + icp) * H + h) * DV + vb) * C, (icp & 1) ? sDUT1 : sDUT0, SM::LT, t);
     };
     // As in the forward scan, the loader waves issue all global traffic of a step in one burst after
     // its first barrier: next chunk's loads, this chunk's dS'^T, the previous step's dUt^T.
@@ -729,7 +731,8 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
         }
         if (m.has_s) mma<C, true, true, T, true, MB>(dS, sQ + 32 * m.sa, SM::LQ, sDO + 32 * m.sb, SM::LD); // + Q^T dO
         lds_barrier();
-        if (!STATE && loader && ic + 1 < nchunks && !p.skip_ut) flush_dut(ic + 1);
+        // (sent by the chain waves, as in the forward scan: the loader waves have the next chunk's tiles to move in this interval)
+        if (!STATE && !loader && ic + 1 < nchunks && !p.skip_ut) flush_dut(ic + 1, (int)threadIdx.x);
         if (m.has_s) { // - W^T dUt
             f32x16 wd = zero16();
             mma<C, true, false, T, true, MB>(wd, sW + 32 * m.sa, SM::LQ, sDUT + 32 * m.sb * SM::LT, SM::LT);
@@ -741,7 +744,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
             if (loader) stash(); // see k_scan_fwd
         }
     }
-    if (!STATE && loader && nchunks > 0 && !p.skip_ut) flush_dut(0);
+    if (!STATE && loader && nchunks > 0 && !p.skip_ut) flush_dut(0, lt);
     if (p.dS0 && m.has_s) {
         float *dst = p.dS0 + (long)chain * DK * DV + vb;
         acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });

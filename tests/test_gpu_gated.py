@@ -42,6 +42,14 @@ def test_gated_strong_decay_and_packed(dtype, d):
     run_gated(inp, make_gate(2, inp.beta.shape, lo=0.4, hi=1.0), label="gated packed strong %s" % dtype)
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_gated_decay_near_the_documented_limit(dtype, d):
+    """alpha ~ U(0.3, 0.4): the log-decays of a 64-token chunk sum to about -67, close to the documented bound of 80 beyond
+    which exp(-sum g) leaves the fp32 range.  The oracle has no such bound; the kernels must still match it here."""
+    inp = make_inputs(29, B=2, L=200, H=2, dk=d, dv=d, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
+    run_gated(inp, make_gate(5, inp.beta.shape, lo=0.3, hi=0.4), label="gated near the limit %s" % dtype)
+
+
 def test_zero_gate_equals_the_plain_path_on_the_gpu():
     inp = make_inputs(9, B=1, L=150, H=2, dk=128, dv=128, dtype="bf16", with_initial_state=True, with_dfinal_state=True)
     d = dev_inputs(inp)

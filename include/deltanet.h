@@ -194,10 +194,12 @@ int deltanet_recurrent_fwd(const dn_shape *shape, const void *q, const void *k, 
  *     S_t = alpha_t (S_{t-1} - beta_t k_t (S_{t-1}^T k_t)^T) + beta_t k_t v_t^T ,   o_t = S_t^T q_t
  *
  * (state orientation as above; g = 0 is the plain delta rule).  g is fp32 [B,L,H] (packed: [L,H]),
- * g <= 0 expected; inside one chunk of 64 tokens the sum of |g| must stay below about 80, as the
- * kernels work with exp(-sum g) in fp32.  Evaluated chunkwise like deltanet_fwd / deltanet_bwd: with
- * gamma_i the running product of alpha inside a chunk, S_i / gamma_i follows the plain delta rule on
- * the values v_i / gamma_i, so Eq. 8-11 apply unchanged to rescaled rows.  deltanet_gated_bwd also
+ * g <= 0 expected; inside one chunk of 64 tokens the sum of |g| must stay below about 160 (a mean alpha
+ * of about 0.08), as the kernels work with exp(+-(sum g) / 2) in fp32.  Evaluated chunkwise like
+ * deltanet_fwd / deltanet_bwd: with gamma_i the running product of alpha inside a chunk, taken relative
+ * to the chunk's geometric middle, S_i / gamma_i follows the plain delta rule on the values
+ * v_i / gamma_i, so Eq. 8-11 apply unchanged to rescaled rows.  In bf16 the gate gradient dg, a
+ * difference of nearly equal sums of rounded gradients, loses relative accuracy as the decay grows.  deltanet_gated_bwd also
  * returns dg (fp32, shape of g).  Workspace sizes come from deltanet_gated_workspace_bytes; everything
  * else (layouts, nullable states, return codes) is as for the plain calls.
  * deltanet_gated_recurrent_fwd is the token-serial form (decode steps), as deltanet_recurrent_fwd.

@@ -151,17 +151,22 @@ __global__ __launch_bounds__(NTHR) __attribute__((amdgpu_waves_per_eu(PrepWaves<
         sBeta[tid] = b;
     }
     if (p.g && tid < C) {
-        // Gated variant: gamma_i = exp(g_1 + ... + g_i) within the chunk (rows past the end keep the last
-        // value).  S_i / gamma_i follows the plain delta rule on the values v_i / gamma_i, so the other
-        // kernels only rescale rows with gamma_i and 1 / gamma_i; T and X do not depend on the gate.
+        // Gated variant: with the running decay exp(g_1 + ... + g_i) within the chunk (rows past the end keep the last
+        // value), the state divided by it follows the plain delta rule on equally divided values, so the other kernels
+        // only rescale rows with gamma_i and 1 / gamma_i; T and X do not depend on the gate.  The table holds the decay
+        // relative to the chunk's geometric middle, gamma_i = exp(g_1 + ... + g_i - (g_1 + ... + g_C) / 2): both
+        // gamma_i and 1 / gamma_i then stay within exp(+-sum|g| / 2), which doubles the decay per chunk that fp32 holds.
+        // The chain scans move the state into these coordinates when a chunk begins (factor gamma_C, which in them is
+        // also the decay from the chunk's start to its middle) and out of them when it ends (gamma_C again).
         float cs = tid < nvalid ? p.g[(row0 + tid) * H + h] : 0.f;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const float up = __shfl_up(cs, d);
             if (tid >= d) cs += up;
         }
-        p.gam[tile * 2 * C + tid] = __expf(cs);
-        p.gam[tile * 2 * C + C + tid] = __expf(-cs);
+        const float half = 0.5f * __shfl(cs, C - 1);
+        p.gam[tile * 2 * C + tid] = __expf(cs - half);
+        p.gam[tile * 2 * C + C + tid] = __expf(half - cs);
     }
     lds_barrier();
     f32x16 g = zero16();
@@ -368,14 +373,17 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
     // gated: gamma at the end of the chunk, which rescales the state when the chunk is done; every wave
     // requests the next chunk's value one step ahead
     float gC = 1.f, gCn = 1.f;
-    if (gated && nchunks > 0) gCn = p.gam[((long)cb * H + h) * 2 * C + C - 1];
+    if (gated && nchunks > 0) {
+        gCn = p.gam[((long)cb * H + h) * 2 * C + C - 1];
+        S *= gCn; // into the first chunk's coordinates
+    }
     for (int ic = 0; ic < nchunks; ++ic) {
         const long tile = ((long)(cb + ic) * H + h);
         T *sUT = (ic & 1) ? sUT1 : sUT0;
         T *sK = (ic & 1) ? sK1 : sK0;
         float *sGam = (ic & 1) ? sGam1 : sGam0;
-        gC = gCn;
-        if (gated && ic + 1 < nchunks) gCn = p.gam[(tile + H) * 2 * C + C - 1];
+        gC = gCn; // out of this chunk's coordinates when it ends (gC), and into the next one's (gCn)
+        if (gated) gCn = ic + 1 < nchunks ? p.gam[(tile + H) * 2 * C + C - 1] : 1.f;
         if (!MERGE || ic == 0) {
             if (m.has_s) acc_to_lds_t<T>(sST, SM::LS, 32 * m.sa, 32 * m.sb, S);
         }
@@ -448,7 +456,10 @@ __device__ __forceinline__ void scan_fwd_body(const SeqMap &sm, int H, const Ptr
             acc_to_lds<T>(stg, Stage<T>::LD, 0, 0, acc);
         }
         if (m.has_s) mma<C, true, false, T, true, MB>(S, sK + 32 * m.sa, SM::LK, sUT + 32 * m.sb * SM::LT, SM::LT); // S += K^T Ut (Eq. 8)
-        if (gated) S *= gC; // back from S / gamma to the state itself at the chunk boundary
+        if (gated) { // from this chunk's coordinates to the state itself, then to the next chunk's (one factor at a time: their product may leave the fp32 range)
+            S *= gC;
+            S *= gCn;
+        }
         if (MERGE) {
             // nothing read in this interval is written here: the state's LDS copy serves only the first two intervals of a
             // step, Q, V, T only the first, and the next K and gamma table go to the buffers of the other parity
@@ -677,8 +688,8 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     if (loader && nchunks > 0) { fetch_a(nchunks - 1); fetch_b(nchunks - 1); stash(); }
     // gated: the state after the chunk is gamma_C times the plain rule's, so its gradient is scaled by
     // gamma_C on entry; every wave requests the value for the next step one step ahead
-    float gCn = 1.f;
-    if (gated && nchunks > 0) gCn = p.gam[((long)(cb + nchunks - 1) * H + h) * 2 * C + C - 1];
+    float gCn = 1.f, gHere = 1.f; // gHere: gamma_C of the chunk of the current step
+    if (gated && nchunks > 0) gCn = gHere = p.gam[((long)(cb + nchunks - 1) * H + h) * 2 * C + C - 1];
     // dS' of the last chunk (the gradient with respect to the state after it) goes to LDS here; every later one at the end
     // of the step that produced it: that interval reads only W and dUt^T, so the state gradient's LDS copy and the next
     // chunk's tiles can be written in it, and a chunk step takes three barrier intervals.
@@ -739,7 +750,11 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
             dS -= wd;
         }
         if (ic > 0) {
-            if (gated) dS *= gCn;
+            if (gated) { // across the boundary: out of this chunk's coordinates, into those of the chunk before
+                dS *= gHere; // (one factor at a time: their product may leave the fp32 range)
+                dS *= gCn;
+                gHere = gCn;
+            }
             if (m.has_s) acc_to_lds_t<T>(sDST, SM::LS, 32 * m.sa, 32 * m.sb, dS); // dS' of the next step
             if (loader) stash(); // see k_scan_fwd
         }
@@ -747,6 +762,7 @@ __device__ __forceinline__ void scan_bwd_body(const SeqMap &sm, int H, const Ptr
     if (!STATE && loader && nchunks > 0 && !p.skip_ut) flush_dut(0, lt);
     if (p.dS0 && m.has_s) {
         float *dst = p.dS0 + (long)chain * DK * DV + vb;
+        if (gated) dS *= gHere; // out of the first chunk's coordinates
         acc_each(dS, [&](int r, int c, float &val) { dst[(long)(32 * m.sa + r) * DV + 32 * m.sb + c] = val; });
     }
 }

@@ -12,7 +12,7 @@ from tests.gpu_util import TOL, check_tensors, dev_inputs, nerr
 pytestmark = pytest.mark.gpu
 
 
-def run_gated(inp, g, bwd=True, label=""):
+def run_gated(inp, g, bwd=True, label="", tol_of=None):
     d = dev_inputs(inp)
     gd = torch.from_numpy(g).cuda()
     o, ST = dn.deltanet_gated_fwd(d["q"], d["k"], d["v"], d["beta"], gd, d["S0"], cu_seqlens=d["cu"])
@@ -25,7 +25,7 @@ def run_gated(inp, g, bwd=True, label=""):
         ref = oracle.gated_bwd(inp.q, inp.k, inp.v, inp.beta, g, inp.d_o, inp.initial_state, inp.dfinal_state, inp.cu_seqlens)
         # binding order: dq, dk, dv, dbeta, dg, dS0 -- same as the oracle's
         named += [(name, a.float().cpu().numpy(), b) for name, a, b in zip(("dq", "dk", "dv", "dbeta", "dg", "dinitial_state"), out, ref)]
-    check_tensors(named, inp.dtype, label=label)
+    check_tensors(named, inp.dtype, label=label, tol_of=tol_of)
 
 
 @pytest.mark.parametrize("dtype,dk,dv", [("f32", 64, 64), ("f32", 32, 64), ("bf16", 128, 128), ("bf16", 64, 128), ("bf16", 256, 256)])
@@ -42,12 +42,21 @@ def test_gated_strong_decay_and_packed(dtype, d):
     run_gated(inp, make_gate(2, inp.beta.shape, lo=0.4, hi=1.0), label="gated packed strong %s" % dtype)
 
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
-def test_gated_decay_near_the_documented_limit(dtype, d):
-    """alpha ~ U(0.3, 0.4): the log-decays of a 64-token chunk sum to about -67, close to the documented bound of 80 beyond
-    which exp(-sum g) leaves the fp32 range.  The oracle has no such bound; the kernels must still match it here."""
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 256)])
+@pytest.mark.parametrize("lo,hi", [(0.3, 0.4), (0.15, 0.25)])
+def test_gated_strong_decay_within_the_documented_bound(dtype, d, lo, hi):
+    """alpha ~ U(0.3, 0.4) and U(0.15, 0.25): the log-decays of a 64-token chunk sum to about -67 and -103.  The kernels hold
+    the running decay relative to the chunk's geometric middle, so exp(+-sum|g| / 2) has to stay inside fp32 (documented
+    bound: sum|g| up to about 160 per chunk); the second case is past what a table relative to the chunk's start could
+    hold.  The oracle has no such bound; the kernels must match it."""
     inp = make_inputs(29, B=2, L=200, H=2, dk=d, dv=d, dtype=dtype, with_initial_state=True, with_dfinal_state=True)
-    run_gated(inp, make_gate(5, inp.beta.shape, lo=0.3, hi=0.4), label="gated near the limit %s" % dtype)
+    # The gate gradient is a difference of row dot products q_i . dq_i - v_i . dv_i formed from gradients already rounded to
+    # bf16; the stronger the decay, the smaller the difference against its two terms.  At alpha around 0.2 its largest
+    # error is 2.2e-2 of its largest entry in bf16, its RMS error 9e-2 and the median relative error of an entry 1.6e-1 (fp32:
+    # all below 1e-5, so the arithmetic is the oracle's): bounds 3e-2, 2e-1 and 3e-1 here, for dg in bf16 only.
+    tol_of = {"dg": (3e-2, 2e-1, 3e-1)} if (dtype == "bf16" and hi < 0.3) else None
+    run_gated(inp, make_gate(5, inp.beta.shape, lo=lo, hi=hi), tol_of=tol_of,
+              label="gated strong decay %s d=%d alpha in (%.2f, %.2f)" % (dtype, d, lo, hi))
 
 
 def test_zero_gate_equals_the_plain_path_on_the_gpu():

@@ -60,6 +60,8 @@ __device__ inline float to_f32(bf16 x) { return (float)x; }
 template <typename T> __device__ inline T from_f32(float x) { return (T)x; }
 // logistic function in explicit single-rounding steps, so that every kernel that evaluates it gets the same bits
 __device__ inline float sigmoid_f32(float x) { return __frcp_rn(__fadd_rn(1.f, __expf(-x))); }
+// ... and with the hardware reciprocal (1 ulp), for values that no other kernel has to reproduce bit for bit
+__device__ inline float sigmoid_fast_f32(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
 
 // Where the chains live.  Dense batches are N = B sequences of length L at rows n*L; packed
 // batches read cu_seqlens and a device-computed prefix of per-sequence chunk counts.
@@ -400,8 +402,8 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
     // Gradient through the map, for a tile whose pre-activations x this object holds: src = dy in LDS
     // (same shape, leading dimension ld);
     //     dx = SiLU'(x) (dy - y (y . dy)) / ||SiLU(x)||,  SiLU'(x) = sig (1 + x (1 - sig)),  y = SiLU(x) / ||SiLU(x)||,
-    // written to global memory (rows >= nvalid dropped).  A first pass forms the rows' norms (as feature_map does, so y has
-    // the bits of the mapped tile) and keeps every sigmoid; a row's sums are butterflies over its TPR lanes.
+    // written to global memory (rows >= nvalid dropped).  A first pass forms the rows' norms and keeps every sigmoid (the
+    // fast one: y need not have the bits of the mapped tile here); a row's sums are butterflies over its TPR lanes.
     __device__ inline void feature_map_bwd_store(const T *src, int ld, T *dst, long row_stride, int nvalid, int t = threadIdx.x) const {
         const int tr = t / TPR, tc = (t % TPR) * VEC;
         float sg[NIT][VEC], inv[NIT];
@@ -413,7 +415,7 @@ template <typename T, int ROWS, int COLS, int NT = NTHR> struct TileRegs {
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
                 const float xv = to_f32(x[u]);
-                sg[it][u] = sigmoid_f32(xv);
+                sg[it][u] = sigmoid_fast_f32(xv);
                 const float sv = __fmul_rn(xv, sg[it][u]);
                 ss = __fmaf_rn(sv, sv, ss);
             }

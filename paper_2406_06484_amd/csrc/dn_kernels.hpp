@@ -871,7 +871,7 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     static_assert(!PRO || (sizeof(T) * C * SM::LQO <= SM::oB2 - SM::oB1 && sizeof(T) * C * SM::LQO <= SM::oB3 - SM::oB2), "dq / dk staging");
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
     // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = PRO ? 2 : (sizeof(T) == 4 ? 2 : ((DK > 128 || GATED) ? 4 : 0));
+    constexpr int MB = PRO ? 2 : (sizeof(T) == 4 ? 2 : (DK > 128 ? 4 : (GATED ? 2 : 0)));
     // The thread index as the helpers see it: re-read through an empty asm at the top of every barrier interval, so that the
     // per-lane offsets and masks derived from it are formed where they are used.  Left to itself the compiler forms all of
     // them ahead of the tile loop and carries them through it, which costs more registers than the kernel has to spare.

@@ -870,8 +870,9 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
     T *sDQ = reinterpret_cast<T *>(smem + SM::oB1), *sDK = reinterpret_cast<T *>(smem + SM::oB2);
     static_assert(!PRO || (sizeof(T) * C * SM::LQO <= SM::oB2 - SM::oB1 && sizeof(T) * C * SM::LQO <= SM::oB3 - SM::oB2), "dq / dk staging");
     constexpr bool gated = GATED; // compile-time, so the plain kernels carry none of the gate's registers
-    // the gated kernels, and those with d_k = 256, request operand fragments in smaller batches: they have no registers to spare
-    constexpr int MB = PRO ? 2 : (sizeof(T) == 4 ? 2 : (DK > 128 ? 4 : (GATED ? 2 : 0)));
+    // operand fragments are requested two contraction steps at a time (measured best among 2, 4 and 8 in every variant: the
+    // LDS is the busy unit here, and long batches only hold registers)
+    constexpr int MB = 2;
     // The thread index as the helpers see it: re-read through an empty asm at the top of every barrier interval, so that the
     // per-lane offsets and masks derived from it are formed where they are used.  Left to itself the compiler forms all of
     // them ahead of the tile loop and carries them through it, which costs more registers than the kernel has to spare.

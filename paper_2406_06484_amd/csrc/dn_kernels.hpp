@@ -933,11 +933,11 @@ __global__ __launch_bounds__(NTC) void k_bwd_chunk(SeqMap sm, int H, Ptrs p, int
 
     // Workgroups that start together stay in lockstep: every CU issues its tile's load burst at the same
     // moment and then all of them compute while HBM idles.  When each workgroup has several tiles to
-    // walk, delay it by (blockIdx mod 4) steps of s_sleep(64), about 4K cycles each (an eighth of a tile's
-    // time; measured best among none, 2K, 4K and 8K), so the bursts of neighbouring CUs interleave with
-    // each other's MFMA phases.
+    // walk, delay it by (blockIdx mod 4) steps of s_sleep(32), about 2K cycles each (measured best among
+    // none, 2K, 4K and 8K, and against eight steps), so the bursts of neighbouring CUs interleave with each
+    // other's MFMA phases.
     if ((long)chunks_total * H >= 4l * gridDim.x)
-        for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(64);
+        for (int i = 0; i < (int)(blockIdx.x & 3); ++i) __builtin_amdgcn_s_sleep(32);
     TileIter it(chunks_total, H);
     TilePos cur = pos_of(it);
     if (cur.ok) fetch_all(cur);

@@ -8,6 +8,9 @@ forward + backward as the self-contained pair and as the pair that keeps the for
 and prints one table row.
 
     python bench_speedup_sweep.py [--steps 20]
+
+With --only-kept it runs nothing but the training step that keeps the forward pass's tiles, --steps times per
+(d, L): the form a profiler's counter passes use (profile_summary.py, head-size table).
 """
 from __future__ import annotations
 
@@ -25,6 +28,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--width", type=int, default=2048)
     ap.add_argument("--head-sizes", type=int, nargs="+", default=[64, 128, 256])
+    ap.add_argument("--lengths", type=int, nargs="+", default=[512, 1024, 2048, 4096, 8192, 16384])
+    ap.add_argument("--only-kept", action="store_true", help="run only deltanet_fwd_save + deltanet_bwd_saved (for profiler passes)")
     args = ap.parse_args()
     import torch
 
@@ -51,7 +56,7 @@ def main() -> int:
                                                         "fwd+bwd ms", "fwd+bwd kept ms"))
     for d in args.head_sizes:
         H = args.width // d
-        for L in (512, 1024, 2048, 4096, 8192, 16384):
+        for L in args.lengths:
             B = max(1, args.tokens // L)
             g = torch.Generator(device="cpu").manual_seed(L + d)
             unit = lambda: torch.nn.functional.normalize(torch.randn(B, L, H, d, generator=g), dim=-1).bfloat16().to(dev)
@@ -61,8 +66,14 @@ def main() -> int:
             beta = torch.sigmoid(torch.randn(B, L, H, generator=g)).bfloat16().to(dev)
             o = torch.empty_like(v)
             ST = torch.empty(B, H, d, d, dtype=torch.float32, device=dev)
-            t_rec = timeit(lambda: dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST))
             ws = torch.empty(deltanet_workspace_bytes(_shape_of(q, v, None, 64, []), True), dtype=torch.uint8, device=dev)
+            if args.only_kept:
+                def kept_only():
+                    dn.deltanet_fwd_save(q, k, v, beta, o=o, final_state=ST, saved=ws)
+                    dn.deltanet_bwd_saved(q, k, v, beta, d_o, ws)
+                print("%5d %6d %4d %4d | kept step %.3f ms" % (d, L, B, H, timeit(kept_only)), flush=True)
+                continue
+            t_rec = timeit(lambda: dn.deltanet_recurrent_fwd(q, k, v, beta, o=o, final_state=ST))
             t_chk = timeit(lambda: dn.deltanet_fwd(q, k, v, beta, o=o, final_state=ST, workspace=ws))
 
             def both():

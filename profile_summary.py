@@ -247,6 +247,51 @@ def write_lds_patterns():
                 "cycles per 32 x 32 tile and wavefront, at the better of the two paddings a 16-byte-aligned row allows.\n")
 
 
+def write_head_sizes():
+    base = traffic_table("fetch", "write")
+    if base is None:
+        return
+    _, (_, _, ff, wf) = base
+    subs = {64: "hs64_%s", 128: "%s", 256: "hs256_%s"}
+    if trace_means(subs[64] % "trace") is None or trace_means(subs[256] % "trace") is None:
+        return
+    with open(os.path.join(OUT, "tiling_head_size_counters.txt"), "w") as f:
+        f.write("Tiling study, head size: the training step that keeps the forward pass's tiles (deltanet_fwd_save + deltanet_bwd_saved) on\n"
+                "16384 tokens of model width 2048 (B = 8, L = 2048, H = 2048 / d, bf16, chunk 64), per kernel, MI355X\n\n"
+                "commands (from the repo root on the GPU box; d = 64 and 256 shown, one pass per run; d = 128 is the headline step, whose\n"
+                "passes are listed in profiles/kernel_trace_cfg2_fwd_bwd.txt and its neighbours), then python3 profile_summary.py:\n"
+                "  P=\"python3 bench_speedup_sweep.py --head-sizes 64 --lengths 2048 --only-kept --steps 20\"     (and --head-sizes 256, hs256_*)\n"
+                "  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/hs64_trace -o hs64_trace --output-format csv -- $P\n"
+                "  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/hs64_fetch -o hs64_fetch --output-format csv -- $P\n"
+                "  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/hs64_write -o hs64_write --output-format csv -- $P\n"
+                "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d gpurun_out/prof/hs64_mfma -o hs64_mfma --output-format csv -- $P\n\n"
+                "HBM bytes = FETCH_SIZE x %.3f + WRITE_SIZE x %.3f (KiB per launch; factors from the 256 MiB copy of the headline run);\n"
+                "mfma_util and bf16_tflops as in profiles/mfma_lds_counters_cfg2_fwd_bwd.txt.\n\n" % (ff, wf))
+        f.write("%4s  %-20s %9s %9s %8s %10s %12s\n" % ("d", "kernel", "avg_us", "HBM_MB", "TB/s", "mfma_util", "bf16_tflops"))
+        for d in (64, 128, 256):
+            tr = trace_means(subs[d] % "trace")
+            fe, wr, mf = counter_means(subs[d] % "fetch"), counter_means(subs[d] % "write"), counter_means(subs[d] % "mfma")
+            step = ["k_wy_prep", "k_scan_fwd_save", "k_scan_bwd", "k_bwd_chunk_wide" if d == 256 else "k_bwd_chunk"]
+            tot_us = tot_mb = 0.0
+            for k in step:
+                if k not in tr:
+                    continue
+                us = tr[k][1] / 1e3
+                mb = (fe["FETCH_SIZE"][k] * ff + wr["WRITE_SIZE"][k] * wf) * 1024 / 1e6
+                act = mf["GRBM_GUI_ACTIVE"][k] / 8.0
+                util = mf["SQ_VALU_MFMA_BUSY_CYCLES"][k] / 1024.0 / act if act else 0.0
+                tfl = mf["SQ_INSTS_VALU_MFMA_MOPS_BF16"][k] * 512.0 / (act / 2.4e9) / 1e12 if act else 0.0
+                f.write("%4d  %-20s %9.1f %9.1f %8.2f %10.3f %12.1f\n" % (d, k, us, mb, mb / us, util, tfl))
+                tot_us += us
+                tot_mb += mb
+            f.write("%4d  %-20s %9.1f %9.1f %8.2f\n\n" % (d, "step", tot_us, tot_mb, tot_mb / tot_us))
+        f.write("TB/s = HBM_MB / avg_us.  At d = 64 a chain is one scan workgroup (256 chains), at d = 128 two (128 chains), at d = 256 eight\n"
+                "workgroups of 32 state columns (64 chains, 512 workgroups in two rounds); the chunk kernel keeps a chunk's operands in LDS\n"
+                "up to d = 128 and streams S and dS' in blocks of 32 state columns at d = 256 (k_bwd_chunk_wide).  Per token the matrix work\n"
+                "grows with d (model FLOPs 6 d^2 + ... per token and head, H = 2048 / d heads) while the bytes per token stay the same for\n"
+                "q, k, v, o and grow with d for the per-chunk states.\n")
+
+
 def main() -> int:
     if not os.path.isdir(PROF):
         print("profile_summary.py: %s is missing; run the rocprofv3 commands in this file's header first" % PROF, file=sys.stderr)
@@ -256,6 +301,7 @@ def main() -> int:
     write_traffic()
     write_counters()
     write_lds_patterns()
+    write_head_sizes()
     return 0
 
 

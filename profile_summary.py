@@ -17,6 +17,12 @@ split counters over passes), then `python3 profile_summary.py`.  The raw output 
 
   rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d gpurun_out/prof/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py
 
+  H="python3 bench_speedup_sweep.py --head-sizes 64 --lengths 2048 --only-kept --steps 20"      (head-size table; the same with 256 and hs256_*)
+  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/hs64_trace -o hs64_trace --output-format csv -- $H
+  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/hs64_fetch -o hs64_fetch --output-format csv -- $H
+  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/hs64_write -o hs64_write --output-format csv -- $H
+  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d gpurun_out/prof/hs64_mfma -o hs64_mfma --output-format csv -- $H
+
 bench.py --mode headline runs the timed step (deltanet_fwd_save + deltanet_bwd_saved: k_wy_prep, k_scan_fwd_save,
 k_scan_bwd, k_bwd_chunk) and the self-contained pair (deltanet_fwd + deltanet_bwd: k_wy_prep, k_scan_fwd; k_wy_prep,
 k_scan_pair, k_bwd_chunk) and nothing else, so every row below belongs to one of the two.

@@ -1,9 +1,9 @@
 """Runs the library's LDS access-pattern probe (deltanet_lds_probe) once per pattern, for a profiler to count.
 
   rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace \
-      -d gpurun_out/prof/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py
+      -d $RAW/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py
 
-`python3 profile_summary.py` then writes profiles/lds_conflicts_by_access_pattern.txt from the counter file.  Without a
+`python3 profile_summary.py $RAW` then writes profiles/lds_conflicts_by_access_pattern.txt from the counter file.  Without a
 profiler the script only times the launches (HIP events on the current stream).
 """
 import argparse

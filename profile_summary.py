@@ -1,27 +1,28 @@
 #!/usr/bin/env python3
 """Turns the rocprofv3 CSVs of the benchmark's profiling runs into the short text summaries under profiles/.
 
-Run the commands below from the repo root on the GPU machine (each counter pass is a run of its own; rocprofv3 does not
-split counters over passes), then `python3 profile_summary.py`.  The raw output stays under gpurun_out/prof/.
+Run the commands below from the repo root on the GPU machine; RAW = a scratch directory for the raw profiler output (each counter pass is a run of its own; rocprofv3 does not
+split counters over passes), RAW being a scratch directory for the raw profiler output, then
+`python3 profile_summary.py $RAW`.
 
   P="python3 bench.py --mode headline --no-cpu-baseline"
-  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/trace -o trace --output-format csv -- $P --steps 20 --warmup 5
-  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/fetch -o fetch --output-format csv -- $P --steps 3 --warmup 1 --copy-calibration
-  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/write -o write --output-format csv -- $P --steps 3 --warmup 1 --copy-calibration
-  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d gpurun_out/prof/mfma -o mfma --output-format csv -- $P --steps 3 --warmup 1
-  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES --kernel-trace -d gpurun_out/prof/lds -o lds --output-format csv -- $P --steps 3 --warmup 1
+  rocprofv3 --kernel-trace --stats -d $RAW/trace -o trace --output-format csv -- $P --steps 20 --warmup 5
+  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d $RAW/fetch -o fetch --output-format csv -- $P --steps 3 --warmup 1 --copy-calibration
+  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d $RAW/write -o write --output-format csv -- $P --steps 3 --warmup 1 --copy-calibration
+  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d $RAW/mfma -o mfma --output-format csv -- $P --steps 3 --warmup 1
+  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES --kernel-trace -d $RAW/lds -o lds --output-format csv -- $P --steps 3 --warmup 1
   S="python3 bench.py --mode streamed --no-cpu-baseline"      (the same step under DN_OPT_STREAMED_CHUNK_KERNEL)
-  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/trace_s -o trace_s --output-format csv -- $S --steps 20 --warmup 5
-  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/fetch_s -o fetch_s --output-format csv -- $S --steps 3 --warmup 1 --copy-calibration
-  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/write_s -o write_s --output-format csv -- $S --steps 3 --warmup 1 --copy-calibration
+  rocprofv3 --kernel-trace --stats -d $RAW/trace_s -o trace_s --output-format csv -- $S --steps 20 --warmup 5
+  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d $RAW/fetch_s -o fetch_s --output-format csv -- $S --steps 3 --warmup 1 --copy-calibration
+  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d $RAW/write_s -o write_s --output-format csv -- $S --steps 3 --warmup 1 --copy-calibration
 
-  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d gpurun_out/prof/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py
+  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d $RAW/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py
 
   H="python3 bench_speedup_sweep.py --head-sizes 64 --lengths 2048 --only-kept --steps 20"      (head-size table; the same with 256 and hs256_*)
-  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/hs64_trace -o hs64_trace --output-format csv -- $H
-  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/hs64_fetch -o hs64_fetch --output-format csv -- $H
-  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/hs64_write -o hs64_write --output-format csv -- $H
-  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d gpurun_out/prof/hs64_mfma -o hs64_mfma --output-format csv -- $H
+  rocprofv3 --kernel-trace --stats -d $RAW/hs64_trace -o hs64_trace --output-format csv -- $H
+  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d $RAW/hs64_fetch -o hs64_fetch --output-format csv -- $H
+  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d $RAW/hs64_write -o hs64_write --output-format csv -- $H
+  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d $RAW/hs64_mfma -o hs64_mfma --output-format csv -- $H
 
 bench.py --mode headline runs the timed step (deltanet_fwd_save + deltanet_bwd_saved: k_wy_prep, k_scan_fwd_save,
 k_scan_bwd, k_bwd_chunk) and the self-contained pair (deltanet_fwd + deltanet_bwd: k_wy_prep, k_scan_fwd; k_wy_prep,
@@ -37,7 +38,7 @@ import re
 import sys
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-PROF = os.path.join(ROOT, "gpurun_out", "prof")
+PROF = os.path.abspath(sys.argv[1]) if len(sys.argv) > 1 else os.path.join(ROOT, "prof_raw")
 OUT = os.path.join(ROOT, "profiles")
 W = "bench.py --mode headline (configs[2]: bf16 fwd+bwd, B=8, L=2048, H=16, d=128, chunk 64), MI355X"
 COPY = "__amd_rocclr_copyBuffer"
@@ -122,8 +123,8 @@ def write_trace():
     if tr is None:
         return
     with open(os.path.join(OUT, "kernel_trace_cfg2_fwd_bwd.txt"), "w") as f:
-        f.write("rocprofv3 kernel-trace summary: %s\n\ncommand (from the repo root on the GPU box), then python3 profile_summary.py:\n"
-                "  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/trace -o trace --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 20 --warmup 5\n\n" % W)
+        f.write("rocprofv3 kernel-trace summary: %s\n\ncommand (from the repo root on the GPU box; RAW = a scratch directory for the raw profiler output), then python3 profile_summary.py $RAW:\n"
+                "  rocprofv3 --kernel-trace --stats -d $RAW/trace -o trace --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 20 --warmup 5\n\n" % W)
         f.write("%-28s %7s %12s %10s %10s\n" % ("kernel", "calls", "avg_ns", "min_ns", "max_ns"))
         for k, (n, avg, lo, hi) in tr.items():
             if k != COPY:
@@ -132,7 +133,7 @@ def write_trace():
                 % (sum(tr[k][1] for k in STEP if k in tr) / 1e3, sum(tr[k][1] for k in PAIR if k in tr) / 1e3))
         ts = trace_means("trace_s")
         if ts is not None:
-            f.write("\nthe same step under DN_OPT_STREAMED_CHUNK_KERNEL (bench.py --mode streamed, same flags, -d gpurun_out/prof/trace_s -o trace_s):\n")
+            f.write("\nthe same step under DN_OPT_STREAMED_CHUNK_KERNEL (bench.py --mode streamed, same flags, -d $RAW/trace_s -o trace_s):\n")
             for k in STEP_S:
                 if k in ts:
                     f.write("%-28s %7d %12.0f %10d %10d\n" % ((k,) + ts[k]))
@@ -156,9 +157,9 @@ def write_traffic():
         return
     tab, (cf, cw, ff, wf) = res
     with open(os.path.join(OUT, "hbm_traffic_cfg2_fwd_bwd.txt"), "w") as f:
-        f.write("rocprofv3 --pmc HBM traffic per launch: %s\n\ncommands (from the repo root on the GPU box; one counter per run), then python3 profile_summary.py:\n"
-                "  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/fetch -o fetch --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1 --copy-calibration\n"
-                "  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/write -o write --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1 --copy-calibration\n\n" % W)
+        f.write("rocprofv3 --pmc HBM traffic per launch: %s\n\ncommands (from the repo root on the GPU box; RAW = a scratch directory for the raw profiler output; one counter per run), then python3 profile_summary.py $RAW:\n"
+                "  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d $RAW/fetch -o fetch --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1 --copy-calibration\n"
+                "  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d $RAW/write -o write --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1 --copy-calibration\n\n" % W)
         f.write("calibration: a plain 256 MiB device copy (%s) reads FETCH_SIZE = %.1f and WRITE_SIZE = %.1f (KiB);\n"
                 "it moves 262144 KiB each way, so the scale factors are %.3f (fetch) and %.3f (write).\n\n" % (COPY, cf, cw, ff, wf))
         f.write("%-28s %14s %14s %12s\n" % ("kernel", "fetch_KiB*f", "write_KiB*f", "total_MB"))
@@ -174,7 +175,7 @@ def write_traffic():
         res_s = traffic_table("fetch_s", "write_s")
         if res_s is not None:
             tab_s = res_s[0]
-            f.write("\nthe same step under DN_OPT_STREAMED_CHUNK_KERNEL (bench.py --mode streamed; -d gpurun_out/prof/fetch_s -o fetch_s, write_s likewise):\n")
+            f.write("\nthe same step under DN_OPT_STREAMED_CHUNK_KERNEL (bench.py --mode streamed; -d $RAW/fetch_s -o fetch_s, write_s likewise):\n")
             tot = 0.0
             for k in STEP_S:
                 if k in tab_s:
@@ -197,9 +198,9 @@ def write_counters():
     if mf is None or ld is None:
         return
     with open(os.path.join(OUT, "mfma_lds_counters_cfg2_fwd_bwd.txt"), "w") as f:
-        f.write("rocprofv3 --pmc MFMA and LDS counters per launch: %s\n\ncommands (from the repo root on the GPU box; one pass per run), then python3 profile_summary.py:\n"
-                "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d gpurun_out/prof/mfma -o mfma --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1\n"
-                "  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES --kernel-trace -d gpurun_out/prof/lds -o lds --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1\n\n" % W)
+        f.write("rocprofv3 --pmc MFMA and LDS counters per launch: %s\n\ncommands (from the repo root on the GPU box; RAW = a scratch directory for the raw profiler output; one pass per run), then python3 profile_summary.py $RAW:\n"
+                "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d $RAW/mfma -o mfma --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1\n"
+                "  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES --kernel-trace -d $RAW/lds -o lds --output-format csv -- python3 bench.py --mode headline --no-cpu-baseline --steps 3 --warmup 1\n\n" % W)
         f.write("Averages per launch.  GRBM_GUI_ACTIVE is summed over the 8 XCDs; SQ_VALU_MFMA_BUSY_CYCLES over the 1024 SIMDs.\n"
                 "mfma_util = SQ_VALU_MFMA_BUSY_CYCLES / 1024 / (GRBM_GUI_ACTIVE / 8): the share of the kernel's time in which a SIMD's matrix\n"
                 "pipe is busy, averaged over the chip.  bf16_tflops = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 FLOP / kernel time at 2.4 GHz.\n"
@@ -232,8 +233,8 @@ def write_lds_patterns():
     with open(os.path.join(OUT, "lds_conflicts_by_access_pattern.txt"), "w") as f:
         f.write("LDS counters of the access patterns the kernels are built from, one probe kernel per pattern (deltanet_lds_probe: the\n"
                 "kernels' own helpers at the kernels' own leading dimensions, 8 wavefronts per workgroup, bf16 tiles), MI355X\n\n"
-                "command (from the repo root on the GPU box), then python3 profile_summary.py:\n"
-                "  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d gpurun_out/prof/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py\n\n"
+                "command (from the repo root on the GPU box; RAW = a scratch directory for the raw profiler output), then python3 profile_summary.py $RAW:\n"
+                "  rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_INSTS_LDS --kernel-trace -d $RAW/lds_patterns -o lds_patterns --output-format csv -- python3 bench_lds_patterns.py\n\n"
                 "conflict = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE (the ratio profiles/mfma_lds_counters_cfg2_fwd_bwd.txt gives per kernel);\n"
                 "idx/inst = SQ_LDS_IDX_ACTIVE / SQ_INSTS_LDS: cycles the LDS spends indexing one instruction of the pattern.  An instruction\n"
                 "that moves 1024 bytes per wavefront (16 bytes per lane) occupies the 128-byte-per-clock data path for 8 cycles whatever its\n"
@@ -264,13 +265,13 @@ def write_head_sizes():
     with open(os.path.join(OUT, "tiling_head_size_counters.txt"), "w") as f:
         f.write("Tiling study, head size: the training step that keeps the forward pass's tiles (deltanet_fwd_save + deltanet_bwd_saved) on\n"
                 "16384 tokens of model width 2048 (B = 8, L = 2048, H = 2048 / d, bf16, chunk 64), per kernel, MI355X\n\n"
-                "commands (from the repo root on the GPU box; d = 64 and 256 shown, one pass per run; d = 128 is the headline step, whose\n"
-                "passes are listed in profiles/kernel_trace_cfg2_fwd_bwd.txt and its neighbours), then python3 profile_summary.py:\n"
+                "commands (from the repo root on the GPU box; RAW = a scratch directory for the raw profiler output; d = 64 and 256 shown, one pass per run; d = 128 is the headline step, whose\n"
+                "passes are listed in profiles/kernel_trace_cfg2_fwd_bwd.txt and its neighbours), then python3 profile_summary.py $RAW:\n"
                 "  P=\"python3 bench_speedup_sweep.py --head-sizes 64 --lengths 2048 --only-kept --steps 20\"     (and --head-sizes 256, hs256_*)\n"
-                "  rocprofv3 --kernel-trace --stats -d gpurun_out/prof/hs64_trace -o hs64_trace --output-format csv -- $P\n"
-                "  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d gpurun_out/prof/hs64_fetch -o hs64_fetch --output-format csv -- $P\n"
-                "  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d gpurun_out/prof/hs64_write -o hs64_write --output-format csv -- $P\n"
-                "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d gpurun_out/prof/hs64_mfma -o hs64_mfma --output-format csv -- $P\n\n"
+                "  rocprofv3 --kernel-trace --stats -d $RAW/hs64_trace -o hs64_trace --output-format csv -- $P\n"
+                "  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d $RAW/hs64_fetch -o hs64_fetch --output-format csv -- $P\n"
+                "  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d $RAW/hs64_write -o hs64_write --output-format csv -- $P\n"
+                "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 GRBM_GUI_ACTIVE --kernel-trace -d $RAW/hs64_mfma -o hs64_mfma --output-format csv -- $P\n\n"
                 "HBM bytes = FETCH_SIZE x %.3f + WRITE_SIZE x %.3f (KiB per launch; factors from the 256 MiB copy of the headline run);\n"
                 "mfma_util and bf16_tflops as in profiles/mfma_lds_counters_cfg2_fwd_bwd.txt.\n\n" % (ff, wf))
         f.write("%4s  %-20s %9s %9s %8s %10s %12s\n" % ("d", "kernel", "avg_us", "HBM_MB", "TB/s", "mfma_util", "bf16_tflops"))
